@@ -1,0 +1,149 @@
+"""Pins for the oracle's integer GEMM (O1) and the bit-serial identities (O1b).
+
+Each pin is something other than the oracle itself: a library routine (numpy
+int64 matmul), the plane identity of Sec. 3.1 through a separately written
+popcount implementation of Algorithms 1 and 2, brute force over every value
+tuple on tiny shapes, closed forms, the bipolar XOR identity, padding neutrality.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+
+U, TC, BP = oracle.UNSIGNED, oracle.TWOS_COMPLEMENT, oracle.BIPOLAR
+
+
+def draw(rng, shape, bits, fmt):
+    if fmt == BP:
+        return (2 * rng.integers(0, 2, size=shape) - 1).astype(np.int8)
+    if fmt == TC:
+        return rng.integers(-(1 << (bits - 1)), 1 << (bits - 1), size=shape).astype(np.int8)
+    return rng.integers(0, 1 << bits, size=shape).astype(np.int8)
+
+
+def value_range(bits, fmt):
+    if fmt == BP:
+        return [-1, 1]
+    if fmt == TC:
+        return list(range(-(1 << (bits - 1)), 1 << (bits - 1)))
+    return list(range(1 << bits))
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (17, 63, 9), (64, 256, 64), (33, 1000, 130)])
+def test_gemm_matches_numpy_int64_matmul(shape):
+    M, K, N = shape
+    rng = np.random.default_rng(7)
+    W = rng.integers(-8, 8, size=(M, K)).astype(np.int8)
+    A = rng.integers(0, 16, size=(K, N)).astype(np.int8)
+    C = oracle.gemm(W, A)
+    ref = W.astype(np.int64) @ A.astype(np.int64)
+    assert C.dtype == np.int32 and np.array_equal(C.astype(np.int64), ref)
+    # transposed-operand mistake would fail here because M != N != K
+    for (m, n) in [(0, 0), (M - 1, N - 1), (M // 2, N // 3)]:
+        assert oracle.dot(W, A, m, n) == ref[m, n]
+
+
+@pytest.mark.parametrize("K", [1, 63, 64, 65, 127, 256])
+@pytest.mark.parametrize("wfmt", [U, TC])
+@pytest.mark.parametrize("afmt", [U, TC])
+def test_plane_identity_all_precisions(K, wfmt, afmt):
+    """W.A = sum_i sum_j sgn 2^(i+j) W[i].A[j] (Sec. 3.1, Alg. 2) for all w, a <= 4."""
+    rng = np.random.default_rng(K * 10 + wfmt * 3 + afmt)
+    M, N = 5, 6
+    for w in range(1, 5):
+        for a in range(1, 5):
+            W = draw(rng, (M, K), w, wfmt)
+            A = draw(rng, (K, N), a, afmt)
+            Wp = oracle.pack(W, w, wfmt)
+            Ap = oracle.pack(A.T, a, afmt)
+            bs = oracle.bitserial_gemm(Wp, wfmt == TC, Ap, afmt == TC)
+            assert np.array_equal(bs, oracle.gemm(W, A).astype(np.int64)), (w, a)
+
+
+def test_alg2_with_w1_signed_gives_zero_minus_one():
+    """With w = 1 the sign rule of Alg. 2 makes the single plane the sign plane:
+    values are {0, -1}, not the +-1 of a bipolar matrix."""
+    rng = np.random.default_rng(3)
+    W = draw(rng, (4, 70), 1, TC)
+    assert set(np.unique(W)) <= {-1, 0}
+    A = draw(rng, (70, 3), 2, U)
+    bs = oracle.bitserial_gemm(oracle.pack(W, 1, TC), True, oracle.pack(A.T, 2, U), False)
+    assert np.array_equal(bs, W.astype(np.int64) @ A.astype(np.int64))
+
+
+@pytest.mark.parametrize("wbits,wfmt,abits,afmt", [(1, BP, 2, U), (2, TC, 2, U), (1, BP, 1, BP), (2, U, 2, TC)])
+def test_brute_force_every_value_tuple(wbits, wfmt, abits, afmt):
+    """M = N = 1, K <= 3: every possible pair of value vectors, product written out in Python."""
+    wv, av = value_range(wbits, wfmt), value_range(abits, afmt)
+    for K in (1, 2, 3):
+        for ws in itertools.product(wv, repeat=K):
+            for as_ in itertools.product(av, repeat=K):
+                want = sum(x * y for x, y in zip(ws, as_))
+                W = np.array([ws], dtype=np.int8)
+                A = np.array(as_, dtype=np.int8).reshape(K, 1)
+                assert int(oracle.gemm(W, A)[0, 0]) == want
+                assert oracle.dot(W, A, 0, 0) == want
+
+
+@pytest.mark.parametrize("K", [1, 64, 100, 2400])
+def test_closed_forms(K):
+    M, N = 4, 3
+    ones = np.ones((M, K), dtype=np.int8)
+    threes = np.full((K, N), 3, dtype=np.int8)
+    assert (oracle.gemm(ones, threes) == 3 * K).all()
+    assert (oracle.gemm(-ones, threes) == -3 * K).all()
+    for w in range(1, 5):
+        for a in range(1, 5):
+            Wm = np.full((M, K), -(1 << (w - 1)), dtype=np.int8)
+            Am = np.full((K, N), (1 << a) - 1, dtype=np.int8)
+            assert (oracle.gemm(Wm, Am) == -K * (1 << (w - 1)) * ((1 << a) - 1)).all()
+    rng = np.random.default_rng(K)
+    A = rng.integers(0, 16, size=(K, N)).astype(np.int8)
+    sel = rng.integers(0, K, size=M)
+    onehot = np.zeros((M, K), dtype=np.int8)
+    onehot[np.arange(M), sel] = 1
+    assert np.array_equal(oracle.gemm(onehot, A), A[sel].astype(np.int32))
+    assert (oracle.gemm(draw(rng, (M, K), 4, TC), np.zeros((K, N), dtype=np.int8)) == 0).all()
+
+
+@pytest.mark.parametrize("K", [1, 5, 64, 77, 300])
+def test_bipolar_identities(K):
+    """+-1 x unsigned: sum_j 2^j (2 popc(B & A[j]) - popc(A[j]));  +-1 x +-1: K - 2 popc(XOR)."""
+    rng = np.random.default_rng(K)
+    M, N = 7, 5
+    W = draw(rng, (M, K), 1, BP)
+    Bp = oracle.pack(W, 1, BP)
+    for a in (1, 2, 3, 4):
+        A = draw(rng, (K, N), a, U)
+        C = oracle.gemm(W, A).astype(np.int64)
+        assert np.array_equal(oracle.bipolar_weight_gemm(Bp, oracle.pack(A.T, a, U)), C)
+    A = draw(rng, (K, N), 1, BP)
+    assert np.array_equal(oracle.bipolar_xor_gemm(Bp, oracle.pack(A.T, 1, BP), K),
+                          oracle.gemm(W, A).astype(np.int64))
+
+
+@pytest.mark.parametrize("K", [1, 63, 65, 200])
+def test_zero_padding_is_neutral(K):
+    rng = np.random.default_rng(K)
+    W = draw(rng, (6, K), 3, TC)
+    A = draw(rng, (K, 4), 2, U)
+    Kp = 64 * ((K + 63) // 64) + 64
+    Wz = np.zeros((6, Kp), dtype=np.int8); Wz[:, :K] = W
+    Az = np.zeros((Kp, 4), dtype=np.int8); Az[:K] = A
+    assert np.array_equal(oracle.gemm(W, A), oracle.gemm(Wz, Az))
+    # and in the packed domain: planes of the padded matrix equal the planes of the original
+    Wp, Wzp = oracle.pack(W, 3, TC), oracle.pack(Wz, 3, TC)
+    s = Wp.shape[2]
+    assert np.array_equal(Wzp[:, :, :s], Wp) and not Wzp[:, :, s:].any()
+
+
+def test_full_size_tiny_config_against_numpy():
+    from paper_1709_04060_amd import workloads
+    d = workloads.cfg1_tiny()
+    C = oracle.gemm(d["W"], d["A"])
+    assert C.shape == (64, 64)
+    assert np.array_equal(C, d["W"].astype(np.int64) @ d["A"].astype(np.int64))
+    bs = oracle.bipolar_weight_gemm(oracle.pack(d["W"], 1, BP), oracle.pack(d["A"].T, 2, U))
+    assert np.array_equal(bs, C)
