@@ -1,0 +1,147 @@
+/*
+ * bsgemm -- bit-serial few-bit integer matrix multiply for AMD MI355X (gfx950).
+ *
+ * C ABI of the library.  The operations are those of "Streamlined Deployment for
+ * Quantized Neural Networks" (Umuroglu & Jahre): bit-plane packing (Sec. 3.1),
+ * the bit-serial GEMM built from AND-popcount binary GEMMs (Alg. 1 and Alg. 2),
+ * successive thresholding as the integer activation (Sec. 2.1.1, 2.1.3) and
+ * channel-interleaved lowering of convolutions on packed data (Sec. 3.2).
+ *
+ * Conventions that hold for every call
+ *  - All data pointers are DEVICE pointers.  The caller owns every buffer; the
+ *    library never allocates, frees or keeps device memory and has no global
+ *    state.
+ *  - `stream` is a hipStream_t (NULL = the default stream).  Calls only enqueue
+ *    work on that stream and return; results are valid once the stream has
+ *    reached that point.
+ *  - Every call returns a bs_status and never throws or aborts.  Arguments are
+ *    checked on the host before anything is launched; on any error nothing has
+ *    been enqueued.
+ *  - M = weight rows (output channels), K = depth, N = columns (batch x pixels).
+ *
+ * Packed format (it crosses this boundary, so it is part of the ABI)
+ *  - A matrix X of `rows` x `depth` b-bit values is stored as b bit planes,
+ *    uint64_t planes[b][rows][S] with S = bs_words_per_row(depth).
+ *  - Bit `t` of word `d` of row `r` of plane `p` is bit p of the code of
+ *    X[r][64 d + t] (least significant bit first).  Bits at depth indices >= depth
+ *    are ZERO in every plane; consumers rely on it.
+ *  - Codes: BS_UNSIGNED v in [0, 2^b): code = v.  BS_TWOS_COMPLEMENT v in
+ *    [-2^(b-1), 2^(b-1)): code = v mod 2^b (the top plane carries weight
+ *    -2^(b-1), the sign rule of Alg. 2).  BS_BIPOLAR (b must be 1) v in {-1,+1}:
+ *    code = (v + 1) / 2.
+ *  - Both GEMM operands are depth-contiguous: weights as planes of W [M][K],
+ *    activations as planes of A-transposed [N][K] (Alg. 1 indexes A by column).
+ *  - S is even, so every packed row starts on a 16-byte boundary; plane buffers
+ *    must be 16-byte aligned.
+ */
+#ifndef BSGEMM_H
+#define BSGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BS_OK = 0,
+    BS_ERR_INVALID_ARG = -1,   /* null pointer, non-positive size, bits out of range, bad enum */
+    BS_ERR_UNSUPPORTED = -2,   /* valid but not implemented (e.g. bits > 4) */
+    BS_ERR_ALIGNMENT = -3,     /* pointer or leading dimension not aligned as documented */
+    BS_ERR_OVERFLOW_RISK = -4, /* an int32 accumulator or a 32-bit index could overflow */
+    BS_ERR_LAUNCH = -5         /* the HIP runtime refused the launch */
+} bs_status;
+
+typedef enum { BS_UNSIGNED = 0, BS_TWOS_COMPLEMENT = 1, BS_BIPOLAR = 2 } bs_format;
+typedef enum { BS_I8 = 0, BS_I32 = 1 } bs_dtype;
+
+/* Row stride S of a packed plane in 64-bit words: ceil(depth/64) rounded up to an
+ * even count.  Returns 0 for depth <= 0.  Host-only helper. */
+int64_t bs_words_per_row(int64_t depth);
+
+/* Depth of a lowered column (Sec. 3.2): kh * kw * 32 * ceil(C / 32).  Each pixel
+ * contributes its channels padded to a 32-bit word.  Host-only helper. */
+int64_t bs_lowered_depth(int64_t C, int64_t kh, int64_t kw);
+
+/*
+ * Bit-plane packing (Sec. 3.1: plane i holds bit i of every element; Alg. 1:
+ * depth packed into machine words).
+ *   src     device, `dtype` elements holding logical values.
+ *           depth_is_strided == 0: element (r, k) at src[r * ld + k]  (weights, M x K)
+ *           depth_is_strided != 0: element (r, k) at src[k * ld + r]  (activations
+ *           stored K x N; rows = N; the pack transposes)
+ *   ld      leading dimension in elements (>= depth, resp. >= rows)
+ *   bits    1..4; fmt as above (BS_BIPOLAR requires bits == 1)
+ *   planes  device, uint64_t [bits][rows][bs_words_per_row(depth)], 16-byte
+ *           aligned, fully overwritten (padding bits and words written as zero)
+ * Values outside the format's range are reduced to their low `bits` bits
+ * (bipolar: any v > 0 packs as +1).  Errors: INVALID_ARG, UNSUPPORTED,
+ * ALIGNMENT (planes), OVERFLOW_RISK (a plane of more than 2^31 32-bit words), LAUNCH.
+ */
+bs_status bs_pack_planes(const void *src, bs_dtype dtype, int64_t rows, int64_t depth, int64_t ld,
+                         int depth_is_strided, int bits, bs_format fmt, uint64_t *planes, void *stream);
+
+/*
+ * Bit-serial GEMM (Alg. 2 over Alg. 1): C = W . A with
+ *   C[m][n] = sum_i sum_j sgnW(i) sgnA(j) 2^(i+j) sum_d popcount(Wp[i][m][d] & Ap[j][n][d])
+ * sgn = -1 only on the top plane of a BS_TWOS_COMPLEMENT operand; for a
+ * BS_BIPOLAR operand (value 2 bit - 1) the algebraically equal popcount form is
+ * used, so the result is always the integer product of the logical values.
+ *   Wp  device, planes [wbits][M][S], S = bs_words_per_row(K)
+ *   Ap  device, planes [abits][N][S]
+ *   C   device int32 [M][ldc], ldc >= N, OVERWRITTEN (not accumulated into)
+ * Errors: INVALID_ARG; UNSUPPORTED (bits > 4); ALIGNMENT (planes 16 B, C 4 B);
+ * OVERFLOW_RISK if K * 2^(wbits+abits) >= 2^31 (bounds every partial sum) or an operand
+ * exceeds 2^31 32-bit words; LAUNCH.
+ */
+bs_status bs_gemm(const uint64_t *Wp, int wbits, bs_format wfmt,
+                  const uint64_t *Ap, int abits, bs_format afmt,
+                  int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc, void *stream);
+
+/*
+ * Successive thresholding (Sec. 2.1.1; integer thresholds per Sec. 2.1.3):
+ *   Y[m][n] = number of i < T with C[m][n] >= thr[m][i],  T = 2^obits - 1,
+ * written as channel-interleaved bit planes, i.e. packed along m:
+ *   Yp  device uint64_t [obits][N][bs_words_per_row(M)], fully overwritten.
+ * This is exactly the activation-operand format of bs_gemm (depth = M) and the
+ * pixel format of bs_im2col_interleaved.
+ *   C   device int32 [M][ldc];  thr  device int32 [M][T] (non-decreasing per row
+ *   expected; the count is defined and computed for any order).
+ * obits 1..4.  Errors: INVALID_ARG, UNSUPPORTED, ALIGNMENT, LAUNCH.
+ */
+bs_status bs_threshold_activate(const int32_t *C, int64_t ldc, int64_t M, int64_t N,
+                                const int32_t *thr, int obits, uint64_t *Yp, void *stream);
+
+/* bs_gemm followed by bs_threshold_activate in one kernel: the int32 product
+ * never leaves the chip.  Arguments as in the two calls above. */
+bs_status bs_gemm_threshold(const uint64_t *Wp, int wbits, bs_format wfmt,
+                            const uint64_t *Ap, int abits, bs_format afmt,
+                            int64_t M, int64_t N, int64_t K,
+                            const int32_t *thr, int obits, uint64_t *Yp, void *stream);
+
+/*
+ * Channel-interleaved lowering on packed data (Sec. 3.2): one im2col per
+ * activation bit, moving whole 32-bit words.
+ *   in   device uint64_t [abits][H][W][bs_words_per_row(C)]: per bit position,
+ *        per pixel, the channels packed as a depth (what bs_threshold_activate
+ *        emits for a layer with C output channels and N = H*W).
+ *   out  device uint64_t [abits][OH*OW][bs_words_per_row(Kl)], Kl =
+ *        bs_lowered_depth(C, kh, kw), OH = (H + 2 pad - kh)/stride + 1, same for
+ *        OW; fully overwritten.  Column (oh, ow) is the concatenation over
+ *        (r, s) in kernel-row-major order of the first ceil(C/32) 32-bit words of
+ *        pixel (oh*stride + r - pad, ow*stride + s - pad), zero words for taps
+ *        outside the image.  Lowered depth index = (r*kw + s) * 32*ceil(C/32) + c.
+ * The weight matrix must be packed with the same padded depth order.
+ * Errors: INVALID_ARG (sizes, kernel larger than padded image), ALIGNMENT, LAUNCH.
+ */
+bs_status bs_im2col_interleaved(const uint64_t *in, int abits, int H, int W, int C,
+                                int kh, int kw, int stride, int pad, uint64_t *out, void *stream);
+
+const char *bs_status_string(bs_status s);
+int bs_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BSGEMM_H */

@@ -1,0 +1,164 @@
+"""Thin Python binding of libbsgemm (C ABI in include/bsgemm.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of the
+library.  PyTorch is used for device memory and streams, nothing else.  There is no
+CPU fallback: if the library is missing or a call fails, an exception is raised.
+
+Functions carry the names of the C entry points.  Tensors must live on the GPU; the
+functions enqueue on torch's current stream and return without synchronising.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # imported before the library so that both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbsgemm.so")
+
+BS_OK = 0
+BS_ERR_INVALID_ARG, BS_ERR_UNSUPPORTED, BS_ERR_ALIGNMENT, BS_ERR_OVERFLOW_RISK, BS_ERR_LAUNCH = -1, -2, -3, -4, -5
+BS_UNSIGNED, BS_TWOS_COMPLEMENT, BS_BIPOLAR = 0, 1, 2
+BS_I8, BS_I32 = 0, 1
+
+EXPORTS = ("bs_words_per_row", "bs_lowered_depth", "bs_pack_planes", "bs_gemm", "bs_threshold_activate",
+           "bs_gemm_threshold", "bs_im2col_interleaved", "bs_status_string", "bs_version")
+
+
+class BsError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, status_string(status), status))
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libbsgemm.so (built in-tree by paper_1709_04060_amd.build).  Fails loudly."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libbsgemm.so is not built: run `python -m paper_1709_04060_amd.build` "
+                          "(or __graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+    lib.bs_words_per_row.argtypes = [i64]; lib.bs_words_per_row.restype = i64
+    lib.bs_lowered_depth.argtypes = [i64, i64, i64]; lib.bs_lowered_depth.restype = i64
+    lib.bs_pack_planes.argtypes = [vp, i32, i64, i64, i64, i32, i32, i32, vp, vp]; lib.bs_pack_planes.restype = i32
+    lib.bs_gemm.argtypes = [vp, i32, i32, vp, i32, i32, i64, i64, i64, vp, i64, vp]; lib.bs_gemm.restype = i32
+    lib.bs_threshold_activate.argtypes = [vp, i64, i64, i64, vp, i32, vp, vp]; lib.bs_threshold_activate.restype = i32
+    lib.bs_gemm_threshold.argtypes = [vp, i32, i32, vp, i32, i32, i64, i64, i64, vp, i32, vp, vp]
+    lib.bs_gemm_threshold.restype = i32
+    lib.bs_im2col_interleaved.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.bs_im2col_interleaved.restype = i32
+    lib.bs_status_string.argtypes = [i32]; lib.bs_status_string.restype = ctypes.c_char_p
+    lib.bs_version.argtypes = []; lib.bs_version.restype = i32
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().bs_status_string(int(status)).decode()
+
+
+def bs_version() -> int:
+    return int(load_library().bs_version())
+
+
+def bs_words_per_row(depth: int) -> int:
+    return int(load_library().bs_words_per_row(int(depth)))
+
+
+def bs_lowered_depth(C: int, kh: int, kw: int) -> int:
+    return int(load_library().bs_lowered_depth(int(C), int(kh), int(kw)))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(st: int, where: str):
+    if st != BS_OK:
+        raise BsError(st, where)
+
+
+def _dev(t: torch.Tensor, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError("%s must be a GPU tensor" % name)
+    return t.data_ptr()
+
+
+def _planes(bits: int, rows: int, depth: int, device) -> torch.Tensor:
+    # uint64 planes are carried as int64 tensors (same bytes)
+    return torch.empty((bits, rows, bs_words_per_row(depth)), dtype=torch.int64, device=device)
+
+
+def bs_pack_planes(src: torch.Tensor, bits: int, fmt: int, depth_is_strided: bool = False,
+                   out: torch.Tensor | None = None) -> torch.Tensor:
+    """Pack a 2-D int8/int32 matrix of logical values into bit planes [bits][rows][S].
+    depth_is_strided=False: src is [rows][depth]; True: src is [depth][rows]."""
+    if src.dim() != 2 or src.stride(1) != 1:
+        raise ValueError("src must be 2-D with a contiguous last dimension")
+    dtype = {torch.int8: BS_I8, torch.int32: BS_I32}[src.dtype]
+    rows, depth = (src.shape[1], src.shape[0]) if depth_is_strided else (src.shape[0], src.shape[1])
+    if out is None:
+        out = _planes(bits, rows, depth, src.device)
+    st = load_library().bs_pack_planes(_dev(src, "src"), dtype, rows, depth, src.stride(0), int(bool(depth_is_strided)),
+                                       bits, fmt, _dev(out, "out"), _stream())
+    _check(st, "bs_pack_planes")
+    return out
+
+
+def bs_gemm(Wp: torch.Tensor, wfmt: int, Ap: torch.Tensor, afmt: int, K: int,
+            out: torch.Tensor | None = None) -> torch.Tensor:
+    """C[M][N] (int32) = W . A from packed planes Wp [w][M][S], Ap [a][N][S]."""
+    wbits, M, _ = Wp.shape
+    abits, N, _ = Ap.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=Wp.device)
+    st = load_library().bs_gemm(_dev(Wp, "Wp"), wbits, wfmt, _dev(Ap, "Ap"), abits, afmt, M, N, K,
+                                _dev(out, "out"), out.stride(0), _stream())
+    _check(st, "bs_gemm")
+    return out
+
+
+def bs_threshold_activate(C: torch.Tensor, thr: torch.Tensor, obits: int,
+                          out: torch.Tensor | None = None) -> torch.Tensor:
+    """Yp [obits][N][S_M]: bit planes of the number of thresholds thr[m][:] that C[m][n] reaches."""
+    M, N = C.shape
+    if out is None:
+        out = _planes(obits, N, M, C.device)
+    st = load_library().bs_threshold_activate(_dev(C, "C"), C.stride(0), M, N, _dev(thr, "thr"), obits,
+                                              _dev(out, "out"), _stream())
+    _check(st, "bs_threshold_activate")
+    return out
+
+
+def bs_gemm_threshold(Wp: torch.Tensor, wfmt: int, Ap: torch.Tensor, afmt: int, K: int, thr: torch.Tensor,
+                      obits: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Fused bs_gemm + bs_threshold_activate; the int32 product never leaves the chip."""
+    wbits, M, _ = Wp.shape
+    abits, N, _ = Ap.shape
+    if out is None:
+        out = _planes(obits, N, M, Wp.device)
+    st = load_library().bs_gemm_threshold(_dev(Wp, "Wp"), wbits, wfmt, _dev(Ap, "Ap"), abits, afmt, M, N, K,
+                                          _dev(thr, "thr"), obits, _dev(out, "out"), _stream())
+    _check(st, "bs_gemm_threshold")
+    return out
+
+
+def bs_im2col_interleaved(x: torch.Tensor, H: int, W: int, C: int, kh: int, kw: int, stride: int, pad: int,
+                          out: torch.Tensor | None = None) -> torch.Tensor:
+    """Lower packed HWC planes x [abits][H*W][S_C] to packed columns [abits][OH*OW][S_Kl]."""
+    abits = x.shape[0]
+    OH = (H + 2 * pad - kh) // stride + 1
+    OW = (W + 2 * pad - kw) // stride + 1
+    if out is None:
+        out = _planes(abits, OH * OW, bs_lowered_depth(C, kh, kw), x.device)
+    st = load_library().bs_im2col_interleaved(_dev(x, "x"), abits, H, W, C, kh, kw, stride, pad,
+                                              _dev(out, "out"), _stream())
+    _check(st, "bs_im2col_interleaved")
+    return out

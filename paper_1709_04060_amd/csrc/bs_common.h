@@ -1,0 +1,34 @@
+// Internal helpers shared by the HIP translation units of libbsgemm (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bsgemm.h"
+
+namespace bs {
+
+constexpr int kWave = 64;        // CDNA4 wavefront width
+constexpr int kMaxBits = 4;      // the few-bit range of the paper (w, a <= 4)
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+inline bs_status after_launch() { return hipGetLastError() == hipSuccess ? BS_OK : BS_ERR_LAUNCH; }
+
+inline bs_status check_bits_fmt(int bits, bs_format fmt)
+{
+    if (bits < 1) return BS_ERR_INVALID_ARG;
+    if (fmt != BS_UNSIGNED && fmt != BS_TWOS_COMPLEMENT && fmt != BS_BIPOLAR) return BS_ERR_INVALID_ARG;
+    if (fmt == BS_BIPOLAR && bits != 1) return BS_ERR_INVALID_ARG;
+    if (bits > kMaxBits) return BS_ERR_UNSUPPORTED;
+    return BS_OK;
+}
+
+// Largest magnitude a value of this format can take.
+inline int64_t max_abs(int bits, bs_format fmt)
+{
+    if (fmt == BS_BIPOLAR) return 1;
+    if (fmt == BS_TWOS_COMPLEMENT) return int64_t(1) << (bits - 1);
+    return (int64_t(1) << bits) - 1;
+}
+
+}  // namespace bs

@@ -1,0 +1,85 @@
+// Host side of the bit-serial GEMM entry points: argument checks, the per-plane
+// coefficients of Alg. 2 (and of the bipolar popcount form), and dispatch on the number
+// of weight planes.  The kernel itself lives in bs_gemm_kernel.h.
+#include "bs_gemm_kernel.h"
+
+namespace bs {
+extern template bs_status launch_wb<1>(const GemmParams &, int, bool, bool, hipStream_t);
+extern template bs_status launch_wb<2>(const GemmParams &, int, bool, bool, hipStream_t);
+extern template bs_status launch_wb<3>(const GemmParams &, int, bool, bool, hipStream_t);
+extern template bs_status launch_wb<4>(const GemmParams &, int, bool, bool, hipStream_t);
+}
+
+namespace {
+using namespace bs;
+
+void set_coefficients(GemmParams &g, int wbits, bs_format wfmt, int abits, bs_format afmt, int64_t K)
+{
+    int cw[4] = {0, 0, 0, 0}, ca[4] = {0, 0, 0, 0};
+    int ow = 0, oa = 0;
+    for (int i = 0; i < wbits; ++i) cw[i] = (wfmt == BS_TWOS_COMPLEMENT && i == wbits - 1) ? -(1 << i) : (1 << i);
+    for (int j = 0; j < abits; ++j) ca[j] = (afmt == BS_TWOS_COMPLEMENT && j == abits - 1) ? -(1 << j) : (1 << j);
+    if (wfmt == BS_BIPOLAR) { cw[0] = 2; ow = -1; }
+    if (afmt == BS_BIPOLAR) { ca[0] = 2; oa = -1; }
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 4; ++j) g.coef[i * 4 + j] = cw[i] * ca[j];
+    for (int i = 0; i < 4; ++i) { g.crow[i] = oa * cw[i]; g.ccol[i] = ow * ca[i]; }
+    g.c0 = ow * oa * (int)K;
+}
+
+bs_status gemm_common(const uint64_t *Wp, int wbits, bs_format wfmt, const uint64_t *Ap, int abits, bs_format afmt,
+                      int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc,
+                      const int32_t *thr, int obits, uint64_t *Yp, bool fuse, void *stream)
+{
+    if (!Wp || !Ap || M <= 0 || N <= 0 || K <= 0) return BS_ERR_INVALID_ARG;
+    if (bs_status s = bs::check_bits_fmt(wbits, wfmt)) return s;
+    if (bs_status s = bs::check_bits_fmt(abits, afmt)) return s;
+    if (!bs::aligned(Wp, 16) || !bs::aligned(Ap, 16)) return BS_ERR_ALIGNMENT;
+    if (fuse) {
+        if (!thr || !Yp) return BS_ERR_INVALID_ARG;
+        if (obits < 1) return BS_ERR_INVALID_ARG;
+        if (obits > bs::kMaxBits) return BS_ERR_UNSUPPORTED;
+        if (!bs::aligned(thr, 4) || !bs::aligned(Yp, 16)) return BS_ERR_ALIGNMENT;
+    } else {
+        if (!C || ldc < N) return BS_ERR_INVALID_ARG;
+        if (!bs::aligned(C, 4)) return BS_ERR_ALIGNMENT;
+    }
+    // Conservative: bounds every partial sum of plane-pair terms, not only the result.
+    if ((K << (wbits + abits)) >= (int64_t(1) << 31)) return BS_ERR_OVERFLOW_RISK;
+    const int64_t S = bs_words_per_row(K);
+    const int64_t lim = int64_t(1) << 31;
+    if (wbits * M * S * 2 >= lim || abits * N * S * 2 >= lim || M >= lim || N >= lim) return BS_ERR_OVERFLOW_RISK;
+
+    GemmParams g;
+    g.W = reinterpret_cast<const uint32_t *>(Wp);
+    g.A = reinterpret_cast<const uint32_t *>(Ap);
+    g.M = (int)M; g.N = (int)N; g.Kd = (int)(2 * S);
+    set_coefficients(g, wbits, wfmt, abits, afmt, K);
+    g.C = C; g.ldc = ldc;
+    g.thr = thr; g.obits = obits; g.T = fuse ? (1 << obits) - 1 : 0;
+    g.Y = reinterpret_cast<uint32_t *>(Yp);
+    g.Yd = (int)(2 * bs_words_per_row(M));
+    const bool corr = (wfmt == BS_BIPOLAR) || (afmt == BS_BIPOLAR);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    switch (wbits) {
+    case 1: return launch_wb<1>(g, abits, fuse, corr, st);
+    case 2: return launch_wb<2>(g, abits, fuse, corr, st);
+    case 3: return launch_wb<3>(g, abits, fuse, corr, st);
+    default: return launch_wb<4>(g, abits, fuse, corr, st);
+    }
+}
+
+}  // namespace
+
+extern "C" bs_status bs_gemm(const uint64_t *Wp, int wbits, bs_format wfmt, const uint64_t *Ap, int abits,
+                             bs_format afmt, int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc, void *stream)
+{
+    return gemm_common(Wp, wbits, wfmt, Ap, abits, afmt, M, N, K, C, ldc, nullptr, 0, nullptr, false, stream);
+}
+
+extern "C" bs_status bs_gemm_threshold(const uint64_t *Wp, int wbits, bs_format wfmt, const uint64_t *Ap, int abits,
+                                       bs_format afmt, int64_t M, int64_t N, int64_t K, const int32_t *thr,
+                                       int obits, uint64_t *Yp, void *stream)
+{
+    return gemm_common(Wp, wbits, wfmt, Ap, abits, afmt, M, N, K, nullptr, 0, thr, obits, Yp, true, stream);
+}

@@ -1,0 +1,357 @@
+// Bit-serial GEMM (Alg. 2 built from the AND-popcount BinaryGEMM of Alg. 1), with the
+// plane-pair weighting and, optionally, successive thresholding (Sec. 2.1.1) fused
+// into the epilogue.
+//
+// General form.  With packed bits Wb[i], Ab[j] the logical operands are
+//   W = sum_i cw_i Wb[i] + ow,   A = sum_j ca_j Ab[j] + oa
+// (unsigned: cw_i = 2^i; two's complement: top plane negated, the sign rule of Alg. 2;
+// bipolar: value = 2 bit - 1, i.e. cw_0 = 2, ow = -1).  Then
+//   C[m][n] = sum_ij cw_i ca_j P_ij[m][n] + ow sum_j ca_j popA_j[n]
+//             + oa sum_i cw_i popW_i[m] + ow oa K,
+//   P_ij[m][n] = sum_d popcount(Wb[i][m][d] & Ab[j][n][d])      (Alg. 1)
+// where popW / popA are row popcounts of the planes.  Padding bits are zero in both
+// operands, so all counts run over the true depth.
+//
+// Kernel shape (CDNA4): a workgroup owns a BM x BN tile of C and walks the depth in
+// stages of 32 dwords (1024 bits) per packed row.  Each stage is fetched from global
+// memory into registers while the previous one is being consumed, then written to LDS
+// as 16-byte chunks, XOR-swizzled so that the eight distinct rows a ds_read_b128
+// touches fall in eight different bank groups.  A wavefront is an 8 x 8 grid of lanes,
+// each lane holding a TM x TN block of int32 accumulators; per 16-byte chunk it reads
+// TM weight rows and TN activation columns per plane from LDS and issues
+// v_and_b32 + v_bcnt_u32_b32 (whose add operand makes the accumulation free).
+#pragma once
+#include "bs_common.h"
+
+namespace bs {
+
+constexpr int KT = 32;      // dwords of depth per packed row and stage
+constexpr int KCH = KT / 4; // 16-byte chunks per row and stage
+
+struct GemmParams {
+    const uint32_t *W;  // dword view of Wp
+    const uint32_t *A;  // dword view of Ap
+    int M, N;
+    int Kd;             // dwords per packed row (2 * S)
+    int coef[16];       // cw_i * ca_j at [i * 4 + j]
+    int crow[4];        // oa * cw_i   (row-popcount correction weights)
+    int ccol[4];        // ow * ca_j   (column-popcount correction weights)
+    int c0;             // ow * oa * K
+    int32_t *C;
+    long long ldc;
+    const int32_t *thr; // [M][T]
+    int T, obits;
+    uint32_t *Y;        // dword view of Yp
+    int Yd;             // dwords per column of Yp (2 * S_M)
+};
+
+__device__ __forceinline__ int popc_and4(const uint4 &a, const uint4 &b, int acc)
+{
+    acc += __builtin_popcount(a.x & b.x);
+    acc += __builtin_popcount(a.y & b.y);
+    acc += __builtin_popcount(a.z & b.z);
+    acc += __builtin_popcount(a.w & b.w);
+    return acc;
+}
+
+__device__ __forceinline__ int popc4(const uint4 &a)
+{
+    return __builtin_popcount(a.x) + __builtin_popcount(a.y) + __builtin_popcount(a.z) + __builtin_popcount(a.w);
+}
+
+// WB, AB: weight / activation planes.  TM x TN: accumulators per lane.  WM x WN:
+// wavefronts per workgroup.  FUSE: thresholding epilogue instead of the int32 store.
+// CORR: popcount correction terms needed (some operand is bipolar).
+template <int WB, int AB, int TM, int TN, int WM, int WN, bool FUSE, bool CORR>
+__global__ void __launch_bounds__(WM * WN * 64)
+bs_gemm_kernel(const GemmParams p)
+{
+    constexpr int BM = 8 * TM * WM, BN = 8 * TN * WN, NT = 64 * WM * WN;
+    constexpr int WROWS = WB * BM, AROWS = AB * BN, ROWS = WROWS + AROWS;
+    constexpr int CHUNKS = ROWS * KCH;
+    constexpr int CPT = (CHUNKS + NT - 1) / NT;  // chunks each thread moves per stage
+    constexpr int PAIRS = WB * AB;
+    constexpr bool PER_PAIR = PAIRS <= 4;        // one accumulator set per plane pair
+    constexpr int NACC = PER_PAIR ? PAIRS : 1;
+
+    __shared__ uint4 lds[CHUNKS];
+    __shared__ int corr_row[CORR ? BM : 1];
+    __shared__ int corr_col[CORR ? BN : 1];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int ly = lane >> 3, lx = lane & 7;
+    const int wm = wave / WN, wn = wave % WN;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+
+    // ---- loader set-up: which chunk of which stacked row this thread moves ----
+    int goff[CPT];    // dword offset into W or A of the chunk at stage 0, -1 if out of range
+    int loff[CPT];    // destination chunk index in LDS
+    int cweight[CPT]; // correction weight of the plane the chunk belongs to
+    int cnt[CPT];
+#pragma unroll
+    for (int s = 0; s < CPT; ++s) {
+        const int id = tid + s * NT;
+        const int srow = id / KCH, c = id % KCH;
+        goff[s] = -1; loff[s] = 0; cweight[s] = 0; cnt[s] = 0;
+        if (id < CHUNKS) {
+            if (srow < WROWS) {
+                const int pl = srow / BM, r = srow % BM;
+                loff[s] = srow * KCH + (c ^ ((r / TM) & 7));
+                if (m0 + r < p.M) goff[s] = (pl * p.M + m0 + r) * p.Kd + c * 4;
+                if (CORR) cweight[s] = p.crow[pl];
+            } else {
+                const int q = srow - WROWS;
+                const int pl = q / BN, r = q % BN;
+                loff[s] = srow * KCH + (c ^ ((r / TN) & 7));
+                if (n0 + r < p.N) goff[s] = (pl * p.N + n0 + r) * p.Kd + c * 4;
+                if (CORR) cweight[s] = p.ccol[pl];
+            }
+        }
+    }
+    if (CORR) {
+        for (int i = tid; i < BM; i += NT) corr_row[i] = 0;
+        for (int i = tid; i < BN; i += NT) corr_col[i] = 0;
+    }
+
+    uint4 stage[CPT];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int s = 0; s < CPT; ++s) {
+            const int id = tid + s * NT;
+            const int srow = id / KCH, c = id % KCH;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (goff[s] >= 0 && k0 + c * 4 < p.Kd) {
+                const uint32_t *base = srow < WROWS ? p.W : p.A;
+                v = *reinterpret_cast<const uint4 *>(base + (size_t)(unsigned)goff[s] + k0);
+            }
+            stage[s] = v;
+        }
+    };
+
+    int acc[NACC][TM][TN];
+#pragma unroll
+    for (int a = 0; a < NACC; ++a)
+#pragma unroll
+        for (int r = 0; r < TM; ++r)
+#pragma unroll
+            for (int c = 0; c < TN; ++c) acc[a][r][c] = 0;
+
+    const int wrow0 = (wm * 8 + ly) * TM;          // first weight row of this lane in the tile
+    const int acol0 = (wn * 8 + lx) * TN;          // first activation column
+    const uint4 *ldsW = lds + wrow0 * KCH;
+    const uint4 *ldsA = lds + (WROWS + acol0) * KCH;
+
+    fetch(0);
+    for (int k0 = 0; k0 < p.Kd; k0 += KT) {
+        __syncthreads();  // everyone is done reading the previous stage
+#pragma unroll
+        for (int s = 0; s < CPT; ++s) {
+            if (tid + s * NT < CHUNKS) lds[loff[s]] = stage[s];
+            if (CORR) cnt[s] += popc4(stage[s]);
+        }
+        __syncthreads();
+        if (k0 + KT < p.Kd) fetch(k0 + KT);
+
+        if constexpr (PER_PAIR) {
+#pragma unroll
+            for (int q = 0; q < KCH; ++q) {
+                uint4 w[WB][TM], a[AB][TN];
+#pragma unroll
+                for (int i = 0; i < WB; ++i)
+#pragma unroll
+                    for (int r = 0; r < TM; ++r) w[i][r] = ldsW[(i * BM + r) * KCH + (q ^ ly)];
+#pragma unroll
+                for (int j = 0; j < AB; ++j)
+#pragma unroll
+                    for (int c = 0; c < TN; ++c) a[j][c] = ldsA[(j * BN + c) * KCH + (q ^ lx)];
+#pragma unroll
+                for (int i = 0; i < WB; ++i)
+#pragma unroll
+                    for (int j = 0; j < AB; ++j)
+#pragma unroll
+                        for (int r = 0; r < TM; ++r)
+#pragma unroll
+                            for (int c = 0; c < TN; ++c)
+                                acc[i * AB + j][r][c] = popc_and4(w[i][r], a[j][c], acc[i * AB + j][r][c]);
+            }
+        } else {
+            // Many plane pairs: one pair at a time over the whole stage into a small
+            // counter (at most 1024 per stage), then one weighted add per pair and stage.
+#pragma unroll 1
+            for (int i = 0; i < WB; ++i) {
+#pragma unroll 1
+                for (int j = 0; j < AB; ++j) {
+                    int t[TM][TN];
+#pragma unroll
+                    for (int r = 0; r < TM; ++r)
+#pragma unroll
+                        for (int c = 0; c < TN; ++c) t[r][c] = 0;
+#pragma unroll
+                    for (int q = 0; q < KCH; ++q) {
+                        uint4 w[TM], a[TN];
+#pragma unroll
+                        for (int r = 0; r < TM; ++r) w[r] = ldsW[(i * BM + r) * KCH + (q ^ ly)];
+#pragma unroll
+                        for (int c = 0; c < TN; ++c) a[c] = ldsA[(j * BN + c) * KCH + (q ^ lx)];
+#pragma unroll
+                        for (int r = 0; r < TM; ++r)
+#pragma unroll
+                            for (int c = 0; c < TN; ++c) t[r][c] = popc_and4(w[r], a[c], t[r][c]);
+                    }
+                    const int cf = p.coef[i * 4 + j];
+#pragma unroll
+                    for (int r = 0; r < TM; ++r)
+#pragma unroll
+                        for (int c = 0; c < TN; ++c) acc[0][r][c] += __mul24(t[r][c], cf);
+                }
+            }
+        }
+    }
+
+    // ---- correction terms (bipolar operands): weighted row popcounts via LDS atomics ----
+    if (CORR) {
+#pragma unroll
+        for (int s = 0; s < CPT; ++s) {
+            const int id = tid + s * NT;
+            if (id < CHUNKS && cweight[s] != 0) {
+                const int srow = id / KCH;
+                if (srow < WROWS) atomicAdd(&corr_row[srow % BM], cweight[s] * cnt[s]);
+                else atomicAdd(&corr_col[(srow - WROWS) % BN], cweight[s] * cnt[s]);
+            }
+        }
+    }
+    __syncthreads();  // also: all LDS tile reads are finished, the tile space may be reused
+
+    // ---- epilogue: weight the plane pairs (Alg. 2), add corrections ----
+    int val[TM][TN];
+#pragma unroll
+    for (int r = 0; r < TM; ++r)
+#pragma unroll
+        for (int c = 0; c < TN; ++c) {
+            int v;
+            if constexpr (PER_PAIR) {
+                v = 0;
+#pragma unroll
+                for (int i = 0; i < WB; ++i)
+#pragma unroll
+                    for (int j = 0; j < AB; ++j) v += p.coef[i * 4 + j] * acc[i * AB + j][r][c];
+            } else {
+                v = acc[0][r][c];
+            }
+            if (CORR) v += corr_row[wrow0 + r] + corr_col[acol0 + c] + p.c0;
+            val[r][c] = v;
+        }
+
+    if constexpr (!FUSE) {
+        const bool vec_ok = (TN % 4 == 0) && ((p.ldc & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.C) & 15) == 0);
+#pragma unroll
+        for (int r = 0; r < TM; ++r) {
+            const int m = m0 + wrow0 + r;
+            if (m >= p.M) continue;
+            int32_t *crow = p.C + (long long)m * p.ldc;
+            const int n = n0 + acol0;
+            if (vec_ok && n + TN <= p.N) {
+#pragma unroll
+                for (int c = 0; c < TN; c += 4)
+                    *reinterpret_cast<int4 *>(crow + n + c) =
+                        make_int4(val[r][c], val[r][c + 1], val[r][c + 2], val[r][c + 3]);
+            } else {
+#pragma unroll
+                for (int c = 0; c < TN; ++c)
+                    if (n + c < p.N) crow[n + c] = val[r][c];
+            }
+        }
+    } else {
+        // Successive thresholding: count the thresholds reached, stage the few-bit
+        // results as bytes in LDS ([column][row]), then pack along the rows.
+        static_assert(BM % 32 == 0, "packed output is written in 32-bit words");
+        uint8_t *ytile = reinterpret_cast<uint8_t *>(lds);  // BN * BM bytes <= tile space
+        static_assert(BN * BM <= CHUNKS * 16, "epilogue staging must fit in the tile space");
+#pragma unroll
+        for (int r = 0; r < TM; ++r) {
+            const int m = m0 + wrow0 + r;
+            const int32_t *th = p.thr + (long long)m * p.T;
+#pragma unroll
+            for (int c = 0; c < TN; ++c) {
+                int y = 0;
+                if (m < p.M)
+                    for (int t = 0; t < p.T; ++t) y += (val[r][c] >= th[t]) ? 1 : 0;
+                ytile[(acol0 + c) * BM + wrow0 + r] = (uint8_t)y;
+            }
+        }
+        __syncthreads();
+        constexpr int WPC = BM / 32;  // output dwords per column and plane in this tile
+        const int last_m_block = (blockIdx.y == gridDim.y - 1);
+        for (int it = tid; it < BN * WPC; it += NT) {
+            const int col = it / WPC, wi = it % WPC;
+            const int n = n0 + col;
+            if (n >= p.N) continue;
+            const uint32_t *yb = reinterpret_cast<const uint32_t *>(ytile + col * BM + wi * 32);
+            uint32_t bitsw[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int d = 0; d < 8; ++d) {
+                const uint32_t x = yb[d];
+#pragma unroll
+                for (int pl = 0; pl < 4; ++pl) {
+                    // bits pl of the four bytes of x -> a 4-bit group
+                    const uint32_t nib = ((((x >> pl) & 0x01010101u) * 0x01020408u) >> 24) & 0xFu;
+                    bitsw[pl] |= nib << (4 * d);
+                }
+            }
+            for (int pl = 0; pl < p.obits; ++pl) {
+                uint32_t *dst = p.Y + ((long long)pl * p.N + n) * p.Yd;
+                dst[m0 / 32 + wi] = bitsw[pl];
+                // the last row block also clears the padding words of the column
+                if (last_m_block && wi == WPC - 1)
+                    for (int z = m0 / 32 + WPC; z < p.Yd; ++z) dst[z] = 0;
+            }
+        }
+    }
+}
+
+template <int WB, int AB, int TM, int TN, int WM, int WN>
+bs_status launch_cfg(const GemmParams &g, bool fuse, bool corr, hipStream_t st)
+{
+    constexpr int BM = 8 * TM * WM, BN = 8 * TN * WN;
+    dim3 grid((unsigned)((g.N + BN - 1) / BN), (unsigned)((g.M + BM - 1) / BM));
+    if (grid.y > 65535) return BS_ERR_UNSUPPORTED;
+    dim3 block(WM * WN * 64);
+    // A bipolar operand has exactly one plane, so the correction variant only exists
+    // where WB == 1 or AB == 1.
+    constexpr bool CAN_CORR = (WB == 1 || AB == 1);
+    if (corr && !CAN_CORR) return BS_ERR_INVALID_ARG;
+    if (fuse) {
+        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, true, CAN_CORR><<<grid, block, 0, st>>>(g);
+        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, true, false><<<grid, block, 0, st>>>(g);
+    } else {
+        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, false, CAN_CORR><<<grid, block, 0, st>>>(g);
+        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, false, false><<<grid, block, 0, st>>>(g);
+    }
+    return bs::after_launch();
+}
+
+template <int WB, int AB>
+bs_status launch_planes(const GemmParams &g, bool fuse, bool corr, hipStream_t st)
+{
+    // Small problems get 32 x 32 tiles (one wavefront per workgroup) so that more
+    // compute units have work; everything else 64 x 64 with four wavefronts.
+    const long long tiles64 = (long long)((g.M + 63) / 64) * ((g.N + 63) / 64);
+    if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1>(g, fuse, corr, st);
+    return launch_cfg<WB, AB, 4, 4, 2, 2>(g, fuse, corr, st);
+}
+
+// Defined once per WB in bs_gemm_w<WB>.hip (explicit instantiation) to keep builds parallel.
+template <int WB>
+bs_status launch_wb(const GemmParams &g, int abits, bool fuse, bool corr, hipStream_t st)
+{
+    switch (abits) {
+    case 1: return launch_planes<WB, 1>(g, fuse, corr, st);
+    case 2: return launch_planes<WB, 2>(g, fuse, corr, st);
+    case 3: return launch_planes<WB, 3>(g, fuse, corr, st);
+    default: return launch_planes<WB, 4>(g, fuse, corr, st);
+    }
+}
+
+
+}  // namespace bs

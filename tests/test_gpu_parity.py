@@ -1,0 +1,142 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, bit-exact,
+element by element, on seeded inputs that span several tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1709_04060_amd as bs
+from gpu_util import FMT, assert_equal, dev, draw, planes_to_dev, planes_to_numpy
+
+pytestmark = pytest.mark.gpu
+U, TC, BP = oracle.UNSIGNED, oracle.TWOS_COMPLEMENT, oracle.BIPOLAR
+
+
+# ------------------------------------------------------------------ S1 pack
+@pytest.mark.parametrize("rows,depth", [(1, 1), (3, 63), (5, 64), (7, 65), (64, 256), (130, 1000), (33, 4097)])
+@pytest.mark.parametrize("bits,fmt", [(1, U), (2, U), (4, U), (2, TC), (3, TC), (4, TC), (1, BP)])
+@pytest.mark.parametrize("dtype", [np.int8, np.int32])
+def test_pack_rows_and_cols(rows, depth, bits, fmt, dtype):
+    rng = np.random.default_rng(rows * 1000 + depth + bits)
+    X = draw(rng, (rows, depth), bits, fmt).astype(dtype)
+    want = oracle.pack(X, bits, fmt)
+    got = bs.bs_pack_planes(dev(X), bits, FMT[fmt])
+    assert_equal(planes_to_numpy(got), want, "pack depth-contiguous")
+    got_t = bs.bs_pack_planes(dev(X.T.copy()), bits, FMT[fmt], depth_is_strided=True)
+    assert_equal(planes_to_numpy(got_t), want, "pack depth-strided")
+
+
+def test_pack_respects_leading_dimension_and_overwrites_padding():
+    rng = np.random.default_rng(11)
+    big = draw(rng, (40, 300), 2, U)
+    X = big[:, :200]
+    t = dev(big)[:, :200]                      # ld = 300 > depth
+    out = torch.full((2, 40, bs.bs_words_per_row(200)), -1, dtype=torch.int64, device="cuda")
+    bs.bs_pack_planes(t, 2, bs.BS_UNSIGNED, out=out)
+    assert_equal(planes_to_numpy(out), oracle.pack(X, 2, U), "pack with ld")
+    tt = dev(big.T.copy())[:200, :]            # strided: [depth][rows], all 40 rows, ld = 40
+    out.fill_(-1)
+    bs.bs_pack_planes(tt, 2, bs.BS_UNSIGNED, depth_is_strided=True, out=out)
+    assert_equal(planes_to_numpy(out), oracle.pack(X, 2, U), "pack strided with ld")
+
+
+# ------------------------------------------------------------------ S3 + S4 GEMM
+ALL_WA = [(w, wf, a, af) for w in (1, 2, 3, 4) for a in (1, 2, 3, 4) for wf in (U, TC) for af in (U, TC)]
+BIP = [(1, BP, a, af) for a in (1, 2, 3, 4) for af in (U, TC)] + [(w, wf, 1, BP) for w in (1, 2, 3, 4) for wf in (U, TC)] \
+      + [(1, BP, 1, BP)]
+
+
+def run_gemm(W, A, w, wf, a, af):
+    Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
+    Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
+    return bs.bs_gemm(Wp, FMT[wf], Ap, FMT[af], W.shape[1]).cpu().numpy()
+
+
+@pytest.mark.parametrize("w,wf,a,af", ALL_WA + BIP)
+def test_gemm_all_precisions_and_formats(w, wf, a, af):
+    rng = np.random.default_rng(w * 64 + a * 16 + wf * 4 + af)
+    M, K, N = 70, 1100, 45                      # ragged in every dimension, 2 depth stages
+    W, A = draw(rng, (M, K), w, wf), draw(rng, (K, N), a, af)
+    assert_equal(run_gemm(W, A, w, wf, a, af), oracle.gemm(W, A), "gemm W%dA%d" % (w, a))
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 1, 1), (1, 64, 1), (64, 256, 64), (65, 129, 63), (200, 3000, 130),
+                                   (257, 1024, 129), (31, 2049, 700), (1000, 100, 3), (3, 5000, 1000)])
+@pytest.mark.parametrize("w,wf,a,af", [(1, BP, 2, U), (2, TC, 2, U), (4, TC, 4, U), (3, TC, 3, TC)])
+def test_gemm_shapes(M, K, N, w, wf, a, af):
+    rng = np.random.default_rng(M + K + N)
+    W, A = draw(rng, (M, K), w, wf), draw(rng, (K, N), a, af)
+    assert_equal(run_gemm(W, A, w, wf, a, af), oracle.gemm(W, A), "gemm %dx%dx%d" % (M, K, N))
+
+
+def test_gemm_extreme_values_and_ldc():
+    M, K, N = 66, 640, 50
+    for w, a in [(2, 2), (4, 4)]:
+        W = np.full((M, K), -(1 << (w - 1)), dtype=np.int8)
+        A = np.full((K, N), (1 << a) - 1, dtype=np.int8)
+        assert (run_gemm(W, A, w, TC, a, U) == -K * (1 << (w - 1)) * ((1 << a) - 1)).all()
+    rng = np.random.default_rng(5)
+    W, A = draw(rng, (M, K), 2, TC), draw(rng, (K, N), 2, U)
+    Wp = bs.bs_pack_planes(dev(W), 2, bs.BS_TWOS_COMPLEMENT)
+    Ap = bs.bs_pack_planes(dev(A), 2, bs.BS_UNSIGNED, depth_is_strided=True)
+    big = torch.full((M, 77), 123456, dtype=torch.int32, device="cuda")
+    bs.bs_gemm(Wp, bs.BS_TWOS_COMPLEMENT, Ap, bs.BS_UNSIGNED, K, out=big[:, :N])     # ldc = 77, unaligned rows
+    got = big.cpu().numpy()
+    assert_equal(got[:, :N], oracle.gemm(W, A), "gemm ldc")
+    assert (got[:, N:] == 123456).all()         # nothing written beyond N
+
+
+# ------------------------------------------------------------------ S5 threshold
+def make_thr(rng, C, obits):
+    T = (1 << obits) - 1
+    lo, hi = int(C.min()) - 2, int(C.max()) + 3
+    return np.sort(rng.integers(lo, hi, size=(C.shape[0], T)), axis=1).astype(np.int32)
+
+
+@pytest.mark.parametrize("M,N", [(1, 1), (64, 64), (70, 45), (129, 300), (300, 2), (4096, 1)])
+@pytest.mark.parametrize("obits", [1, 2, 3, 4])
+def test_threshold_activate(M, N, obits):
+    rng = np.random.default_rng(M * 7 + N + obits)
+    C = rng.integers(-500, 500, size=(M, N)).astype(np.int32)
+    thr = make_thr(rng, C, obits)
+    out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
+    bs.bs_threshold_activate(dev(C), dev(thr), obits, out=out)
+    assert_equal(planes_to_numpy(out), oracle.threshold_pack(C, thr, obits), "threshold")
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 64, 1), (64, 256, 64), (70, 1100, 45), (200, 700, 130), (260, 300, 3)])
+@pytest.mark.parametrize("w,wf,a,af,obits", [(1, BP, 2, U, 2), (2, TC, 2, U, 2), (4, TC, 4, U, 4), (1, BP, 1, BP, 1),
+                                             (2, U, 3, TC, 3)])
+def test_gemm_threshold_fused(M, K, N, w, wf, a, af, obits):
+    rng = np.random.default_rng(M + K + N + obits)
+    W, A = draw(rng, (M, K), w, wf), draw(rng, (K, N), a, af)
+    C = oracle.gemm(W, A)
+    thr = make_thr(rng, C, obits)
+    Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
+    Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
+    out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
+    bs.bs_gemm_threshold(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits, out=out)
+    assert_equal(planes_to_numpy(out), oracle.threshold_pack(C, thr, obits), "fused gemm+threshold")
+
+
+# ------------------------------------------------------------------ S2 lowering
+def pad_channels(x, Cp):
+    out = np.zeros(x.shape[:-1] + (Cp,), dtype=x.dtype)
+    out[..., : x.shape[-1]] = x
+    return out
+
+
+@pytest.mark.parametrize("H,W,C,k,s,p", [(5, 6, 3, 3, 1, 1), (7, 7, 32, 5, 1, 2), (9, 8, 40, 3, 2, 0),
+                                         (6, 6, 96, 1, 1, 0), (27, 27, 96, 5, 1, 2), (8, 9, 130, 3, 2, 1)])
+@pytest.mark.parametrize("abits", [1, 2, 4])
+def test_im2col_interleaved(H, W, C, k, s, p, abits):
+    rng = np.random.default_rng(H * W + C + abits)
+    x = draw(rng, (H, W, C), abits, U)
+    Cp = 32 * ((C + 31) // 32)
+    # expected: plain lowering of the channel-padded image, then packed column by column
+    L = oracle.im2col_plain(pad_channels(x, Cp), k, k, s, p)
+    assert L.shape[0] == bs.bs_lowered_depth(C, k, k)
+    want = oracle.pack(L.T.copy(), abits, U)
+    xin = oracle.pack(x.reshape(H * W, C), abits, U)          # packed HWC planes
+    out = bs.bs_im2col_interleaved(planes_to_dev(xin), H, W, C, k, k, s, p)
+    assert_equal(planes_to_numpy(out), want, "interleaved lowering")
