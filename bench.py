@@ -1,0 +1,181 @@
+"""Benchmark of the bit-serial GEMM hot path on one MI355X.
+
+    python bench.py --gpus 1 --steps K --warmup W
+
+A step is one pass of the hot path over one batch of the W2A2 4096^3 configuration:
+bit-plane packing of the int8 activation matrix (K x N, transposing) followed by the
+bit-serial GEMM to int32 (weights are packed once, outside the timed region, as they
+would be for inference).  All inputs are resident in HBM before timing starts.  One JSON
+line is printed: the headline metric (GOPS = 2 M N K / T, Sec. 4.1 of the paper), the
+roofline figures of the dominant kernel, the CPU oracle timed on the host's cores, and
+per-kernel figures for the other configurations (GEMV chain, lowered convolution, W4A4
+sweep) for context.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+# chip figures used for the rooflines
+CUS, LANES_PER_CU_CLK, CLOCK_HZ = 256, 64, 2.4e9
+VALU_LANE_OPS = CUS * LANES_PER_CU_CLK * CLOCK_HZ            # 32-bit integer lane-ops / s
+BINARY_PEAK_TOPS = VALU_LANE_OPS / 2 * 32 * 2 / 1e12           # one AND + one BCNT per 32 binary MACs, 2 ops / MAC
+HBM_PEAK_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding "
+              "in this library)" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_1709_04060_amd as bs
+    from paper_1709_04060_amd import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    bs.load_library()
+
+    def dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    def timed(fn, iters, warm):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / iters
+        return e0.elapsed_time(e1) / iters, wall
+
+    # ------------------------------------------------------------- headline: W2A2 4096^3
+    M = N = K = 4096
+    w, a = 2, 2
+    d = workloads.cfg2_square(M)
+    Wd, Ad = dev(d["W"]), dev(d["A"])
+    Wp = bs.bs_pack_planes(Wd, w, bs.BS_TWOS_COMPLEMENT)
+    Ap = torch.empty((a, N, bs.bs_words_per_row(K)), dtype=torch.int64, device="cuda")
+    C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+
+    def step():
+        bs.bs_pack_planes(Ad, a, bs.BS_UNSIGNED, depth_is_strided=True, out=Ap)
+        bs.bs_gemm(Wp, bs.BS_TWOS_COMPLEMENT, Ap, bs.BS_UNSIGNED, K, out=C)
+
+    ev_ms, wall_ms = timed(step, args.steps, args.warmup)
+    ms_per_step = max(ev_ms, wall_ms)
+    gops = 2.0 * M * N * K / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel alone, on the same stream (events are recorded on torch's current
+    # stream, which is the stream handed to the library)
+    gemm_ms, _ = timed(lambda: bs.bs_gemm(Wp, bs.BS_TWOS_COMPLEMENT, Ap, bs.BS_UNSIGNED, K, out=C), args.steps, 2)
+    pack_ms, _ = timed(lambda: bs.bs_pack_planes(Ad, a, bs.BS_UNSIGNED, depth_is_strided=True, out=Ap), args.steps, 2)
+    binary_tops = w * a * 2.0 * M * N * K / (gemm_ms * 1e-3) / 1e12
+
+    # spot check against the oracle (sampled outputs; the full comparison is in tests/)
+    import oracle
+    Ch = C.cpu().numpy()
+    rng = np.random.default_rng(0)
+    for _ in range(64):
+        m, n = int(rng.integers(M)), int(rng.integers(N))
+        assert int(Ch[m, n]) == oracle.dot(d["W"], d["A"], m, n), "GPU result differs from the oracle"
+
+    result = {
+        "metric": "bit-serial GEMM GOPS (2*M*N*K/T), W2A2", "value": round(gops, 1), "unit": "GOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32 popcount (u32 bitwise)",
+        "data": "synthetic",
+        "config": {"workload": "W2A2 4096x4096x4096: pack int8 activations (K x N) to bit planes + bit-serial "
+                               "GEMM to int32; weights pre-packed", "M": M, "N": N, "K": K, "wbits": w, "abits": a},
+        "roofline": {"bound": "alu", "kernel": "bs_gemm_kernel<2,2,...>", "achieved": round(binary_tops, 1),
+                     "peak": round(BINARY_PEAK_TOPS, 1), "unit": "binary TOP/s", "frac": round(binary_tops / BINARY_PEAK_TOPS, 4),
+                     "kernel_ms": round(gemm_ms, 4), "traffic": None},
+        "breakdown_ms": {"pack_activations": round(pack_ms, 4), "bs_gemm": round(gemm_ms, 4)},
+    }
+
+    # ------------------------------------------------------------- CPU oracle on the host cores
+    if not args.no_cpu_baseline:
+        reps = 3
+        oracle.gemm(d["W"][:64], d["A"])
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            oracle.gemm(d["W"], d["A"])
+        dt = (time.perf_counter() - t0) / reps
+        result["cpu_baseline"] = {"value": round(2.0 * M * N * K / dt / 1e9, 1), "unit": "GOPS",
+                                  "cores": oracle.num_threads(), "kind": "oracle",
+                                  "sample": "the full 4096^3 integer product (no packing), mean of %d runs, %.2f s each"
+                                            % (reps, dt)}
+
+    # ------------------------------------------------------------- other configurations, per kernel
+    if not args.no_extras:
+        result["other_configs"] = extras(bs, workloads, dev, timed)
+
+    print(json.dumps(result))
+    return 0
+
+
+def extras(bs, workloads, dev, timed):
+    import torch
+    out = {}
+
+    def planes(bits, rows, K):
+        return torch.randint(-2 ** 62, 2 ** 62, (bits, rows, bs.bs_words_per_row(K)), dtype=torch.int64, device="cuda")
+
+    def thr_for(Mrows, obits):
+        T = (1 << obits) - 1
+        return torch.sort(torch.randint(-1000, 1000, (Mrows, T), dtype=torch.int32, device="cuda"), dim=1)[0].contiguous()
+
+    def fused(name, w, wf, a, af, M, N, K, obits, copies=1):
+        # `copies` distinct weight buffers are cycled through so that the weights of a
+        # small layer do not simply sit in the last-level cache from the previous launch
+        Wps = [planes(w, M, K) for _ in range(copies)]
+        Ap, th = planes(a, N, K), thr_for(M, obits)
+        Y = torch.empty((obits, N, bs.bs_words_per_row(M)), dtype=torch.int64, device="cuda")
+        state = {"i": 0}
+
+        def f():
+            bs.bs_gemm_threshold(Wps[state["i"] % copies], wf, Ap, af, K, th, obits, out=Y)
+            state["i"] += 1
+        ms, _ = timed(f, max(20, 2 * copies), max(3, copies))
+        byts = (w * M + a * N) * bs.bs_words_per_row(K) * 8 + th.numel() * 4 + Y.numel() * 8
+        out[name] = {"us": round(ms * 1e3, 2), "GOPS": round(2.0 * M * N * K / ms / 1e6, 1),
+                     "binary_frac_of_valu_peak": round(w * a * 2.0 * M * N * K / (ms * 1e-3) / 1e12 / BINARY_PEAK_TOPS, 4),
+                     "GBps": round(byts / ms / 1e6, 1), "frac_of_hbm_peak": round(byts / ms / 1e6 / HBM_PEAK_GBS, 4),
+                     "weight_copies_cycled": copies}
+
+    BP, U, TC = bs.BS_BIPOLAR, bs.BS_UNSIGNED, bs.BS_TWOS_COMPLEMENT
+    fused("fc6_W1A2_4096x9216x1_cold", 1, BP, 2, U, 4096, 1, 9216, 2, copies=64)
+    fused("fc7_W1A2_4096x4096x1_cold", 1, BP, 2, U, 4096, 1, 4096, 2, copies=128)
+    fused("fc6_W1A2_4096x9216x1_warm", 1, BP, 2, U, 4096, 1, 9216, 2, copies=1)
+    fused("conv2_W1A2_256x2400x729", 1, BP, 2, U, 256, 729, 2400, 2)
+    for n in (1, 64, 1024, 8192):
+        fused("W4A4_8192x8192x%d" % n, 4, TC, 4, U, 8192, n, 8192, 4, copies=(10 if n == 1 else 1))
+    # interleaved lowering of conv2 alone
+    x = planes(2, 27 * 27, 96)
+    low = torch.empty((2, 729, bs.bs_words_per_row(2400)), dtype=torch.int64, device="cuda")
+    ms, _ = timed(lambda: bs.bs_im2col_interleaved(x, 27, 27, 96, 5, 5, 1, 2, out=low), 50, 3)
+    out["conv2_interleaved_lowering"] = {"us": round(ms * 1e3, 2),
+                                         "GBps": round((low.numel() * 8 + x.numel() * 8) / ms / 1e6, 1)}
+    return out
+
+
+if __name__ == "__main__":
+    sys.exit(main())
