@@ -61,6 +61,7 @@ bs_status gemm_common(const uint64_t *Wp, int wbits, bs_format wfmt, const uint6
     g.Yd = (int)(2 * bs_words_per_row(M));
     const bool corr = (wfmt == BS_BIPOLAR) || (afmt == BS_BIPOLAR);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (gemv_applicable(g, abits, afmt == BS_BIPOLAR)) return launch_gemv(g, wbits, abits, fuse, st);
     switch (wbits) {
     case 1: return launch_wb<1>(g, abits, fuse, corr, st);
     case 2: return launch_wb<2>(g, abits, fuse, corr, st);

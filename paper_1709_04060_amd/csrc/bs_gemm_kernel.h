@@ -45,6 +45,12 @@ struct GemmParams {
     int Yd;             // dwords per column of Yp (2 * S_M)
 };
 
+// GEMV path (bs_gemv.hip): used for at most this many columns, activation planes in LDS.
+constexpr int kGemvMaxCols = 4;
+constexpr size_t kGemvMaxLds = 64 * 1024;
+bool gemv_applicable(const GemmParams &g, int abits, bool a_bipolar);
+bs_status launch_gemv(const GemmParams &g, int wbits, int abits, bool fuse, hipStream_t st);
+
 __device__ __forceinline__ int popc_and4(const uint4 &a, const uint4 &b, int acc)
 {
     acc += __builtin_popcount(a.x & b.x);

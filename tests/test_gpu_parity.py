@@ -12,6 +12,12 @@ pytestmark = pytest.mark.gpu
 U, TC, BP = oracle.UNSIGNED, oracle.TWOS_COMPLEMENT, oracle.BIPOLAR
 
 
+def make_thr(rng, C, obits):
+    T = (1 << obits) - 1
+    lo, hi = int(C.min()) - 2, int(C.max()) + 3
+    return np.sort(rng.integers(lo, hi, size=(C.shape[0], T)), axis=1).astype(np.int32)
+
+
 # ------------------------------------------------------------------ S1 pack
 @pytest.mark.parametrize("rows,depth", [(1, 1), (3, 63), (5, 64), (7, 65), (64, 256), (130, 1000), (33, 4097)])
 @pytest.mark.parametrize("bits,fmt", [(1, U), (2, U), (4, U), (2, TC), (3, TC), (4, TC), (1, BP)])
@@ -69,6 +75,24 @@ def test_gemm_shapes(M, K, N, w, wf, a, af):
     assert_equal(run_gemm(W, A, w, wf, a, af), oracle.gemm(W, A), "gemm %dx%dx%d" % (M, K, N))
 
 
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("M,K", [(1, 1), (7, 64), (8, 130), (9, 1000), (100, 9216), (333, 4100)])
+@pytest.mark.parametrize("w,wf,a,af,obits", [(1, BP, 2, U, 2), (4, TC, 4, U, 4), (2, U, 3, TC, 1), (3, TC, 1, U, 3),
+                                             (1, U, 1, BP, 2)])
+def test_few_column_path(N, M, K, w, wf, a, af, obits):
+    """N <= 4 takes the streaming (GEMV) kernel; N = 5 and bipolar activations the tiled one."""
+    rng = np.random.default_rng(N * 100 + M + K + w)
+    W, A = draw(rng, (M, K), w, wf), draw(rng, (K, N), a, af)
+    want = oracle.gemm(W, A)
+    assert_equal(run_gemm(W, A, w, wf, a, af), want, "gemv int32")
+    thr = make_thr(rng, want, obits)
+    Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
+    Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
+    out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
+    bs.bs_gemm_threshold(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits, out=out)
+    assert_equal(planes_to_numpy(out), oracle.threshold_pack(want, thr, obits), "gemv fused")
+
+
 def test_gemm_extreme_values_and_ldc():
     M, K, N = 66, 640, 50
     for w, a in [(2, 2), (4, 4)]:
@@ -87,12 +111,6 @@ def test_gemm_extreme_values_and_ldc():
 
 
 # ------------------------------------------------------------------ S5 threshold
-def make_thr(rng, C, obits):
-    T = (1 << obits) - 1
-    lo, hi = int(C.min()) - 2, int(C.max()) + 3
-    return np.sort(rng.integers(lo, hi, size=(C.shape[0], T)), axis=1).astype(np.int32)
-
-
 @pytest.mark.parametrize("M,N", [(1, 1), (64, 64), (70, 45), (129, 300), (300, 2), (4096, 1)])
 @pytest.mark.parametrize("obits", [1, 2, 3, 4])
 def test_threshold_activate(M, N, obits):
