@@ -51,12 +51,24 @@ constexpr size_t kGemvMaxLds = 64 * 1024;
 bool gemv_applicable(const GemmParams &g, int abits, bool a_bipolar);
 bs_status launch_gemv(const GemmParams &g, int wbits, int abits, bool fuse, hipStream_t st);
 
+// acc + popcount(x) in ONE instruction: v_bcnt_u32_b32 adds its second operand for
+// free.  Written as inline assembly because the optimiser otherwise re-associates a sum
+// of popcounts into a tree and pays separate adds for it (25 % more VALU work in the
+// inner loop).  Not volatile: the scheduler may move and interleave it freely.
+__device__ __forceinline__ int bcnt_acc(uint32_t x, int acc)
+{
+    int r;
+    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(acc));
+    return r;
+}
+
+// Alg. 1's inner statement on one 16-byte chunk: acc += popcount(a & b) over 4 dwords.
 __device__ __forceinline__ int popc_and4(const uint4 &a, const uint4 &b, int acc)
 {
-    acc += __builtin_popcount(a.x & b.x);
-    acc += __builtin_popcount(a.y & b.y);
-    acc += __builtin_popcount(a.z & b.z);
-    acc += __builtin_popcount(a.w & b.w);
+    acc = bcnt_acc(a.x & b.x, acc);
+    acc = bcnt_acc(a.y & b.y, acc);
+    acc = bcnt_acc(a.z & b.z, acc);
+    acc = bcnt_acc(a.w & b.w, acc);
     return acc;
 }
 
