@@ -34,6 +34,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run plain 256 MiB device copies, so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                         "readings can be scaled by what the same counter reports for a copy of known size")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding "
@@ -66,6 +69,14 @@ def main() -> int:
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3 / iters
         return e0.elapsed_time(e1) / iters, wall
+
+    if args.calibration_copy:
+        src = torch.full((256 << 20,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ------------------------------------------------------------- headline: W2A2 4096^3
     M = N = K = 4096

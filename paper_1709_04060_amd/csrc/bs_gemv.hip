@@ -3,67 +3,40 @@
 // bit is read exactly once and used for N <= 4 columns, so the kernel is a stream over
 // the packed weight planes bound by HBM, not by popcount throughput.
 //
-// Shape: one wavefront per workgroup, eight rows per wavefront, eight lanes per row.
-// The eight lanes of a row read consecutive 16-byte chunks (one full 128-byte line per
-// load and row) and stride over the depth; the activation planes sit in LDS, read with
-// broadcast.  Several loads per lane are issued before the first use so that enough
-// bytes are in flight.  The eight partial sums of a row are combined with lane
+// Shape: a workgroup of four wavefronts owns eight rows (one output byte per plane and
+// column); 32 lanes share a row and read consecutive 16-byte chunks, so one load
+// instruction of a wavefront covers two 512-byte runs.  The weight stream is started
+// before anything else; the (small) activation planes are then copied to LDS, where all
+// rows read them with broadcast.  The 32 partial sums of a row are combined with lane
 // exchanges; the row leaders apply the plane-pair weights (Alg. 2), the bipolar
-// correction and, if asked, successive thresholding, and a ballot turns the eight
-// results into one output byte per plane and column.
+// correction and, if asked, successive thresholding; the eight results of the workgroup
+// meet in LDS and leave as one byte per plane and column.
 #include "bs_gemm_kernel.h"
 
 namespace bs {
 namespace {
 
-constexpr int ROWS_PER_WAVE = 8;   // also the bits of one output byte
-constexpr int LANES_PER_ROW = 8;
-constexpr int UNROLL = 4;          // chunks per lane and plane in flight
+constexpr int ROWS_PER_BLOCK = 8;   // also the bits of one output byte
+constexpr int LANES_PER_ROW = 32;
+constexpr int GEMV_THREADS = ROWS_PER_BLOCK * LANES_PER_ROW;
+constexpr int UNROLL = 4;           // chunks per lane and plane fetched in one go
 
 template <int WB, int AB, int NC, bool FUSE>
-__global__ void __launch_bounds__(64) bs_gemv_kernel(const GemmParams p)
+__global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams p)
 {
     extern __shared__ uint4 ldsA[];  // [AB][NC][nch]
-    const int lane = threadIdx.x;
+    __shared__ int colsum_s[NC];
+    __shared__ int yrow[ROWS_PER_BLOCK][NC];
+    const int tid = threadIdx.x;
     const int nch = p.Kd >> 2;       // 16-byte chunks per packed row
 
-    // ---- activation planes -> LDS, and their weighted popcounts (bipolar weights) ----
-    int colsum[NC];
-#pragma unroll
-    for (int n = 0; n < NC; ++n) colsum[n] = 0;
-    {
-        const uint4 *Ag = reinterpret_cast<const uint4 *>(p.A);
-        const int total = AB * NC * nch;
-        for (int id = lane; id < total; id += 64) {
-            const int c = id % nch, jn = id / nch;
-            const int n = jn % NC, j = jn / NC;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (n < p.N) v = Ag[(size_t)(j * p.N + n) * nch + c];
-            ldsA[id] = v;
-            const int pc = popc4(v) * p.ccol[j];
-#pragma unroll
-            for (int nn = 0; nn < NC; ++nn) colsum[nn] += (nn == n) ? pc : 0;
-        }
-#pragma unroll
-        for (int n = 0; n < NC; ++n)
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) colsum[n] += __shfl_xor(colsum[n], o);
-    }
-    __syncthreads();
-
-    const int g = lane & (LANES_PER_ROW - 1), r = lane / LANES_PER_ROW;
-    const int m = blockIdx.x * ROWS_PER_WAVE + r;
+    const int g = tid & (LANES_PER_ROW - 1), r = tid / LANES_PER_ROW;
+    const int m = blockIdx.x * ROWS_PER_BLOCK + r;
     const bool mvalid = m < p.M;
     const uint4 *Wg = reinterpret_cast<const uint4 *>(p.W);
 
-    int acc[WB * AB][NC];
-#pragma unroll
-    for (int q = 0; q < WB * AB; ++q)
-#pragma unroll
-        for (int n = 0; n < NC; ++n) acc[q][n] = 0;
-
-    for (int c0 = g; c0 < nch; c0 += LANES_PER_ROW * UNROLL) {
-        uint4 w[UNROLL][WB];
+    uint4 w[UNROLL][WB];
+    auto fetch_w = [&](int c0) {
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int c = c0 + u * LANES_PER_ROW;
@@ -73,6 +46,57 @@ __global__ void __launch_bounds__(64) bs_gemv_kernel(const GemmParams p)
                 if (mvalid && c < nch) w[u][i] = Wg[(size_t)(i * p.M + m) * nch + c];
             }
         }
+    };
+    fetch_w(g);  // the weight stream starts first; the activation fill below overlaps with it
+    // Row leaders fetch their thresholds now as well, so that the epilogue does not wait
+    // for a second round trip to memory.
+    int32_t thv[FUSE ? 15 : 1];
+    if constexpr (FUSE) {
+#pragma unroll
+        for (int t = 0; t < 15; ++t) {
+            thv[t] = 0x7fffffff;
+            if (g == 0 && mvalid && t < p.T) thv[t] = p.thr[(long long)m * p.T + t];
+        }
+    }
+
+    // ---- activation planes -> LDS, and their weighted popcounts (bipolar weights) ----
+    if (tid < NC) colsum_s[tid] = 0;
+    __syncthreads();
+    {
+        int colsum[NC];
+#pragma unroll
+        for (int n = 0; n < NC; ++n) colsum[n] = 0;
+        const uint4 *Ag = reinterpret_cast<const uint4 *>(p.A);
+        const int total = AB * NC * nch;
+        for (int id = tid; id < total; id += GEMV_THREADS) {
+            const int c = id % nch, jn = id / nch;
+            const int n = jn % NC, j = jn / NC;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (n < p.N) v = Ag[(size_t)(j * p.N + n) * nch + c];
+            ldsA[id] = v;
+            const int pc = popc4(v) * p.ccol[j];
+#pragma unroll
+            for (int nn = 0; nn < NC; ++nn) colsum[nn] += (nn == n) ? pc : 0;
+        }
+        if (p.ccol[0] != 0) {  // only a bipolar weight operand needs the column term
+#pragma unroll
+            for (int n = 0; n < NC; ++n) {
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) colsum[n] += __shfl_xor(colsum[n], o);
+                if ((tid & 63) == 0) atomicAdd(&colsum_s[n], colsum[n]);
+            }
+        }
+    }
+    __syncthreads();
+
+    int acc[WB * AB][NC];
+#pragma unroll
+    for (int q = 0; q < WB * AB; ++q)
+#pragma unroll
+        for (int n = 0; n < NC; ++n) acc[q][n] = 0;
+
+    for (int c0 = g; c0 < nch; c0 += LANES_PER_ROW * UNROLL) {
+        if (c0 != g) fetch_w(c0);
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int c = c0 + u * LANES_PER_ROW;
@@ -100,7 +124,7 @@ __global__ void __launch_bounds__(64) bs_gemv_kernel(const GemmParams p)
             for (int j = 0; j < AB; ++j) v += p.coef[i * 4 + j] * acc[i * AB + j][n];
 #pragma unroll
         for (int o = LANES_PER_ROW / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
-        val[n] = v + colsum[n];
+        val[n] = v + colsum_s[n];
     }
     const bool leader = (g == 0) && mvalid;
 
@@ -113,32 +137,37 @@ __global__ void __launch_bounds__(64) bs_gemv_kernel(const GemmParams p)
     } else {
         uint8_t *Yb = reinterpret_cast<uint8_t *>(p.Y);
         const long long col_bytes = (long long)p.Yd * 4;
-        int y[NC];
+        if (g == 0) {
+            int y[NC];
 #pragma unroll
-        for (int n = 0; n < NC; ++n) y[n] = 0;
-        if (leader) {
-            const int32_t *th = p.thr + (long long)m * p.T;
-            for (int t = 0; t < p.T; ++t) {
-                const int32_t tv = th[t];
+            for (int n = 0; n < NC; ++n) y[n] = 0;
+            if (mvalid) {
 #pragma unroll
-                for (int n = 0; n < NC; ++n) y[n] += (val[n] >= tv) ? 1 : 0;
-            }
-        }
-        for (int pl = 0; pl < p.obits; ++pl) {
+                for (int t = 0; t < 15; ++t) {
+                    if (t < p.T) {
 #pragma unroll
-            for (int n = 0; n < NC; ++n) {
-                if (n < p.N) {
-                    // leaders sit at lanes 0, 8, ..., 56: gather those eight bits into a byte
-                    const unsigned long long mask = __ballot(leader && ((y[n] >> pl) & 1));
-                    const unsigned byte = (unsigned)((mask * 0x0102040810204080ull) >> 56);
-                    if (lane == 0) Yb[((long long)pl * p.N + n) * col_bytes + blockIdx.x] = (uint8_t)byte;
+                        for (int n = 0; n < NC; ++n) y[n] += (val[n] >= thv[t]) ? 1 : 0;
+                    }
                 }
+            }
+#pragma unroll
+            for (int n = 0; n < NC; ++n) yrow[r][n] = y[n];
+        }
+        __syncthreads();
+        // thread (pl, n) assembles the byte of plane pl, column n from the eight rows
+        if (tid < p.obits * NC) {
+            const int pl = tid / NC, n = tid % NC;
+            if (n < p.N) {
+                unsigned byte = 0;
+#pragma unroll
+                for (int rr = 0; rr < ROWS_PER_BLOCK; ++rr) byte |= ((yrow[rr][n] >> pl) & 1u) << rr;
+                Yb[((long long)pl * p.N + n) * col_bytes + blockIdx.x] = (uint8_t)byte;
             }
         }
         // the last workgroup clears the padding bytes of every column
         if (blockIdx.x == gridDim.x - 1) {
             const int first = gridDim.x, npad = (int)col_bytes - first;
-            for (int it = lane; it < npad * p.obits * p.N; it += 64) {
+            for (int it = tid; it < npad * p.obits * p.N; it += GEMV_THREADS) {
                 const int z = it % npad, cn = it / npad;
                 Yb[(long long)cn * col_bytes + first + z] = 0;
             }
@@ -149,9 +178,9 @@ __global__ void __launch_bounds__(64) bs_gemv_kernel(const GemmParams p)
 template <int WB, int AB, int NC>
 bs_status launch_gemv_nc(const GemmParams &g, bool fuse, size_t lds_bytes, hipStream_t st)
 {
-    dim3 grid((unsigned)((g.M + ROWS_PER_WAVE - 1) / ROWS_PER_WAVE));
-    if (fuse) bs_gemv_kernel<WB, AB, NC, true><<<grid, 64, lds_bytes, st>>>(g);
-    else bs_gemv_kernel<WB, AB, NC, false><<<grid, 64, lds_bytes, st>>>(g);
+    dim3 grid((unsigned)((g.M + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK));
+    if (fuse) bs_gemv_kernel<WB, AB, NC, true><<<grid, GEMV_THREADS, lds_bytes, st>>>(g);
+    else bs_gemv_kernel<WB, AB, NC, false><<<grid, GEMV_THREADS, lds_bytes, st>>>(g);
     return after_launch();
 }
 
