@@ -20,6 +20,14 @@
 // each lane holding a TM x TN block of int32 accumulators; per 16-byte chunk it reads
 // TM weight rows and TN activation columns per plane from LDS and issues
 // v_and_b32 + v_bcnt_u32_b32 (whose add operand makes the accumulation free).
+// Small output grids use 32 x 32 tiles whose four wavefronts split each stage's depth
+// among themselves (KS = 4) and add their partial sums in LDS, so that enough
+// wavefronts exist to fill 1024 SIMDs.
+//
+// Workgroups are dealt round-robin to the chip's 8 XCDs, each with its own L2.  For
+// large grids the linear workgroup index is therefore mapped so that every XCD owns one
+// compact rectangle of the tile grid and pulls only that rectangle's weight rows and
+// activation columns through its L2.
 #pragma once
 #include "bs_common.h"
 
@@ -43,6 +51,10 @@ struct GemmParams {
     int T, obits;
     uint32_t *Y;        // dword view of Yp
     int Yd;             // dwords per column of Yp (2 * S_M)
+    // tile grid and its mapping onto the linear workgroup index (see tile_of_block)
+    int gx, gy;         // tiles along N and along M
+    int rx, ry;         // XCD regions along N and M (rx * ry == 8), or 0 = plain row-major order
+    int hx, hy;         // tiles per region along N and M
 };
 
 // GEMV path (bs_gemv.hip): used for at most this many columns, activation planes in LDS.
@@ -77,30 +89,54 @@ __device__ __forceinline__ int popc4(const uint4 &a)
     return __builtin_popcount(a.x) + __builtin_popcount(a.y) + __builtin_popcount(a.z) + __builtin_popcount(a.w);
 }
 
+// Tile owned by workgroup `bid`.  Returns false for the (few) surplus workgroups of
+// the XCD-aware layout.
+__device__ __forceinline__ bool tile_of_block(const GemmParams &p, int bid, int &tm, int &tn)
+{
+    if (p.rx == 0) {
+        tm = bid / p.gx;
+        tn = bid - tm * p.gx;
+        return true;
+    }
+    const int xcd = bid & 7, local = bid >> 3;
+    const int ry = xcd / p.rx, rx = xcd - ry * p.rx;
+    const int ly = local / p.hx, lx = local - ly * p.hx;
+    tm = ry * p.hy + ly;
+    tn = rx * p.hx + lx;
+    return ly < p.hy && tm < p.gy && tn < p.gx;
+}
+
 // WB, AB: weight / activation planes.  TM x TN: accumulators per lane.  WM x WN:
-// wavefronts per workgroup.  FUSE: thresholding epilogue instead of the int32 store.
-// CORR: popcount correction terms needed (some operand is bipolar).
-template <int WB, int AB, int TM, int TN, int WM, int WN, bool FUSE, bool CORR>
-__global__ void __launch_bounds__(WM * WN * 64)
+// wavefronts across the tile, KS: wavefronts across the depth of each stage.  FUSE:
+// thresholding epilogue instead of the int32 store.  CORR: popcount correction terms
+// needed (some operand is bipolar).
+template <int WB, int AB, int TM, int TN, int WM, int WN, int KS, bool FUSE, bool CORR>
+__global__ void __launch_bounds__(WM * WN * KS * 64)
 bs_gemm_kernel(const GemmParams p)
 {
-    constexpr int BM = 8 * TM * WM, BN = 8 * TN * WN, NT = 64 * WM * WN;
+    constexpr int BM = 8 * TM * WM, BN = 8 * TN * WN, NT = 64 * WM * WN * KS;
     constexpr int WROWS = WB * BM, AROWS = AB * BN, ROWS = WROWS + AROWS;
     constexpr int CHUNKS = ROWS * KCH;
     constexpr int CPT = (CHUNKS + NT - 1) / NT;  // chunks each thread moves per stage
     constexpr int PAIRS = WB * AB;
     constexpr bool PER_PAIR = PAIRS <= 4;        // one accumulator set per plane pair
     constexpr int NACC = PER_PAIR ? PAIRS : 1;
+    static_assert(KCH % KS == 0, "the depth split must divide the chunks of a stage");
+    static_assert((KS > 1 ? 5 : 1) * BM * BN <= CHUNKS * 16, "epilogue staging must fit in the tile space");
 
     __shared__ uint4 lds[CHUNKS];
     __shared__ int corr_row[CORR ? BM : 1];
     __shared__ int corr_col[CORR ? BN : 1];
 
+    int tile_m, tile_n;
+    if (!tile_of_block(p, blockIdx.x, tile_m, tile_n)) return;  // uniform for the workgroup
+
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int ly = lane >> 3, lx = lane & 7;
-    const int wm = wave / WN, wn = wave % WN;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int ks = wave / (WM * WN), wq = wave % (WM * WN);
+    const int wm = wq / WN, wn = wq % WN;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     // ---- loader set-up: which chunk of which stacked row this thread moves ----
     int goff[CPT];    // dword offset into W or A of the chunk at stage 0, -1 if out of range
@@ -173,7 +209,8 @@ bs_gemm_kernel(const GemmParams p)
 
         if constexpr (PER_PAIR) {
 #pragma unroll
-            for (int q = 0; q < KCH; ++q) {
+            for (int qq = 0; qq < KCH / KS; ++qq) {
+                const int q = qq * KS + ks;
                 uint4 w[WB][TM], a[AB][TN];
 #pragma unroll
                 for (int i = 0; i < WB; ++i)
@@ -206,7 +243,8 @@ bs_gemm_kernel(const GemmParams p)
 #pragma unroll
                         for (int c = 0; c < TN; ++c) t[r][c] = 0;
 #pragma unroll
-                    for (int q = 0; q < KCH; ++q) {
+                    for (int qq = 0; qq < KCH / KS; ++qq) {
+                        const int q = qq * KS + ks;
                         uint4 w[TM], a[TN];
 #pragma unroll
                         for (int r = 0; r < TM; ++r) w[r] = ldsW[(i * BM + r) * KCH + (q ^ ly)];
@@ -241,7 +279,7 @@ bs_gemm_kernel(const GemmParams p)
     }
     __syncthreads();  // also: all LDS tile reads are finished, the tile space may be reused
 
-    // ---- epilogue: weight the plane pairs (Alg. 2), add corrections ----
+    // ---- weight the plane pairs (Alg. 2) ----
     int val[TM][TN];
 #pragma unroll
     for (int r = 0; r < TM; ++r)
@@ -257,50 +295,83 @@ bs_gemm_kernel(const GemmParams p)
             } else {
                 v = acc[0][r][c];
             }
-            if (CORR) v += corr_row[wrow0 + r] + corr_col[acol0 + c] + p.c0;
             val[r][c] = v;
         }
 
+    // ---- depth split: the KS wavefronts of an output block add their parts in LDS ----
+    if constexpr (KS > 1) {
+        int *ctile = reinterpret_cast<int *>(lds);  // [BM][BN]
+        if (ks == 0) {
+#pragma unroll
+            for (int r = 0; r < TM; ++r)
+#pragma unroll
+                for (int c = 0; c < TN; ++c) ctile[(wrow0 + r) * BN + acol0 + c] = val[r][c];
+        }
+        __syncthreads();
+        if (ks != 0) {
+#pragma unroll
+            for (int r = 0; r < TM; ++r)
+#pragma unroll
+                for (int c = 0; c < TN; ++c) atomicAdd(&ctile[(wrow0 + r) * BN + acol0 + c], val[r][c]);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < TM; ++r)
+#pragma unroll
+            for (int c = 0; c < TN; ++c) val[r][c] = ctile[(wrow0 + r) * BN + acol0 + c];
+    }
+    const bool writer = (ks == 0);
+
+    if (CORR) {
+#pragma unroll
+        for (int r = 0; r < TM; ++r)
+#pragma unroll
+            for (int c = 0; c < TN; ++c) val[r][c] += corr_row[wrow0 + r] + corr_col[acol0 + c] + p.c0;
+    }
+
     if constexpr (!FUSE) {
         const bool vec_ok = (TN % 4 == 0) && ((p.ldc & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.C) & 15) == 0);
+        if (writer) {
 #pragma unroll
-        for (int r = 0; r < TM; ++r) {
-            const int m = m0 + wrow0 + r;
-            if (m >= p.M) continue;
-            int32_t *crow = p.C + (long long)m * p.ldc;
-            const int n = n0 + acol0;
-            if (vec_ok && n + TN <= p.N) {
+            for (int r = 0; r < TM; ++r) {
+                const int m = m0 + wrow0 + r;
+                if (m >= p.M) continue;
+                int32_t *crow = p.C + (long long)m * p.ldc;
+                const int n = n0 + acol0;
+                if (vec_ok && n + TN <= p.N) {
 #pragma unroll
-                for (int c = 0; c < TN; c += 4)
-                    *reinterpret_cast<int4 *>(crow + n + c) =
-                        make_int4(val[r][c], val[r][c + 1], val[r][c + 2], val[r][c + 3]);
-            } else {
+                    for (int c = 0; c < TN; c += 4)
+                        *reinterpret_cast<int4 *>(crow + n + c) =
+                            make_int4(val[r][c], val[r][c + 1], val[r][c + 2], val[r][c + 3]);
+                } else {
 #pragma unroll
-                for (int c = 0; c < TN; ++c)
-                    if (n + c < p.N) crow[n + c] = val[r][c];
+                    for (int c = 0; c < TN; ++c)
+                        if (n + c < p.N) crow[n + c] = val[r][c];
+                }
             }
         }
     } else {
         // Successive thresholding: count the thresholds reached, stage the few-bit
         // results as bytes in LDS ([column][row]), then pack along the rows.
         static_assert(BM % 32 == 0, "packed output is written in 32-bit words");
-        uint8_t *ytile = reinterpret_cast<uint8_t *>(lds);  // BN * BM bytes <= tile space
-        static_assert(BN * BM <= CHUNKS * 16, "epilogue staging must fit in the tile space");
+        uint8_t *ytile = reinterpret_cast<uint8_t *>(lds) + (KS > 1 ? BM * BN * 4 : 0);
+        if (writer) {
 #pragma unroll
-        for (int r = 0; r < TM; ++r) {
-            const int m = m0 + wrow0 + r;
-            const int32_t *th = p.thr + (long long)m * p.T;
+            for (int r = 0; r < TM; ++r) {
+                const int m = m0 + wrow0 + r;
+                const int32_t *th = p.thr + (long long)m * p.T;
 #pragma unroll
-            for (int c = 0; c < TN; ++c) {
-                int y = 0;
-                if (m < p.M)
-                    for (int t = 0; t < p.T; ++t) y += (val[r][c] >= th[t]) ? 1 : 0;
-                ytile[(acol0 + c) * BM + wrow0 + r] = (uint8_t)y;
+                for (int c = 0; c < TN; ++c) {
+                    int y = 0;
+                    if (m < p.M)
+                        for (int t = 0; t < p.T; ++t) y += (val[r][c] >= th[t]) ? 1 : 0;
+                    ytile[(acol0 + c) * BM + wrow0 + r] = (uint8_t)y;
+                }
             }
         }
         __syncthreads();
         constexpr int WPC = BM / 32;  // output dwords per column and plane in this tile
-        const int last_m_block = (blockIdx.y == gridDim.y - 1);
+        const bool last_m_block = (tile_m == p.gy - 1);
         for (int it = tid; it < BN * WPC; it += NT) {
             const int col = it / WPC, wi = it % WPC;
             const int n = n0 + col;
@@ -328,23 +399,53 @@ bs_gemm_kernel(const GemmParams p)
     }
 }
 
-template <int WB, int AB, int TM, int TN, int WM, int WN>
-bs_status launch_cfg(const GemmParams &g, bool fuse, bool corr, hipStream_t st)
+// ---------------------------------------------------------------- launch helpers (host)
+
+// Chooses how the tile grid is laid over the 8 XCDs: each gets a compact hy x hx
+// rectangle (ry x rx rectangles in all) when the grid is large enough for that to waste
+// few workgroups; otherwise plain row-major order.  Returns the number of workgroups.
+inline long long plan_tile_order(GemmParams &g, int BM, int BN, int wbits, int abits)
+{
+    g.gx = (g.N + BN - 1) / BN;
+    g.gy = (g.M + BM - 1) / BM;
+    g.rx = g.ry = g.hx = g.hy = 0;
+    const long long total = (long long)g.gx * g.gy;
+    long long best_cost = -1, best_blocks = total;
+    const int opts[4][2] = {{4, 2}, {2, 4}, {8, 1}, {1, 8}};  // {ry, rx}
+    for (const auto &o : opts) {
+        const int ry = o[0], rx = o[1];
+        if (g.gy < 2 * ry || g.gx < 2 * rx) continue;
+        const int hy = (g.gy + ry - 1) / ry, hx = (g.gx + rx - 1) / rx;
+        const long long blocks = 8LL * hy * hx;
+        if (blocks * 8 > total * 9) continue;                 // more than 12.5 % surplus workgroups
+        const long long cost = (long long)wbits * BM * hy + (long long)abits * BN * hx;  // bytes per XCD ~
+        if (best_cost < 0 || cost < best_cost) {
+            best_cost = cost; best_blocks = blocks;
+            g.ry = ry; g.rx = rx; g.hy = hy; g.hx = hx;
+        }
+    }
+    return best_blocks;
+}
+
+template <int WB, int AB, int TM, int TN, int WM, int WN, int KS>
+bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, hipStream_t st)
 {
     constexpr int BM = 8 * TM * WM, BN = 8 * TN * WN;
-    dim3 grid((unsigned)((g.N + BN - 1) / BN), (unsigned)((g.M + BM - 1) / BM));
-    if (grid.y > 65535) return BS_ERR_UNSUPPORTED;
-    dim3 block(WM * WN * 64);
+    GemmParams g = g_in;
+    const long long blocks = plan_tile_order(g, BM, BN, WB, AB);
+    if (blocks >= (1LL << 31)) return BS_ERR_UNSUPPORTED;
+    dim3 grid((unsigned)blocks);
+    dim3 block(WM * WN * KS * 64);
     // A bipolar operand has exactly one plane, so the correction variant only exists
     // where WB == 1 or AB == 1.
     constexpr bool CAN_CORR = (WB == 1 || AB == 1);
     if (corr && !CAN_CORR) return BS_ERR_INVALID_ARG;
     if (fuse) {
-        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, true, CAN_CORR><<<grid, block, 0, st>>>(g);
-        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, true, false><<<grid, block, 0, st>>>(g);
+        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, true, CAN_CORR><<<grid, block, 0, st>>>(g);
+        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, true, false><<<grid, block, 0, st>>>(g);
     } else {
-        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, false, CAN_CORR><<<grid, block, 0, st>>>(g);
-        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, false, false><<<grid, block, 0, st>>>(g);
+        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, false, CAN_CORR><<<grid, block, 0, st>>>(g);
+        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, false, false><<<grid, block, 0, st>>>(g);
     }
     return bs::after_launch();
 }
@@ -352,11 +453,11 @@ bs_status launch_cfg(const GemmParams &g, bool fuse, bool corr, hipStream_t st)
 template <int WB, int AB>
 bs_status launch_planes(const GemmParams &g, bool fuse, bool corr, hipStream_t st)
 {
-    // Small problems get 32 x 32 tiles (one wavefront per workgroup) so that more
-    // compute units have work; everything else 64 x 64 with four wavefronts.
+    // Large grids: 64 x 64 tiles, four wavefronts side by side.  Small grids: 32 x 32
+    // tiles whose four wavefronts split the depth, so that more wavefronts exist.
     const long long tiles64 = (long long)((g.M + 63) / 64) * ((g.N + 63) / 64);
-    if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1>(g, fuse, corr, st);
-    return launch_cfg<WB, AB, 4, 4, 2, 2>(g, fuse, corr, st);
+    if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4>(g, fuse, corr, st);
+    return launch_cfg<WB, AB, 4, 4, 2, 2, 1>(g, fuse, corr, st);
 }
 
 // Defined once per WB in bs_gemm_w<WB>.hip (explicit instantiation) to keep builds parallel.
@@ -370,6 +471,5 @@ bs_status launch_wb(const GemmParams &g, int abits, bool fuse, bool corr, hipStr
     default: return launch_planes<WB, 4>(g, fuse, corr, st);
     }
 }
-
 
 }  // namespace bs
