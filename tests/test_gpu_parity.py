@@ -32,6 +32,36 @@ def test_pack_rows_and_cols(rows, depth, bits, fmt, dtype):
     assert_equal(planes_to_numpy(got_t), want, "pack depth-strided")
 
 
+@pytest.mark.parametrize("rows,depth", [(4, 64), (132, 1008), (260, 2064), (128, 1024), (516, 80), (1024, 4096)])
+@pytest.mark.parametrize("bits,fmt", [(1, U), (2, U), (4, U), (2, TC), (4, TC), (1, BP)])
+@pytest.mark.parametrize("dtype", [np.int8, np.int32])
+def test_pack_aligned_fast_paths(rows, depth, bits, fmt, dtype):
+    """Shapes whose leading dimensions allow the vectorised kernels, with partial last
+    words and partial row tiles; plus a sliced source whose last quad of rows is incomplete."""
+    rng = np.random.default_rng(rows + depth + bits)
+    X = draw(rng, (rows, depth), bits, fmt).astype(dtype)
+    want = oracle.pack(X, bits, fmt)
+    assert_equal(planes_to_numpy(bs.bs_pack_planes(dev(X), bits, FMT[fmt])), want, "fast pack rows")
+    assert_equal(planes_to_numpy(bs.bs_pack_planes(dev(X.T.copy()), bits, FMT[fmt], depth_is_strided=True)), want,
+                 "fast pack cols")
+    sub = dev(X.T.copy())[:, : rows - 2]          # rows - 2 columns of a [depth][rows] buffer: ld stays aligned
+    assert_equal(planes_to_numpy(bs.bs_pack_planes(sub, bits, FMT[fmt], depth_is_strided=True)),
+                 oracle.pack(X[: rows - 2], bits, fmt), "fast pack cols, incomplete quad")
+
+
+def test_pack_out_of_range_values_follow_the_documented_reduction():
+    """Values outside the format's range keep their low bits; bipolar packs v > 0 as +1."""
+    X = np.array([[-128, -3, -1, 0, 1, 2, 5, 127] * 8], dtype=np.int8)
+    got = planes_to_numpy(bs.bs_pack_planes(dev(X), 1, bs.BS_BIPOLAR))
+    want_bits = (X[0] > 0).astype(np.uint64)
+    assert int(got[0, 0, 0]) == int(sum(int(b) << i for i, b in enumerate(want_bits)))
+    got2 = planes_to_numpy(bs.bs_pack_planes(dev(X), 2, bs.BS_UNSIGNED))
+    for p in range(2):
+        assert int(got2[p, 0, 0]) == int(sum(((int(v) >> p) & 1) << i for i, v in enumerate(X[0].astype(np.int64) & 3)))
+    got3 = planes_to_numpy(bs.bs_pack_planes(dev(X.T.copy()), 1, bs.BS_BIPOLAR, depth_is_strided=True))
+    assert int(got3[0, 0, 0]) == int(got[0, 0, 0])
+
+
 def test_pack_respects_leading_dimension_and_overwrites_padding():
     rng = np.random.default_rng(11)
     big = draw(rng, (40, 300), 2, U)
