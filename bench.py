@@ -25,6 +25,9 @@ CUS, LANES_PER_CU_CLK, CLOCK_HZ = 256, 64, 2.4e9
 VALU_LANE_OPS = CUS * LANES_PER_CU_CLK * CLOCK_HZ            # 32-bit integer lane-ops / s
 BINARY_PEAK_TOPS = VALU_LANE_OPS / 2 * 32 * 2 / 1e12           # one AND + one BCNT per 32 binary MACs, 2 ops / MAC
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per bs_gemm launch on the W2A2 4096^3 workload, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE scaled by a 256 MiB copy (profiles/pmc_fetch_write_w2a2_4096.md): 24.5 MiB + 64 MiB
+GEMM_TRAFFIC_BYTES = int((12544.4 * 2.0 + 65536.0) * 1024)
 
 
 def main() -> int:
@@ -118,17 +121,19 @@ def main() -> int:
                                "GEMM to int32; weights pre-packed", "M": M, "N": N, "K": K, "wbits": w, "abits": a},
         "roofline": {"bound": "alu", "kernel": "bs_gemm_kernel<2,2,...>", "achieved": round(binary_tops, 1),
                      "peak": round(BINARY_PEAK_TOPS, 1), "unit": "binary TOP/s", "frac": round(binary_tops / BINARY_PEAK_TOPS, 4),
-                     "kernel_ms": round(gemm_ms, 4), "traffic": None},
+                     "kernel_ms": round(gemm_ms, 4), "traffic": GEMM_TRAFFIC_BYTES,
+                     "algorithmic_bytes": 2 * (w * M * K // 8) // 1 + 4 * M * N},
         "breakdown_ms": {"pack_activations": round(pack_ms, 4), "bs_gemm": round(gemm_ms, 4)},
     }
 
     # ------------------------------------------------------------- CPU oracle on the host cores
     if not args.no_cpu_baseline:
-        reps = 3
         oracle.gemm(d["W"][:64], d["A"])
         t0 = time.perf_counter()
-        for _ in range(reps):
+        reps = 0
+        while reps < 3 or time.perf_counter() - t0 < 10.0:
             oracle.gemm(d["W"], d["A"])
+            reps += 1
         dt = (time.perf_counter() - t0) / reps
         result["cpu_baseline"] = {"value": round(2.0 * M * N * K / dt / 1e9, 1), "unit": "GOPS",
                                   "cores": oracle.num_threads(), "kind": "oracle",
@@ -143,6 +148,33 @@ def main() -> int:
     return 0
 
 
+def timed_graph(fn_list, reps):
+    """Average time per call with the calls of `fn_list` (distinct closures, run round-robin)
+    captured `reps` times into one HIP graph and replayed: this takes the host's launch
+    overhead out of the timing of kernels that run for a few microseconds."""
+    import torch
+    for f in fn_list:
+        f()
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            for i in range(reps):
+                fn_list[i % len(fn_list)]()
+    torch.cuda.synchronize()
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    rounds = 5
+    e0.record()
+    for _ in range(rounds):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / (rounds * reps)
+
+
 def extras(bs, workloads, dev, timed):
     import torch
     out = {}
@@ -154,37 +186,48 @@ def extras(bs, workloads, dev, timed):
         T = (1 << obits) - 1
         return torch.sort(torch.randint(-1000, 1000, (Mrows, T), dtype=torch.int32, device="cuda"), dim=1)[0].contiguous()
 
-    def fused(name, w, wf, a, af, M, N, K, obits, copies=1):
-        # `copies` distinct weight buffers are cycled through so that the weights of a
-        # small layer do not simply sit in the last-level cache from the previous launch
+    def fused(name, w, wf, a, af, M, N, K, obits, copies=1, reps=None):
+        # `copies` distinct weight buffers are cycled through so that the weights of a small
+        # layer do not simply sit in the last-level cache (256 MB) from the previous launch
         Wps = [planes(w, M, K) for _ in range(copies)]
         Ap, th = planes(a, N, K), thr_for(M, obits)
         Y = torch.empty((obits, N, bs.bs_words_per_row(M)), dtype=torch.int64, device="cuda")
-        state = {"i": 0}
-
-        def f():
-            bs.bs_gemm_threshold(Wps[state["i"] % copies], wf, Ap, af, K, th, obits, out=Y)
-            state["i"] += 1
-        ms, _ = timed(f, max(20, 2 * copies), max(3, copies))
+        fns = [(lambda Wp=Wp: bs.bs_gemm_threshold(Wp, wf, Ap, af, K, th, obits, out=Y)) for Wp in Wps]
+        work = 2.0 * M * N * K
+        if work > 1e12:                       # long kernels: plain back-to-back launches
+            ms, _ = timed(fns[0], 10, 2)
+        else:
+            ms = timed_graph(fns, reps or max(2 * copies, 20))
         byts = (w * M + a * N) * bs.bs_words_per_row(K) * 8 + th.numel() * 4 + Y.numel() * 8
-        out[name] = {"us": round(ms * 1e3, 2), "GOPS": round(2.0 * M * N * K / ms / 1e6, 1),
-                     "binary_frac_of_valu_peak": round(w * a * 2.0 * M * N * K / (ms * 1e-3) / 1e12 / BINARY_PEAK_TOPS, 4),
+        out[name] = {"us": round(ms * 1e3, 2), "GOPS": round(work / ms / 1e6, 1),
+                     "frac_of_valu_popcount_peak": round(w * a * work / (ms * 1e-3) / 1e12 / BINARY_PEAK_TOPS, 4),
                      "GBps": round(byts / ms / 1e6, 1), "frac_of_hbm_peak": round(byts / ms / 1e6 / HBM_PEAK_GBS, 4),
-                     "weight_copies_cycled": copies}
+                     "weight_buffers_cycled": copies}
 
     BP, U, TC = bs.BS_BIPOLAR, bs.BS_UNSIGNED, bs.BS_TWOS_COMPLEMENT
     fused("fc6_W1A2_4096x9216x1_cold", 1, BP, 2, U, 4096, 1, 9216, 2, copies=64)
     fused("fc7_W1A2_4096x4096x1_cold", 1, BP, 2, U, 4096, 1, 4096, 2, copies=128)
     fused("fc6_W1A2_4096x9216x1_warm", 1, BP, 2, U, 4096, 1, 9216, 2, copies=1)
     fused("conv2_W1A2_256x2400x729", 1, BP, 2, U, 256, 729, 2400, 2)
-    for n in (1, 64, 1024, 8192):
-        fused("W4A4_8192x8192x%d" % n, 4, TC, 4, U, 8192, n, 8192, 4, copies=(10 if n == 1 else 1))
-    # interleaved lowering of conv2 alone
+    fused("W4A4_8192x8192x1_cold", 4, TC, 4, U, 8192, 1, 8192, 4, copies=10)
+    fused("W4A4_8192x8192x1_warm", 4, TC, 4, U, 8192, 1, 8192, 4, copies=1)
+    for n in (64, 1024, 8192):
+        fused("W4A4_8192x8192x%d" % n, 4, TC, 4, U, 8192, n, 8192, 4)
+    # a GEMV large enough that launch and first-byte latency stop mattering
+    fused("W1A2_32768x32768x1_cold", 1, BP, 2, U, 32768, 1, 32768, 2, copies=3, reps=12)
+    # interleaved lowering of conv2 alone, and the two pack kernels
     x = planes(2, 27 * 27, 96)
     low = torch.empty((2, 729, bs.bs_words_per_row(2400)), dtype=torch.int64, device="cuda")
-    ms, _ = timed(lambda: bs.bs_im2col_interleaved(x, 27, 27, 96, 5, 5, 1, 2, out=low), 50, 3)
+    ms = timed_graph([lambda: bs.bs_im2col_interleaved(x, 27, 27, 96, 5, 5, 1, 2, out=low)], 50)
     out["conv2_interleaved_lowering"] = {"us": round(ms * 1e3, 2),
                                          "GBps": round((low.numel() * 8 + x.numel() * 8) / ms / 1e6, 1)}
+    X = torch.randint(0, 4, (8192, 8192), dtype=torch.int8, device="cuda")
+    P = torch.empty((2, 8192, bs.bs_words_per_row(8192)), dtype=torch.int64, device="cuda")
+    for strided in (False, True):
+        ms = timed_graph([lambda: bs.bs_pack_planes(X, 2, U, depth_is_strided=strided, out=P)], 20)
+        byts = X.numel() + P.numel() * 8
+        out["pack_8192x8192_i8_to_2_planes_%s" % ("depth_strided" if strided else "depth_contiguous")] = {
+            "us": round(ms * 1e3, 2), "GBps": round(byts / ms / 1e6, 1), "frac_of_hbm_peak": round(byts / ms / 1e6 / HBM_PEAK_GBS, 4)}
     return out
 
 
