@@ -211,3 +211,20 @@ def im2col_plain(x: np.ndarray, KH: int, KW: int, stride: int, pad: int) -> np.n
     L = np.empty((KH * KW * C, OH * OW), dtype=np.int8)
     _load().oracle_im2col_plain(_p(x), _p(L), H, W, C, KH, KW, stride, pad)
     return L
+
+
+def maxpool(Y: np.ndarray, k: int, stride: int) -> np.ndarray:
+    """Max pooling of a few-bit activation map Y [H][W][C] by its definition: the largest
+    value in each k x k window, windows stride apart, no padding.  Thresholding is
+    monotone, so pooling the thresholded codes equals thresholding the pooled
+    accumulators; the paper keeps pooling outside its hot path (Sec. 4.2), here it joins
+    the packed layers into a chain.  [OH][OW][C], OH = (H - k) // stride + 1."""
+    Y = np.asarray(Y)
+    H, W, C = Y.shape
+    OH, OW = (H - k) // stride + 1, (W - k) // stride + 1
+    out = np.empty((OH, OW, C), dtype=Y.dtype)
+    for oh in range(OH):
+        for ow in range(OW):
+            win = Y[oh * stride: oh * stride + k, ow * stride: ow * stride + k, :]
+            out[oh, ow, :] = win.reshape(-1, C).max(axis=0)
+    return out

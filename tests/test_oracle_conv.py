@@ -56,3 +56,36 @@ def test_im2col_row_order_is_kh_kw_c():
     # column 0 = output pixel (0,0): taps (0,0),(0,1),(1,0),(1,1), channels fastest
     assert list(L[:, 0]) == [0, 1, 2, 3, 6, 7, 8, 9]
     assert list(L[:, 3]) == [8, 9, 10, 11, 14, 15, 16, 17]
+
+
+@pytest.mark.parametrize("H,W,C,k,s", [(27, 27, 5, 3, 2), (13, 13, 7, 3, 2), (8, 9, 3, 2, 2), (6, 6, 2, 3, 1)])
+def test_maxpool_against_library_filter(H, W, C, k, s):
+    """oracle.maxpool against numpy's sliding-window view and scipy's maximum_filter."""
+    from scipy.ndimage import maximum_filter
+    rng = np.random.default_rng(H + W + C)
+    Y = rng.integers(0, 4, size=(H, W, C)).astype(np.uint8)
+    got = oracle.maxpool(Y, k, s)
+    OH, OW = (H - k) // s + 1, (W - k) // s + 1
+    assert got.shape == (OH, OW, C)
+    view = np.lib.stride_tricks.sliding_window_view(Y, (k, k), axis=(0, 1))     # [H-k+1][W-k+1][C][k][k]
+    ref = view.max(axis=(-1, -2))[::s, ::s, :]
+    if k % 2 == 1:  # scipy's centred filter: window at centre i covers i - k//2 .. i + k//2
+        full = maximum_filter(Y, size=(k, k, 1), mode="constant", cval=0)
+        assert np.array_equal(full[k // 2: k // 2 + (OH - 1) * s + 1: s, k // 2: k // 2 + (OW - 1) * s + 1: s, :], ref)
+    assert np.array_equal(got, ref)
+    # monotone: pooling commutes with thresholding of the underlying accumulators
+    C32 = rng.integers(-100, 100, size=(H, W, C)).astype(np.int32)
+    thr = np.sort(rng.integers(-80, 80, size=(C, 3)), axis=1).astype(np.int32)
+    Yt = oracle.threshold(C32.reshape(-1, C).T, thr).T.reshape(H, W, C)
+    pooled_acc = oracle.maxpool(C32, k, s)
+    assert np.array_equal(oracle.maxpool(Yt, k, s),
+                          oracle.threshold(pooled_acc.reshape(-1, C).T, thr).T.reshape(OH, OW, C))
+
+
+def test_maxpool_closed_forms():
+    Y = np.full((7, 7, 3), 2, dtype=np.uint8)
+    assert (oracle.maxpool(Y, 3, 2) == 2).all()
+    Y[3, 3, 1] = 3
+    out = oracle.maxpool(Y, 3, 2)                 # windows start at 0, 2, 4: pixel 3 lies in windows 1 and 2
+    assert out.shape == (3, 3, 3)
+    assert (out[1:3, 1:3, 1] == 3).all() and out[0, 0, 1] == 2 and (out[..., 0] == 2).all()
