@@ -86,6 +86,10 @@ def test_maxpool_closed_forms():
     Y = np.full((7, 7, 3), 2, dtype=np.uint8)
     assert (oracle.maxpool(Y, 3, 2) == 2).all()
     Y[3, 3, 1] = 3
-    out = oracle.maxpool(Y, 3, 2)                 # windows start at 0, 2, 4: pixel 3 lies in windows 1 and 2
+    out = oracle.maxpool(Y, 3, 2)                 # windows cover 0..2, 2..4, 4..6: pixel 3 lies in window 1 only
     assert out.shape == (3, 3, 3)
-    assert (out[1:3, 1:3, 1] == 3).all() and out[0, 0, 1] == 2 and (out[..., 0] == 2).all()
+    want = np.full((3, 3, 3), 2); want[1, 1, 1] = 3
+    assert np.array_equal(out, want)
+    Y[4, 2, 0] = 3                                # pixel (4, 2) lies in windows (1, 0), (1, 1), (2, 0), (2, 1)
+    want[1:3, 0:2, 0] = 3
+    assert np.array_equal(oracle.maxpool(Y, 3, 2), want)
