@@ -215,6 +215,42 @@ def extras(bs, workloads, dev, timed):
         fused("W4A4_8192x8192x%d" % n, 4, TC, 4, U, 8192, n, 8192, 4)
     # a GEMV large enough that launch and first-byte latency stop mattering
     fused("W1A2_32768x32768x1_cold", 1, BP, 2, U, 32768, 1, 32768, 2, copies=3, reps=12)
+    # the W1A2 layers of the paper's AlexNet (Table 2) as one packed chain, batch 1:
+    # conv2 (fused lowering + GEMM + thresholds) -> pool -> conv3 -> conv4 -> conv5 -> pool -> fc6 -> fc7
+    xin, layers = workloads.alexnet_inner()
+    H0, W0, C0 = xin.shape
+    x0 = bs.bs_pack_planes(dev(xin.reshape(H0 * W0, C0)), 2, U)
+    prepared = []
+    for L in layers:
+        if L["kind"] == "conv":
+            F = L["geom"][3]
+            prepared.append((L, bs.bs_pack_planes(dev(L["filt"].reshape(F, -1)), 1, BP), dev(L["thr"])))
+        elif L["kind"] == "fc":
+            prepared.append((L, bs.bs_pack_planes(dev(L["W"]), 1, BP), dev(L["thr"])))
+        else:
+            prepared.append((L, None, None))
+
+    def frame():
+        cur = x0
+        for L, Wp, th in prepared:
+            if L["kind"] == "conv":
+                H, W, C, F, k, s, p = L["geom"]
+                cur = bs.bs_conv_threshold(cur, U, H, W, C, Wp, BP, k, k, s, p, th, 2, out=L.setdefault(
+                    "_out", torch.empty((2, ((H + 2 * p - k) // s + 1) ** 2, bs.bs_words_per_row(F)), dtype=torch.int64, device="cuda")))
+            elif L["kind"] == "pool":
+                H, W, C, k, s = L["geom"]
+                cur = bs.bs_maxpool_packed(cur, H, W, C, k, s, out=L.setdefault(
+                    "_out", torch.empty((2, ((H - k) // s + 1) ** 2, bs.bs_words_per_row(C)), dtype=torch.int64, device="cuda")))
+            else:
+                M, K = L["geom"]
+                cur = bs.bs_gemm_threshold(Wp, BP, cur.reshape(2, 1, -1), U, K, th, 2, out=L.setdefault(
+                    "_out", torch.empty((2, 1, bs.bs_words_per_row(M)), dtype=torch.int64, device="cuda")))
+        return cur
+    ms = timed_graph([frame], 20)
+    out["alexnet_W1A2_layers_conv2_to_fc7_chain"] = {
+        "us_per_frame": round(ms * 1e3, 2), "frames_per_s": round(1e3 / ms, 1), "kernels_per_frame": len(prepared),
+        "context": "the same layers (lowering + GEMM rows of Table 2, bsgemm-intl column) sum to 55.1 ms on the "
+                   "paper's Cortex-A57 core; synthetic weights here"}
     # interleaved lowering of conv2 alone, and the two pack kernels
     x = planes(2, 27 * 27, 96)
     low = torch.empty((2, 729, bs.bs_words_per_row(2400)), dtype=torch.int64, device="cuda")

@@ -138,6 +138,37 @@ bs_status bs_gemm_threshold(const uint64_t *Wp, int wbits, bs_format wfmt,
 bs_status bs_im2col_interleaved(const uint64_t *in, int abits, int H, int W, int C,
                                 int kh, int kw, int stride, int pad, uint64_t *out, void *stream);
 
+/*
+ * One quantized convolution layer on packed data, without materialising the lowered
+ * matrix: the interleaved lowering of Sec. 3.2 is folded into the operand fetch of the
+ * bit-serial GEMM (Alg. 2), and successive thresholding (Sec. 2.1.1) into its epilogue.
+ * Equivalent to bs_im2col_interleaved followed by bs_gemm_threshold with M = F,
+ * N = OH*OW, K = bs_lowered_depth(C, kh, kw).
+ *   in   device uint64_t [abits][H][W][bs_words_per_row(C)], packed HWC planes; afmt must be
+ *        BS_UNSIGNED or BS_TWOS_COMPLEMENT (spatial padding is the value 0)
+ *   Fp   device, filter planes [wbits][F][bs_words_per_row(Kl)], depth order
+ *        (r*kw + s) * 32*ceil(C/32) + c as for bs_im2col_interleaved
+ *   thr  device int32 [F][2^obits - 1];  Yp device uint64_t [obits][OH*OW][bs_words_per_row(F)],
+ *        i.e. the packed HWC planes of the output feature map, fully overwritten.
+ * Errors: INVALID_ARG, UNSUPPORTED (bits > 4, bipolar activations, kh or kw > 127, lowered
+ * depth above 65536 bits: use the two-call route), ALIGNMENT, OVERFLOW_RISK, LAUNCH.
+ */
+bs_status bs_conv_threshold(const uint64_t *in, int abits, bs_format afmt, int H, int W, int C,
+                            const uint64_t *Fp, int wbits, bs_format wfmt, int F, int kh, int kw,
+                            int stride, int pad, const int32_t *thr, int obits, uint64_t *Yp, void *stream);
+
+/*
+ * Max pooling of a few-bit feature map held as packed HWC planes (unsigned codes).  Not a
+ * step of the paper's hot path (pooling is one of its "other layers", Sec. 4.2); provided so
+ * that the quantized layers of Table 2 chain without unpacking.  Exact because thresholding
+ * is monotone: pooling codes equals thresholding pooled accumulators.
+ *   in   device uint64_t [bits][H][W][bs_words_per_row(C)]
+ *   out  device uint64_t [bits][OH][OW][bs_words_per_row(C)], OH = (H - k)/stride + 1, no padding
+ * Errors: INVALID_ARG (k > H or W), UNSUPPORTED (bits > 4), ALIGNMENT, OVERFLOW_RISK, LAUNCH.
+ */
+bs_status bs_maxpool_packed(const uint64_t *in, int bits, int H, int W, int C, int k, int stride,
+                            uint64_t *out, void *stream);
+
 const char *bs_status_string(bs_status s);
 int bs_version(void);
 

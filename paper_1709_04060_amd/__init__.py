@@ -23,7 +23,8 @@ BS_UNSIGNED, BS_TWOS_COMPLEMENT, BS_BIPOLAR = 0, 1, 2
 BS_I8, BS_I32 = 0, 1
 
 EXPORTS = ("bs_words_per_row", "bs_lowered_depth", "bs_pack_planes", "bs_gemm", "bs_threshold_activate",
-           "bs_gemm_threshold", "bs_im2col_interleaved", "bs_status_string", "bs_version")
+           "bs_gemm_threshold", "bs_im2col_interleaved", "bs_conv_threshold", "bs_maxpool_packed",
+           "bs_status_string", "bs_version")
 
 
 class BsError(RuntimeError):
@@ -54,6 +55,9 @@ def load_library() -> ctypes.CDLL:
     lib.bs_gemm_threshold.restype = i32
     lib.bs_im2col_interleaved.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.bs_im2col_interleaved.restype = i32
+    lib.bs_conv_threshold.argtypes = [vp, i32, i32, i32, i32, i32, vp, i32, i32, i32, i32, i32, i32, i32, vp, i32, vp, vp]
+    lib.bs_conv_threshold.restype = i32
+    lib.bs_maxpool_packed.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp]; lib.bs_maxpool_packed.restype = i32
     lib.bs_status_string.argtypes = [i32]; lib.bs_status_string.restype = ctypes.c_char_p
     lib.bs_version.argtypes = []; lib.bs_version.restype = i32
     _lib = lib
@@ -161,4 +165,33 @@ def bs_im2col_interleaved(x: torch.Tensor, H: int, W: int, C: int, kh: int, kw: 
     st = load_library().bs_im2col_interleaved(_dev(x, "x"), abits, H, W, C, kh, kw, stride, pad,
                                               _dev(out, "out"), _stream())
     _check(st, "bs_im2col_interleaved")
+    return out
+
+
+def bs_conv_threshold(x: torch.Tensor, afmt: int, H: int, W: int, C: int, Fp: torch.Tensor, wfmt: int,
+                      kh: int, kw: int, stride: int, pad: int, thr: torch.Tensor, obits: int,
+                      out: torch.Tensor | None = None) -> torch.Tensor:
+    """Convolution + thresholding on packed HWC planes x [abits][H*W][S_C] with filter planes
+    Fp [wbits][F][S_Kl]; returns the packed HWC planes [obits][OH*OW][S_F] of the output map."""
+    abits = x.shape[0]
+    wbits, F, _ = Fp.shape
+    OH = (H + 2 * pad - kh) // stride + 1
+    OW = (W + 2 * pad - kw) // stride + 1
+    if out is None:
+        out = _planes(obits, OH * OW, F, x.device)
+    st = load_library().bs_conv_threshold(_dev(x, "x"), abits, afmt, H, W, C, _dev(Fp, "Fp"), wbits, wfmt, F,
+                                          kh, kw, stride, pad, _dev(thr, "thr"), obits, _dev(out, "out"), _stream())
+    _check(st, "bs_conv_threshold")
+    return out
+
+
+def bs_maxpool_packed(x: torch.Tensor, H: int, W: int, C: int, k: int, stride: int,
+                      out: torch.Tensor | None = None) -> torch.Tensor:
+    """Max pooling of packed HWC planes x [bits][H*W][S_C] -> [bits][OH*OW][S_C]."""
+    bits = x.shape[0]
+    OH, OW = (H - k) // stride + 1, (W - k) // stride + 1
+    if out is None:
+        out = _planes(bits, OH * OW, C, x.device)
+    st = load_library().bs_maxpool_packed(_dev(x, "x"), bits, H, W, C, k, stride, _dev(out, "out"), _stream())
+    _check(st, "bs_maxpool_packed")
     return out

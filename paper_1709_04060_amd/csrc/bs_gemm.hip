@@ -4,10 +4,10 @@
 #include "bs_gemm_kernel.h"
 
 namespace bs {
-extern template bs_status launch_wb<1>(const GemmParams &, int, bool, bool, hipStream_t);
-extern template bs_status launch_wb<2>(const GemmParams &, int, bool, bool, hipStream_t);
-extern template bs_status launch_wb<3>(const GemmParams &, int, bool, bool, hipStream_t);
-extern template bs_status launch_wb<4>(const GemmParams &, int, bool, bool, hipStream_t);
+extern template bs_status launch_wb<1>(const GemmParams &, int, bool, bool, bool, hipStream_t);
+extern template bs_status launch_wb<2>(const GemmParams &, int, bool, bool, bool, hipStream_t);
+extern template bs_status launch_wb<3>(const GemmParams &, int, bool, bool, bool, hipStream_t);
+extern template bs_status launch_wb<4>(const GemmParams &, int, bool, bool, bool, hipStream_t);
 }
 
 namespace {
@@ -25,6 +25,16 @@ void set_coefficients(GemmParams &g, int wbits, bs_format wfmt, int abits, bs_fo
         for (int j = 0; j < 4; ++j) g.coef[i * 4 + j] = cw[i] * ca[j];
     for (int i = 0; i < 4; ++i) { g.crow[i] = oa * cw[i]; g.ccol[i] = ow * ca[i]; }
     g.c0 = ow * oa * (int)K;
+}
+
+bs_status dispatch_wb(const GemmParams &g, int wbits, int abits, bool fuse, bool corr, bool conv, hipStream_t st)
+{
+    switch (wbits) {
+    case 1: return launch_wb<1>(g, abits, fuse, corr, conv, st);
+    case 2: return launch_wb<2>(g, abits, fuse, corr, conv, st);
+    case 3: return launch_wb<3>(g, abits, fuse, corr, conv, st);
+    default: return launch_wb<4>(g, abits, fuse, corr, conv, st);
+    }
 }
 
 bs_status gemm_common(const uint64_t *Wp, int wbits, bs_format wfmt, const uint64_t *Ap, int abits, bs_format afmt,
@@ -62,12 +72,7 @@ bs_status gemm_common(const uint64_t *Wp, int wbits, bs_format wfmt, const uint6
     const bool corr = (wfmt == BS_BIPOLAR) || (afmt == BS_BIPOLAR);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (gemv_applicable(g, abits, afmt == BS_BIPOLAR)) return launch_gemv(g, wbits, abits, fuse, st);
-    switch (wbits) {
-    case 1: return launch_wb<1>(g, abits, fuse, corr, st);
-    case 2: return launch_wb<2>(g, abits, fuse, corr, st);
-    case 3: return launch_wb<3>(g, abits, fuse, corr, st);
-    default: return launch_wb<4>(g, abits, fuse, corr, st);
-    }
+    return dispatch_wb(g, wbits, abits, fuse, corr, false, st);
 }
 
 }  // namespace
@@ -83,4 +88,44 @@ extern "C" bs_status bs_gemm_threshold(const uint64_t *Wp, int wbits, bs_format 
                                        int obits, uint64_t *Yp, void *stream)
 {
     return gemm_common(Wp, wbits, wfmt, Ap, abits, afmt, M, N, K, nullptr, 0, thr, obits, Yp, true, stream);
+}
+
+extern "C" bs_status bs_conv_threshold(const uint64_t *in, int abits, bs_format afmt, int H, int W, int C,
+                                       const uint64_t *Fp, int wbits, bs_format wfmt, int F, int kh, int kw,
+                                       int stride, int pad, const int32_t *thr, int obits, uint64_t *Yp, void *stream)
+{
+    if (!in || !Fp || !thr || !Yp || H <= 0 || W <= 0 || C <= 0 || F <= 0 || kh <= 0 || kw <= 0 || stride <= 0 ||
+        pad < 0 || obits < 1)
+        return BS_ERR_INVALID_ARG;
+    if (bs_status s = bs::check_bits_fmt(wbits, wfmt)) return s;
+    if (bs_status s = bs::check_bits_fmt(abits, afmt)) return s;
+    // spatial padding is written as zero words, which is the value 0 only for these formats
+    if (afmt == BS_BIPOLAR) return BS_ERR_UNSUPPORTED;
+    if (obits > bs::kMaxBits) return BS_ERR_UNSUPPORTED;
+    if (H + 2 * pad < kh || W + 2 * pad < kw) return BS_ERR_INVALID_ARG;
+    if (!bs::aligned(in, 16) || !bs::aligned(Fp, 16) || !bs::aligned(Yp, 16) || !bs::aligned(thr, 4))
+        return BS_ERR_ALIGNMENT;
+    const int64_t Kl = bs_lowered_depth(C, kh, kw);
+    const int64_t S = bs_words_per_row(Kl);
+    const int OH = (H + 2 * pad - kh) / stride + 1, OW = (W + 2 * pad - kw) / stride + 1;
+    const int64_t N = (int64_t)OH * OW;
+    if (Kl / 32 > kConvMaxLut || kh > 127 || kw > 127) return BS_ERR_UNSUPPORTED;
+    if ((Kl << (wbits + abits)) >= (int64_t(1) << 31)) return BS_ERR_OVERFLOW_RISK;
+    const int64_t lim = int64_t(1) << 31;
+    const int64_t pix = 2 * bs_words_per_row(C);
+    if (wbits * (int64_t)F * S * 2 >= lim || abits * (int64_t)H * W * pix >= lim || N >= lim) return BS_ERR_OVERFLOW_RISK;
+
+    GemmParams g;
+    g.W = reinterpret_cast<const uint32_t *>(Fp);
+    g.A = reinterpret_cast<const uint32_t *>(in);
+    g.M = F; g.N = (int)N; g.Kd = (int)(2 * S);
+    set_coefficients(g, wbits, wfmt, abits, afmt, Kl);
+    g.C = nullptr; g.ldc = 0;
+    g.thr = thr; g.obits = obits; g.T = (1 << obits) - 1;
+    g.Y = reinterpret_cast<uint32_t *>(Yp);
+    g.Yd = (int)(2 * bs_words_per_row(F));
+    g.cH = H; g.cW = W; g.cCd = (C + 31) / 32; g.cPix = (int)pix; g.cKW = kw;
+    g.cStride = stride; g.cPad = pad; g.cOW = OW; g.cKused = (int)(Kl / 32);
+    const bool corr = (wfmt == BS_BIPOLAR);
+    return dispatch_wb(g, wbits, abits, true, corr, true, static_cast<hipStream_t>(stream));
 }

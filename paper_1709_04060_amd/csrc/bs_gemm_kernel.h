@@ -55,7 +55,17 @@ struct GemmParams {
     int gx, gy;         // tiles along N and along M
     int rx, ry;         // XCD regions along N and M (rx * ry == 8), or 0 = plain row-major order
     int hx, hy;         // tiles per region along N and M
+    // implicit lowering (CONV kernels): A points at packed HWC image planes
+    int cH, cW;         // image size
+    int cCd;            // 32-bit words copied per pixel and tap, ceil(C / 32)
+    int cPix;           // 32-bit words between pixels
+    int cKW;            // kernel width (taps per kernel row)
+    int cStride, cPad;
+    int cOW;            // output width (columns n = oh * cOW + ow)
+    int cKused;         // dwords of a lowered column that carry data: kh * kw * cCd
 };
+
+constexpr int kConvMaxLut = 2048;  // lowered dwords the implicit-lowering kernels can index (65536 depth bits)
 
 // GEMV path (bs_gemv.hip): used for at most this many columns, activation planes in LDS.
 constexpr int kGemvMaxCols = 4;
@@ -110,7 +120,10 @@ __device__ __forceinline__ bool tile_of_block(const GemmParams &p, int bid, int 
 // wavefronts across the tile, KS: wavefronts across the depth of each stage.  FUSE:
 // thresholding epilogue instead of the int32 store.  CORR: popcount correction terms
 // needed (some operand is bipolar).
-template <int WB, int AB, int TM, int TN, int WM, int WN, int KS, bool FUSE, bool CORR>
+// CONV: the activation operand is not a packed matrix but packed HWC image planes; the
+// loader gathers each lowered column's words from the image (Sec. 3.2's lowering folded
+// into the operand fetch, so the lowered matrix never exists in memory).
+template <int WB, int AB, int TM, int TN, int WM, int WN, int KS, bool FUSE, bool CORR, bool CONV = false>
 __global__ void __launch_bounds__(WM * WN * KS * 64)
 bs_gemm_kernel(const GemmParams p)
 {
@@ -122,11 +135,13 @@ bs_gemm_kernel(const GemmParams p)
     constexpr bool PER_PAIR = PAIRS <= 4;        // one accumulator set per plane pair
     constexpr int NACC = PER_PAIR ? PAIRS : 1;
     static_assert(KCH % KS == 0, "the depth split must divide the chunks of a stage");
+    static_assert((WROWS * KCH) % NT == 0, "every loader slot is wholly weights or wholly activations");
     static_assert((KS > 1 ? 5 : 1) * BM * BN <= CHUNKS * 16, "epilogue staging must fit in the tile space");
 
     __shared__ uint4 lds[CHUNKS];
     __shared__ int corr_row[CORR ? BM : 1];
     __shared__ int corr_col[CORR ? BN : 1];
+    __shared__ int lut[CONV ? kConvMaxLut : 1];  // lowered dword -> (kernel row, kernel column, channel word)
 
     int tile_m, tile_n;
     if (!tile_of_block(p, blockIdx.x, tile_m, tile_n)) return;  // uniform for the workgroup
@@ -143,13 +158,15 @@ bs_gemm_kernel(const GemmParams p)
     int loff[CPT];    // destination chunk index in LDS
     int cweight[CPT]; // correction weight of the plane the chunk belongs to
     int cnt[CPT];
+    int pix_h[CONV ? CPT : 1], pix_w[CONV ? CPT : 1];  // CONV: top-left input pixel of the column's window
 #pragma unroll
     for (int s = 0; s < CPT; ++s) {
         const int id = tid + s * NT;
         const int srow = id / KCH, c = id % KCH;
         goff[s] = -1; loff[s] = 0; cweight[s] = 0; cnt[s] = 0;
+        if (CONV) { pix_h[s] = 0; pix_w[s] = 0; }
         if (id < CHUNKS) {
-            if (srow < WROWS) {
+            if (s * NT < WROWS * KCH) {
                 const int pl = srow / BM, r = srow % BM;
                 loff[s] = srow * KCH + (c ^ ((r / TM) & 7));
                 if (m0 + r < p.M) goff[s] = (pl * p.M + m0 + r) * p.Kd + c * 4;
@@ -158,7 +175,16 @@ bs_gemm_kernel(const GemmParams p)
                 const int q = srow - WROWS;
                 const int pl = q / BN, r = q % BN;
                 loff[s] = srow * KCH + (c ^ ((r / TN) & 7));
-                if (n0 + r < p.N) goff[s] = (pl * p.N + n0 + r) * p.Kd + c * 4;
+                if (n0 + r < p.N) {
+                    if constexpr (CONV) {
+                        const int oh = (n0 + r) / p.cOW, ow = (n0 + r) - oh * p.cOW;
+                        pix_h[s] = oh * p.cStride - p.cPad;
+                        pix_w[s] = ow * p.cStride - p.cPad;
+                        goff[s] = pl * p.cH * p.cW * p.cPix;  // plane base
+                    } else {
+                        goff[s] = (pl * p.N + n0 + r) * p.Kd + c * 4;
+                    }
+                }
                 if (CORR) cweight[s] = p.ccol[pl];
             }
         }
@@ -167,17 +193,43 @@ bs_gemm_kernel(const GemmParams p)
         for (int i = tid; i < BM; i += NT) corr_row[i] = 0;
         for (int i = tid; i < BN; i += NT) corr_col[i] = 0;
     }
+    if constexpr (CONV) {
+        for (int q = tid; q < p.cKused; q += NT) {
+            const int tap = q / p.cCd, cd = q - tap * p.cCd;
+            const int fr = tap / p.cKW, fs = tap - fr * p.cKW;
+            lut[q] = (fr << 24) | (fs << 16) | cd;
+        }
+        __syncthreads();
+    }
 
     uint4 stage[CPT];
     auto fetch = [&](int k0) {
 #pragma unroll
         for (int s = 0; s < CPT; ++s) {
-            const int id = tid + s * NT;
-            const int srow = id / KCH, c = id % KCH;
+            const int c = (tid + s * NT) % KCH;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (goff[s] >= 0 && k0 + c * 4 < p.Kd) {
-                const uint32_t *base = srow < WROWS ? p.W : p.A;
-                v = *reinterpret_cast<const uint4 *>(base + (size_t)(unsigned)goff[s] + k0);
+            if (s * NT < WROWS * KCH) {
+                if (goff[s] >= 0 && k0 + c * 4 < p.Kd)
+                    v = *reinterpret_cast<const uint4 *>(p.W + (size_t)(unsigned)goff[s] + k0);
+            } else if constexpr (!CONV) {
+                if (goff[s] >= 0 && k0 + c * 4 < p.Kd)
+                    v = *reinterpret_cast<const uint4 *>(p.A + (size_t)(unsigned)goff[s] + k0);
+            } else {
+                if (goff[s] >= 0) {
+                    uint32_t e[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const int q = k0 + c * 4 + t;
+                        e[t] = 0;
+                        if (q < p.cKused) {
+                            const int l = lut[q];
+                            const int ih = pix_h[s] + (l >> 24), iw = pix_w[s] + ((l >> 16) & 0xFF);
+                            if (ih >= 0 && ih < p.cH && iw >= 0 && iw < p.cW)
+                                e[t] = p.A[(size_t)(unsigned)goff[s] + (size_t)(ih * p.cW + iw) * p.cPix + (l & 0xFFFF)];
+                        }
+                    }
+                    v = make_uint4(e[0], e[1], e[2], e[3]);
+                }
             }
             stage[s] = v;
         }
@@ -428,7 +480,7 @@ inline long long plan_tile_order(GemmParams &g, int BM, int BN, int wbits, int a
 }
 
 template <int WB, int AB, int TM, int TN, int WM, int WN, int KS>
-bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, hipStream_t st)
+bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, hipStream_t st)
 {
     constexpr int BM = 8 * TM * WM, BN = 8 * TN * WN;
     GemmParams g = g_in;
@@ -440,7 +492,11 @@ bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, hipStream_t s
     // where WB == 1 or AB == 1.
     constexpr bool CAN_CORR = (WB == 1 || AB == 1);
     if (corr && !CAN_CORR) return BS_ERR_INVALID_ARG;
-    if (fuse) {
+    if (conv) {  // implicit lowering exists with the thresholding epilogue only
+        if (!fuse) return BS_ERR_UNSUPPORTED;
+        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, true, CAN_CORR, true><<<grid, block, 0, st>>>(g);
+        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, true, false, true><<<grid, block, 0, st>>>(g);
+    } else if (fuse) {
         if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, true, CAN_CORR><<<grid, block, 0, st>>>(g);
         else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, true, false><<<grid, block, 0, st>>>(g);
     } else {
@@ -451,24 +507,24 @@ bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, hipStream_t s
 }
 
 template <int WB, int AB>
-bs_status launch_planes(const GemmParams &g, bool fuse, bool corr, hipStream_t st)
+bs_status launch_planes(const GemmParams &g, bool fuse, bool corr, bool conv, hipStream_t st)
 {
     // Large grids: 64 x 64 tiles, four wavefronts side by side.  Small grids: 32 x 32
     // tiles whose four wavefronts split the depth, so that more wavefronts exist.
     const long long tiles64 = (long long)((g.M + 63) / 64) * ((g.N + 63) / 64);
-    if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4>(g, fuse, corr, st);
-    return launch_cfg<WB, AB, 4, 4, 2, 2, 1>(g, fuse, corr, st);
+    if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4>(g, fuse, corr, conv, st);
+    return launch_cfg<WB, AB, 4, 4, 2, 2, 1>(g, fuse, corr, conv, st);
 }
 
 // Defined once per WB in bs_gemm_w<WB>.hip (explicit instantiation) to keep builds parallel.
 template <int WB>
-bs_status launch_wb(const GemmParams &g, int abits, bool fuse, bool corr, hipStream_t st)
+bs_status launch_wb(const GemmParams &g, int abits, bool fuse, bool corr, bool conv, hipStream_t st)
 {
     switch (abits) {
-    case 1: return launch_planes<WB, 1>(g, fuse, corr, st);
-    case 2: return launch_planes<WB, 2>(g, fuse, corr, st);
-    case 3: return launch_planes<WB, 3>(g, fuse, corr, st);
-    default: return launch_planes<WB, 4>(g, fuse, corr, st);
+    case 1: return launch_planes<WB, 1>(g, fuse, corr, conv, st);
+    case 2: return launch_planes<WB, 2>(g, fuse, corr, conv, st);
+    case 3: return launch_planes<WB, 3>(g, fuse, corr, conv, st);
+    default: return launch_planes<WB, 4>(g, fuse, corr, conv, st);
     }
 }
 

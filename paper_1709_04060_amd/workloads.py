@@ -87,3 +87,46 @@ def cfg5_w4a4(n: int, size: int = 8192):
     mu = -0.5 * 7.5 * size
     sigma = float(np.sqrt((21.5 * 77.5 - (0.5 * 7.5) ** 2) * size))
     return dict(W=W, A=unsigned(rn, (size, n), 4), thr=thresholds(rn, size, 4, mu, sigma, jitter=8))
+
+
+# The W1A2 layers of the paper's quantized AlexNet (Table 2), batch 1: name, kind, geometry.
+# conv: (H, W, C, F, k, stride, pad); pool: (H, W, C, k, stride); fc: (M, K).
+ALEXNET_INNER = [
+    ("conv2", "conv", (27, 27, 96, 256, 5, 1, 2)),
+    ("pool2", "pool", (27, 27, 256, 3, 2)),
+    ("conv3", "conv", (13, 13, 256, 384, 3, 1, 1)),
+    ("conv4", "conv", (13, 13, 384, 384, 3, 1, 1)),
+    ("conv5", "conv", (13, 13, 384, 256, 3, 1, 1)),
+    ("pool5", "pool", (13, 13, 256, 3, 2)),
+    ("fc6", "fc", (4096, 9216)),
+    ("fc7", "fc", (4096, 4096)),
+]
+
+
+def alexnet_inner(scale: int = 1):
+    """Synthetic parameters for the chain conv2 .. fc7: bipolar weights, three sorted int32
+    thresholds per output channel, and the 27 x 27 x 96 unsigned 2-bit input of conv2.
+    `scale` > 1 divides the channel and row counts (smaller test instances); spatial sizes
+    stay, so fc6's depth becomes 36 * (256 // scale)."""
+    r = rng_for(6)
+    layers = []
+    x = None
+    for name, kind, g in ALEXNET_INNER:
+        if kind == "conv":
+            H, W, C, F, k, s, p = g
+            C, F = C // scale, F // scale
+            if x is None:
+                x = unsigned(r, (H, W, C), 2)
+            K = k * k * C
+            layers.append(dict(name=name, kind=kind, geom=(H, W, C, F, k, s, p), filt=bipolar(r, (F, k, k, C)),
+                               thr=thresholds(r, F, 2, 0.0, float(np.sqrt(3.5 * K)))))
+        elif kind == "pool":
+            H, W, C, k, s = g
+            layers.append(dict(name=name, kind=kind, geom=(H, W, C // scale, k, s)))
+        else:
+            M, K = g
+            M = M // scale
+            K = 36 * (256 // scale) if name == "fc6" else K // scale
+            layers.append(dict(name=name, kind=kind, geom=(M, K), W=bipolar(r, (M, K)),
+                               thr=thresholds(r, M, 2, 0.0, float(np.sqrt(3.5 * K)))))
+    return x, layers
