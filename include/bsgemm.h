@@ -169,6 +169,29 @@ bs_status bs_conv_threshold(const uint64_t *in, int abits, bs_format afmt, int H
 bs_status bs_maxpool_packed(const uint64_t *in, int bits, int H, int W, int C, int k, int stride,
                             uint64_t *out, void *stream);
 
+/*
+ * Dense engine.  The paper configures each quantized layer to run on either its
+ * bit-serial engine or an 8-bit engine (Sec. 4.2) and gives the break-even rule (Sec.
+ * 4.1.1).  On this chip the 8-bit matrix cores win every compute-bound shape, so the
+ * same product C = W . A (Sec. 3.1) is also offered from unpacked int8 operands; the
+ * bit-serial calls remain the choice for bandwidth-bound shapes (few columns).
+ *
+ * bs_unpack_planes: inverse of bs_pack_planes.  planes [bits][rows][bs_words_per_row(depth)]
+ *   -> dst int8 [rows][ld], logical values, depth-contiguous; ld a multiple of 16 and
+ *   >= depth; bytes from depth up to the next multiple of 16 are written as 0.
+ * bs_gemm_i8 / bs_gemm_i8_threshold: W int8 [M][ldw], At int8 [N][lda] (activations
+ *   transposed, i.e. depth-contiguous like W), both 16-byte aligned with ldw, lda multiples
+ *   of 16 and >= K; bytes between K and the leading dimension are ignored.  Outputs exactly
+ *   as bs_gemm (C int32 [M][ldc], overwritten) and bs_gemm_threshold (Yp packed planes).
+ * Errors: INVALID_ARG, UNSUPPORTED, ALIGNMENT, OVERFLOW_RISK (K >= 2^17), LAUNCH.
+ */
+bs_status bs_unpack_planes(const uint64_t *planes, int bits, bs_format fmt, int64_t rows, int64_t depth,
+                           int8_t *dst, int64_t ld, void *stream);
+bs_status bs_gemm_i8(const int8_t *W, int64_t ldw, const int8_t *At, int64_t lda, int64_t M, int64_t N, int64_t K,
+                     int32_t *C, int64_t ldc, void *stream);
+bs_status bs_gemm_i8_threshold(const int8_t *W, int64_t ldw, const int8_t *At, int64_t lda, int64_t M, int64_t N,
+                               int64_t K, const int32_t *thr, int obits, uint64_t *Yp, void *stream);
+
 const char *bs_status_string(bs_status s);
 int bs_version(void);
 

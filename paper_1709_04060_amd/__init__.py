@@ -24,7 +24,7 @@ BS_I8, BS_I32 = 0, 1
 
 EXPORTS = ("bs_words_per_row", "bs_lowered_depth", "bs_pack_planes", "bs_gemm", "bs_threshold_activate",
            "bs_gemm_threshold", "bs_im2col_interleaved", "bs_conv_threshold", "bs_maxpool_packed",
-           "bs_status_string", "bs_version")
+           "bs_unpack_planes", "bs_gemm_i8", "bs_gemm_i8_threshold", "bs_status_string", "bs_version")
 
 
 class BsError(RuntimeError):
@@ -58,6 +58,10 @@ def load_library() -> ctypes.CDLL:
     lib.bs_conv_threshold.argtypes = [vp, i32, i32, i32, i32, i32, vp, i32, i32, i32, i32, i32, i32, i32, vp, i32, vp, vp]
     lib.bs_conv_threshold.restype = i32
     lib.bs_maxpool_packed.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp]; lib.bs_maxpool_packed.restype = i32
+    lib.bs_unpack_planes.argtypes = [vp, i32, i32, i64, i64, vp, i64, vp]; lib.bs_unpack_planes.restype = i32
+    lib.bs_gemm_i8.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i64, vp]; lib.bs_gemm_i8.restype = i32
+    lib.bs_gemm_i8_threshold.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i32, vp, vp]
+    lib.bs_gemm_i8_threshold.restype = i32
     lib.bs_status_string.argtypes = [i32]; lib.bs_status_string.restype = ctypes.c_char_p
     lib.bs_version.argtypes = []; lib.bs_version.restype = i32
     _lib = lib
@@ -194,4 +198,38 @@ def bs_maxpool_packed(x: torch.Tensor, H: int, W: int, C: int, k: int, stride: i
         out = _planes(bits, OH * OW, C, x.device)
     st = load_library().bs_maxpool_packed(_dev(x, "x"), bits, H, W, C, k, stride, _dev(out, "out"), _stream())
     _check(st, "bs_maxpool_packed")
+    return out
+
+
+def bs_unpack_planes(planes: torch.Tensor, fmt: int, depth: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """planes [bits][rows][S] -> int8 [rows][ld] of logical values (ld = depth rounded up to 16)."""
+    bits, rows, _ = planes.shape
+    if out is None:
+        out = torch.empty((rows, 16 * ((depth + 15) // 16)), dtype=torch.int8, device=planes.device)
+    st = load_library().bs_unpack_planes(_dev(planes, "planes"), bits, fmt, rows, depth, _dev(out, "out"),
+                                         out.stride(0), _stream())
+    _check(st, "bs_unpack_planes")
+    return out
+
+
+def bs_gemm_i8(W: torch.Tensor, At: torch.Tensor, K: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Dense engine: C[M][N] (int32) from int8 W [M][>=K] and At [N][>=K] (depth-contiguous rows)."""
+    M, N = W.shape[0], At.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=W.device)
+    st = load_library().bs_gemm_i8(_dev(W, "W"), W.stride(0), _dev(At, "At"), At.stride(0), M, N, K,
+                                   _dev(out, "out"), out.stride(0), _stream())
+    _check(st, "bs_gemm_i8")
+    return out
+
+
+def bs_gemm_i8_threshold(W: torch.Tensor, At: torch.Tensor, K: int, thr: torch.Tensor, obits: int,
+                         out: torch.Tensor | None = None) -> torch.Tensor:
+    """Dense engine with the fused thresholding epilogue; output planes as bs_gemm_threshold."""
+    M, N = W.shape[0], At.shape[0]
+    if out is None:
+        out = _planes(obits, N, M, W.device)
+    st = load_library().bs_gemm_i8_threshold(_dev(W, "W"), W.stride(0), _dev(At, "At"), At.stride(0), M, N, K,
+                                             _dev(thr, "thr"), obits, _dev(out, "out"), _stream())
+    _check(st, "bs_gemm_i8_threshold")
     return out

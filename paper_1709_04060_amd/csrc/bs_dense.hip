@@ -1,0 +1,406 @@
+// Dense engine: the product of two few-bit integer matrices (Sec. 3.1 of the paper,
+// "W . A") computed on the matrix cores from UNPACKED int8 operands, with the same
+// thresholding epilogue (Sec. 2.1.1) as the bit-serial engine.
+//
+// Why it exists.  The paper chooses per layer between a bit-serial engine and an 8-bit
+// engine (Sec. 4.2) and states the break-even rule: bit-serial wins while w * a stays
+// below the ratio of binary to 8-bit peak throughput (Sec. 4.1.1).  On gfx950 that ratio
+// is below one: one v_and + v_bcnt pair does 32 binary MACs per lane, an int8 MFMA does
+// 1024 MACs per cycle and SIMD.  For compute-bound shapes the dense contraction therefore
+// belongs on MFMA; bit-serial keeps the bandwidth-bound shapes, where bytes scale with bits.
+//
+// Kernel shape.  A workgroup of four wavefronts (2 x 2) owns a BM x BN tile of C; each
+// wavefront owns WTM x WTN tiles of 32 x 32 accumulated with v_mfma_i32_32x32x32_i8.
+// Operands are depth-contiguous int8 rows; 64 bytes of depth per row and stage are
+// fetched global -> registers one stage ahead, then written to LDS with an 80-byte row
+// stride so that the 16-byte fragment reads of 32 consecutive rows spread over all banks.
+// Both operands give lane l the depth bytes [16 (l / 32), 16 (l / 32) + 16) of row l % 32,
+// so the contraction is over matching depth indices whatever order the instruction uses
+// internally.  Accumulator register v of lane l is C[8 (v / 4) + 4 (l / 32) + v % 4][l % 32]
+// of its 32 x 32 tile.
+#include <type_traits>
+
+#include "bs_common.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int DK = 64;        // depth bytes per row and stage
+constexpr int DROW = 80;      // LDS row stride in bytes (64 + 16 pad)
+constexpr int DCH = DK / 16;  // 16-byte chunks per row and stage
+
+struct DenseParams {
+    const int8_t *W;   // [M][ldw]
+    const int8_t *A;   // [N][lda]  (activations, depth-contiguous)
+    long long ldw, lda;
+    int M, N, K;
+    int32_t *C;
+    long long ldc;
+    const int32_t *thr;
+    int T, obits;
+    uint32_t *Y;
+    int Yd;
+    int gx, gy;        // tiles along N and M
+};
+
+// zero the bytes of a 16-byte chunk that lie at or beyond depth index K
+__device__ __forceinline__ uint4 mask_tail(uint4 v, int k, int K)
+{
+    if (k + 16 <= K) return v;
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const int left = K - (k + 4 * d);  // valid bytes in this dword
+        if (left <= 0) w[d] = 0;
+        else if (left < 4) w[d] &= (1u << (8 * left)) - 1u;
+    }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+template <int WTM, int WTN, bool FUSE>
+__global__ void __launch_bounds__(256)
+dense_gemm_kernel(const DenseParams p)
+{
+    constexpr int BM = 64 * WTM, BN = 64 * WTN;
+    constexpr int ROWS = BM + BN;
+    constexpr int CPT = ROWS * DCH / 256;  // chunks each thread moves per stage
+    static_assert((ROWS * DCH) % 256 == 0 && (BM * DCH) % 256 == 0, "loader slots are uniform");
+    constexpr int TILE_BYTES = ROWS * DROW;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * TILE_BYTES];  // two stages: one read, one written
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, lg = lane >> 5;
+    const int tile_m = blockIdx.x / p.gx, tile_n = blockIdx.x % p.gx;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    // ---- loader: thread moves chunk (row, c) of the stacked [W rows; A rows] tile ----
+    // Loads are unconditional and never feed anything but the later LDS write, so many can
+    // be in flight: rows beyond M / N are clamped to the last row (their products land in
+    // outputs that are never stored), chunks beyond the depth are read from the row's first
+    // chunk and zeroed when the stage is written to LDS.
+    const int8_t *rowp[CPT];
+    int lofs[CPT];
+#pragma unroll
+    for (int s = 0; s < CPT; ++s) {
+        const int id = tid + s * 256;
+        const int row = id / DCH, c = id % DCH;
+        lofs[s] = row * DROW + c * 16;
+        if (s * 256 < BM * DCH) {
+            const int m = m0 + row < p.M ? m0 + row : p.M - 1;
+            rowp[s] = p.W + (long long)m * p.ldw;
+        } else {
+            const int n = n0 + (row - BM) < p.N ? n0 + (row - BM) : p.N - 1;
+            rowp[s] = p.A + (long long)n * p.lda;
+        }
+    }
+    // two stages in flight in registers: enough bytes outstanding to cover memory latency
+    uint4 stage[2][CPT];
+    auto fetch = [&](int ring, int k0) {
+#pragma unroll
+        for (int s = 0; s < CPT; ++s) {
+            const int k = k0 + ((tid + s * 256) % DCH) * 16;
+            stage[ring][s] = *reinterpret_cast<const uint4 *>(rowp[s] + (k < p.K ? k : 0));
+        }
+    };
+    // LDS write of the stage that starts at depth kst.  FULL: the stage lies wholly inside
+    // the depth, nothing to mask.
+    auto commit = [&](auto full, int ring, int buf, int kst) {
+#pragma unroll
+        for (int s = 0; s < CPT; ++s) {
+            uint4 v = stage[ring][s];
+            if constexpr (!decltype(full)::value) {
+                const int k = kst + ((tid + s * 256) % DCH) * 16;
+                v = k < p.K ? mask_tail(v, k, p.K) : make_uint4(0, 0, 0, 0);
+            }
+            *reinterpret_cast<uint4 *>(lds + buf * TILE_BYTES + lofs[s]) = v;
+        }
+    };
+
+    v16i acc[WTM][WTN];
+#pragma unroll
+    for (int a = 0; a < WTM; ++a)
+#pragma unroll
+        for (int b = 0; b < WTN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
+
+    const unsigned char *ldsW = lds + (wm * 32 * WTM + li) * DROW + lg * 16;
+    const unsigned char *ldsA = lds + (BM + wn * 32 * WTN + li) * DROW + lg * 16;
+
+    // Stage k is consumed from one LDS buffer while stage k + 1 (fetched during the previous
+    // iteration) is written to the other and stage k + 2 is requested from memory.  The
+    // fragments of the next 32-byte depth step are read from LDS before the MFMAs of the
+    // current one are issued, so LDS latency hides behind matrix work; the single barrier of
+    // a stage sits between its two depth steps, after which the next stage's buffer is
+    // complete and may be read.
+    static_assert(DK == 64, "the pipeline below is written for two depth steps per stage");
+    v4i fa[2][WTM], fb[2][WTN];
+    auto load_frags = [&](int set, int buf, int sub) {
+        const unsigned char *bw = ldsW + buf * TILE_BYTES + sub * 32, *ba = ldsA + buf * TILE_BYTES + sub * 32;
+#pragma unroll
+        for (int a = 0; a < WTM; ++a) fa[set][a] = *reinterpret_cast<const v4i *>(bw + a * 32 * DROW);
+#pragma unroll
+        for (int b = 0; b < WTN; ++b) fb[set][b] = *reinterpret_cast<const v4i *>(ba + b * 32 * DROW);
+    };
+    auto mfmas = [&](int set) {
+#pragma unroll
+        for (int a = 0; a < WTM; ++a)
+#pragma unroll
+            for (int b = 0; b < WTN; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][a], fb[set][b], acc[a][b], 0, 0, 0);
+    };
+
+    // One stage of the pipeline.  PAR = parity of the stage index = LDS buffer it is read
+    // from; stage k + 1 sits in register ring (PAR ^ 1) and goes to the other LDS buffer,
+    // then that ring is refilled with stage k + 3.
+    // One stage of the pipeline.  PAR = parity of the stage index = LDS buffer it is read
+    // from; stage k + 1 sits in register ring (PAR ^ 1) and goes to the other LDS buffer,
+    // then that ring is refilled with stage k + 3.  FAST steps are branch-free (stages k + 1
+    // exists and is full), which also lets the compiler count outstanding loads exactly and
+    // wait only for the older of the two rings.
+    // The scheduling fences keep the order "issue LDS reads, issue all MFMAs of the step,
+    // only then wait": left alone, the compiler hoists the barrier (and the wait for the
+    // reads just issued) above the MFMAs and the matrix pipe idles during LDS latency.
+    const int nst = (p.K + DK - 1) / DK;      // stages
+    const int nfull = p.K / DK;               // stages wholly inside the depth
+    const int nst_even = (nst + 1) & ~1;      // a surplus stage multiplies zeros
+    auto step = [&](auto par, auto fast, int i) {
+        constexpr int PAR = decltype(par)::value;
+        constexpr bool FAST = decltype(fast)::value;
+        const int k0 = i * DK;
+        const bool more = FAST || i + 1 < nst_even;
+        // first half: write stage k + 1 to LDS, read the fragments of depth step 1, MFMAs of step 0
+        if (more) commit(fast, PAR ^ 1, PAR ^ 1, k0 + DK);
+        load_frags(1, PAR, 1);
+        mfmas(0);
+        if constexpr (FAST) {
+            // one LDS operation between consecutive MFMAs: the four wavefronts of a workgroup
+            // run in lockstep between barriers, so without interleaving they all move data at
+            // once and then all multiply at once, and LDS and matrix time add up
+#pragma unroll
+            for (int r = 0; r < CPT; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // DS write
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();  // stage k + 1 is now complete in the other buffer; nobody reads this one's step 0 any more
+        // second half: request stage k + 3, read the next stage's first fragments, MFMAs of step 1
+        if (more) {
+            fetch(PAR ^ 1, k0 + 3 * DK);
+            load_frags(0, PAR ^ 1, 0);
+        }
+        mfmas(1);
+        if constexpr (FAST) {
+#pragma unroll
+            for (int r = 0; r < CPT; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+
+    fetch(0, 0);
+    commit(std::false_type{}, 0, 0, 0);
+    fetch(1, DK);
+    fetch(0, 2 * DK);
+    __syncthreads();
+    load_frags(0, 0, 0);
+    int i = 0;
+    for (; i + 2 < nfull; i += 2) {           // stages i + 1 and i + 2 are full
+        step(P0{}, std::true_type{}, i);
+        step(P1{}, std::true_type{}, i + 1);
+    }
+    for (; i < nst_even; i += 2) {
+        step(P0{}, std::false_type{}, i);
+        step(P1{}, std::false_type{}, i + 1);
+    }
+
+    // ---- epilogue ----
+    if constexpr (!FUSE) {
+#pragma unroll
+        for (int a = 0; a < WTM; ++a)
+#pragma unroll
+            for (int b = 0; b < WTN; ++b) {
+                const int n = n0 + (wn * WTN + b) * 32 + li;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + (wm * WTM + a) * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
+                    if (m < p.M && n < p.N) p.C[(long long)m * p.ldc + n] = acc[a][b][v];
+                }
+            }
+    } else {
+        // thresholds of the tile's rows -> LDS (the operand tiles are no longer needed),
+        // padded to 16 per row with INT_MAX (never reached) so that a row is four 16-byte reads
+        __syncthreads();
+        int4 *tl = reinterpret_cast<int4 *>(lds);  // [BM][4]
+        for (int it = tid; it < BM * 16; it += 256) {
+            const int r = it >> 4, t = it & 15;
+            reinterpret_cast<int32_t *>(tl)[it] =
+                (m0 + r < p.M && t < p.T) ? p.thr[(long long)(m0 + r) * p.T + t] : 0x7fffffff;
+        }
+        __syncthreads();
+        const int nq = (p.T + 3) >> 2;  // 16-byte groups of thresholds actually used
+#pragma unroll
+        for (int a = 0; a < WTM; ++a) {
+            const int rbase = (wm * WTM + a) * 32;  // first row of this 32-row band within the block tile
+            uint32_t word[WTN][4];
+#pragma unroll
+            for (int b = 0; b < WTN; ++b)
+#pragma unroll
+                for (int pl = 0; pl < 4; ++pl) word[b][pl] = 0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rr = 8 * (v >> 2) + 4 * lg + (v & 3);
+                uint32_t y[WTN];
+#pragma unroll
+                for (int b = 0; b < WTN; ++b) y[b] = 0;
+                // one row's thresholds serve the WTN column tiles this lane holds
+                for (int q = 0; q < nq; ++q) {
+                    const int4 th = tl[(rbase + rr) * 4 + q];
+#pragma unroll
+                    for (int b = 0; b < WTN; ++b) {
+                        const int c = acc[a][b][v];
+                        y[b] += (uint32_t)(c >= th.x) + (uint32_t)(c >= th.y) + (uint32_t)(c >= th.z) + (uint32_t)(c >= th.w);
+                    }
+                }
+                const bool live = m0 + rbase + rr < p.M;
+#pragma unroll
+                for (int b = 0; b < WTN; ++b)
+#pragma unroll
+                    for (int pl = 0; pl < 4; ++pl) word[b][pl] |= (live ? ((y[b] >> pl) & 1u) : 0u) << rr;
+            }
+            // Row bands cover a multiple of 128 rows, i.e. at least the Yd words of a column, so
+            // every word (padding included) is written by some band; words beyond Yd (a 256-row
+            // tile over a shorter column) are dropped.
+            const int wi = (m0 + rbase) / 32;
+#pragma unroll
+            for (int b = 0; b < WTN; ++b) {
+                const int n = n0 + (wn * WTN + b) * 32 + li;
+                // the two half-wavefronts hold complementary rows of the same column
+#pragma unroll
+                for (int pl = 0; pl < 4; ++pl) word[b][pl] |= __shfl_xor(word[b][pl], 32);
+                if (lg == 0 && n < p.N && wi < p.Yd)
+                    for (int pl = 0; pl < p.obits; ++pl) p.Y[((long long)pl * p.N + n) * p.Yd + wi] = word[b][pl];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ unpack (planes -> int8)
+__global__ void __launch_bounds__(256)
+unpack_kernel(const uint32_t *__restrict__ planes, int bits, int coef0, int coef1, int coef2, int coef3, int offset,
+              long long rows, long long depth, int Kd, int8_t *__restrict__ dst, long long ld, long long chunks_per_row)
+{
+    const long long item = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (item >= rows * chunks_per_row) return;
+    const long long r = item / chunks_per_row, c = item - r * chunks_per_row;  // chunk = 16 depth indices
+    const int coef[4] = {coef0, coef1, coef2, coef3};
+    uint32_t half[4] = {0, 0, 0, 0};
+    for (int pl = 0; pl < bits; ++pl)
+        half[pl] = (planes[((long long)pl * rows + r) * Kd + (c >> 1)] >> (16 * (int)(c & 1))) & 0xFFFFu;
+    uint32_t out[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int e = 4 * d + b;
+            int v = offset;
+#pragma unroll
+            for (int pl = 0; pl < 4; ++pl) v += coef[pl] * (int)((half[pl] >> e) & 1u);
+            if (c * 16 + e >= depth) v = 0;
+            w |= ((uint32_t)v & 0xFFu) << (8 * b);
+        }
+        out[d] = w;
+    }
+    *reinterpret_cast<uint4 *>(dst + r * ld + c * 16) = make_uint4(out[0], out[1], out[2], out[3]);
+}
+
+template <int WTM, int WTN>
+bs_status launch_dense(DenseParams &p, bool fuse, hipStream_t st)
+{
+    constexpr int BM = 64 * WTM, BN = 64 * WTN;
+    p.gx = (p.N + BN - 1) / BN;
+    p.gy = (p.M + BM - 1) / BM;
+    const long long blocks = (long long)p.gx * p.gy;
+    if (blocks >= (1LL << 31)) return BS_ERR_UNSUPPORTED;
+    if (fuse) dense_gemm_kernel<WTM, WTN, true><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+    else dense_gemm_kernel<WTM, WTN, false><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+    return bs::after_launch();
+}
+
+bs_status dense_common(const int8_t *W, int64_t ldw, const int8_t *At, int64_t lda, int64_t M, int64_t N, int64_t K,
+                       int32_t *C, int64_t ldc, const int32_t *thr, int obits, uint64_t *Yp, bool fuse, void *stream)
+{
+    if (!W || !At || M <= 0 || N <= 0 || K <= 0 || ldw < K || lda < K) return BS_ERR_INVALID_ARG;
+    if (!bs::aligned(W, 16) || !bs::aligned(At, 16) || (ldw & 15) || (lda & 15)) return BS_ERR_ALIGNMENT;
+    if (fuse) {
+        if (!thr || !Yp || obits < 1) return BS_ERR_INVALID_ARG;
+        if (obits > bs::kMaxBits) return BS_ERR_UNSUPPORTED;
+        if (!bs::aligned(thr, 4) || !bs::aligned(Yp, 16)) return BS_ERR_ALIGNMENT;
+    } else {
+        if (!C || ldc < N) return BS_ERR_INVALID_ARG;
+        if (!bs::aligned(C, 4)) return BS_ERR_ALIGNMENT;
+    }
+    // |w|, |a| <= 128: every partial sum stays below 2^31 while K < 2^17
+    if (K >= (int64_t(1) << 17)) return BS_ERR_OVERFLOW_RISK;
+    if (M >= (int64_t(1) << 31) || N >= (int64_t(1) << 31)) return BS_ERR_OVERFLOW_RISK;
+    DenseParams p;
+    p.W = W; p.A = At; p.ldw = ldw; p.lda = lda;
+    p.M = (int)M; p.N = (int)N; p.K = (int)K;
+    p.C = C; p.ldc = ldc;
+    p.thr = thr; p.obits = obits; p.T = fuse ? (1 << obits) - 1 : 0;
+    p.Y = reinterpret_cast<uint32_t *>(Yp);
+    p.Yd = (int)(2 * bs_words_per_row(M));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // 256 x 256 tiles when they still give every compute unit work, else 128 x 128
+    const long long big = (long long)((M + 255) / 256) * ((N + 255) / 256);
+    if (big >= 256) return launch_dense<4, 4>(p, fuse, st);
+    return launch_dense<2, 2>(p, fuse, st);
+}
+
+}  // namespace
+
+extern "C" bs_status bs_unpack_planes(const uint64_t *planes, int bits, bs_format fmt, int64_t rows, int64_t depth,
+                                      int8_t *dst, int64_t ld, void *stream)
+{
+    if (!planes || !dst || rows <= 0 || depth <= 0) return BS_ERR_INVALID_ARG;
+    if (bs_status s = bs::check_bits_fmt(bits, fmt)) return s;
+    const int64_t chunks = (depth + 15) / 16;
+    if (ld < chunks * 16) return BS_ERR_INVALID_ARG;
+    if (!bs::aligned(planes, 16) || !bs::aligned(dst, 16) || (ld & 15)) return BS_ERR_ALIGNMENT;
+    const int64_t S = bs_words_per_row(depth);
+    if (rows * S * 2 * bits >= (int64_t(1) << 31)) return BS_ERR_OVERFLOW_RISK;
+    int coef[4] = {0, 0, 0, 0}, offset = 0;
+    for (int i = 0; i < bits; ++i) coef[i] = (fmt == BS_TWOS_COMPLEMENT && i == bits - 1) ? -(1 << i) : (1 << i);
+    if (fmt == BS_BIPOLAR) { coef[0] = 2; offset = -1; }
+    const int64_t items = rows * chunks;
+    unpack_kernel<<<dim3((unsigned)((items + 255) / 256)), 256, 0, static_cast<hipStream_t>(stream)>>>(
+        reinterpret_cast<const uint32_t *>(planes), bits, coef[0], coef[1], coef[2], coef[3], offset, rows, depth,
+        (int)(2 * S), dst, ld, chunks);
+    return bs::after_launch();
+}
+
+extern "C" bs_status bs_gemm_i8(const int8_t *W, int64_t ldw, const int8_t *At, int64_t lda, int64_t M, int64_t N,
+                                int64_t K, int32_t *C, int64_t ldc, void *stream)
+{
+    return dense_common(W, ldw, At, lda, M, N, K, C, ldc, nullptr, 0, nullptr, false, stream);
+}
+
+extern "C" bs_status bs_gemm_i8_threshold(const int8_t *W, int64_t ldw, const int8_t *At, int64_t lda, int64_t M,
+                                          int64_t N, int64_t K, const int32_t *thr, int obits, uint64_t *Yp,
+                                          void *stream)
+{
+    return dense_common(W, ldw, At, lda, M, N, K, nullptr, 0, thr, obits, Yp, true, stream);
+}
