@@ -251,6 +251,31 @@ def extras(bs, workloads, dev, timed):
         "us_per_frame": round(ms * 1e3, 2), "frames_per_s": round(1e3 / ms, 1), "kernels_per_frame": len(prepared),
         "context": "the same layers (lowering + GEMM rows of Table 2, bsgemm-intl column) sum to 55.1 ms on the "
                    "paper's Cortex-A57 core; synthetic weights here"}
+    # the dense (int8 MFMA) engine on the compute-bound configurations, beside the bit-serial
+    # numbers above: same logical product, operands unpacked to int8
+    def dense(name, M, N, K, obits):
+        Wd = torch.randint(-8, 8, (M, K), dtype=torch.int8, device="cuda")
+        Ad = torch.randint(0, 16, (N, K), dtype=torch.int8, device="cuda")
+        th = thr_for(M, obits) if obits else None
+        if obits:
+            Y = torch.empty((obits, N, bs.bs_words_per_row(M)), dtype=torch.int64, device="cuda")
+            f = lambda: bs.bs_gemm_i8_threshold(Wd, Ad, K, th, obits, out=Y)
+        else:
+            Cd = torch.empty((M, N), dtype=torch.int32, device="cuda")
+            f = lambda: bs.bs_gemm_i8(Wd, Ad, K, out=Cd)
+        ms, _ = timed(f, 10, 3)
+        tops = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+        out[name] = {"us": round(ms * 1e3, 2), "GOPS": round(tops * 1e3, 1),
+                     "roofline": {"bound": "mfma", "achieved": round(tops, 1), "peak": 5000.0, "unit": "int8 TOP/s",
+                                  "frac": round(tops / 5000.0, 4)}}
+    dense("dense_engine_4096x4096x4096_int32_out", 4096, 4096, 4096, 0)
+    dense("dense_engine_8192x8192x8192_fused_4bit_out", 8192, 8192, 8192, 4)
+    dense("dense_engine_8192x8192x1024_fused_4bit_out", 8192, 1024, 8192, 4)
+    Wp2 = planes(2, 4096, 4096)
+    W8 = torch.empty((4096, 4096), dtype=torch.int8, device="cuda")
+    ms = timed_graph([lambda: bs.bs_unpack_planes(Wp2, TC, 4096, out=W8)], 20)
+    out["unpack_4096x4096_2_planes_to_i8"] = {"us": round(ms * 1e3, 2),
+                                              "GBps": round((Wp2.numel() * 8 + W8.numel()) / ms / 1e6, 1)}
     # interleaved lowering of conv2 alone, and the two pack kernels
     x = planes(2, 27 * 27, 96)
     low = torch.empty((2, 729, bs.bs_words_per_row(2400)), dtype=torch.int64, device="cuda")

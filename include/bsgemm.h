@@ -192,6 +192,28 @@ bs_status bs_gemm_i8(const int8_t *W, int64_t ldw, const int8_t *At, int64_t lda
 bs_status bs_gemm_i8_threshold(const int8_t *W, int64_t ldw, const int8_t *At, int64_t lda, int64_t M, int64_t N,
                                int64_t K, const int32_t *thr, int obits, uint64_t *Yp, void *stream);
 
+/*
+ * Streamlining, host side (Sec. 2.1).  HOST pointers, double precision, no GPU work.
+ *
+ * bs_streamline_collapse (Sec. 2.1.2): collapses, per output channel m, the chain
+ *   previous quantizer affine (a_q, b_q) moved past the product, alpha-scaling, batch norm
+ *   into y = a[m] x + b[m] of the integer accumulator x = (W x_int)[m]:
+ *     a[m] = gamma/sigma * alpha * a_q,  b[m] = gamma/sigma * (alpha * b_q * rowsum_w[m] - mu) + beta.
+ *   alpha may be NULL (1); gamma, beta, mu, sigma all NULL (no batch norm) or all given;
+ *   rowsum_w[m] = sum_k W[m][k] is needed when b_q != 0.
+ * bs_streamline_thresholds (Sec. 2.1.3): thr[m][i] = ceil((t[i] - b[m]) / a[m]) for a[m] > 0, so
+ *   that for every integer x  #{i : a x + b >= t[i]} = #{i : x >= thr[m][i]}.  For a[m] < 0 the
+ *   channel is marked negate[m] = 1 and the thresholds hold for -x (negate that weight row);
+ *   negate == NULL with some a[m] < 0 is BS_ERR_UNSUPPORTED.  a[m] == 0 gives thresholds that
+ *   are always / never reached.  Values are clamped to the int32 range.
+ *   t [T] is the quantizer's threshold list (Sec. 2.1.1), thr [M][T] row-major.
+ */
+bs_status bs_streamline_collapse(int64_t M, double a_q, double b_q, const int64_t *rowsum_w, const double *alpha,
+                                 const double *gamma, const double *beta, const double *mu, const double *sigma,
+                                 double *a, double *b);
+bs_status bs_streamline_thresholds(const double *t, int T, const double *a, const double *b, int64_t M,
+                                   int32_t *thr, uint8_t *negate);
+
 const char *bs_status_string(bs_status s);
 int bs_version(void);
 

@@ -24,7 +24,8 @@ BS_I8, BS_I32 = 0, 1
 
 EXPORTS = ("bs_words_per_row", "bs_lowered_depth", "bs_pack_planes", "bs_gemm", "bs_threshold_activate",
            "bs_gemm_threshold", "bs_im2col_interleaved", "bs_conv_threshold", "bs_maxpool_packed",
-           "bs_unpack_planes", "bs_gemm_i8", "bs_gemm_i8_threshold", "bs_status_string", "bs_version")
+           "bs_unpack_planes", "bs_gemm_i8", "bs_gemm_i8_threshold", "bs_streamline_collapse",
+           "bs_streamline_thresholds", "bs_status_string", "bs_version")
 
 
 class BsError(RuntimeError):
@@ -62,6 +63,10 @@ def load_library() -> ctypes.CDLL:
     lib.bs_gemm_i8.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i64, vp]; lib.bs_gemm_i8.restype = i32
     lib.bs_gemm_i8_threshold.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i32, vp, vp]
     lib.bs_gemm_i8_threshold.restype = i32
+    f64 = ctypes.c_double
+    lib.bs_streamline_collapse.argtypes = [i64, f64, f64, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.bs_streamline_collapse.restype = i32
+    lib.bs_streamline_thresholds.argtypes = [vp, i32, vp, vp, i64, vp, vp]; lib.bs_streamline_thresholds.restype = i32
     lib.bs_status_string.argtypes = [i32]; lib.bs_status_string.restype = ctypes.c_char_p
     lib.bs_version.argtypes = []; lib.bs_version.restype = i32
     _lib = lib
@@ -233,3 +238,35 @@ def bs_gemm_i8_threshold(W: torch.Tensor, At: torch.Tensor, K: int, thr: torch.T
                                              _dev(thr, "thr"), obits, _dev(out, "out"), _stream())
     _check(st, "bs_gemm_i8_threshold")
     return out
+
+
+def _np_ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def bs_streamline_collapse(M: int, a_q: float = 1.0, b_q: float = 0.0, rowsum_w=None, alpha=None, gamma=None,
+                           beta=None, mu=None, sigma=None):
+    """Host-side: per-channel (a, b) of y = a x + b from the layer's float pieces (numpy arrays)."""
+    import numpy as np
+    f = lambda v: None if v is None else np.ascontiguousarray(v, dtype=np.float64)
+    rs = None if rowsum_w is None else np.ascontiguousarray(rowsum_w, dtype=np.int64)
+    alpha, gamma, beta, mu, sigma = f(alpha), f(gamma), f(beta), f(mu), f(sigma)
+    a, b = np.empty(M, dtype=np.float64), np.empty(M, dtype=np.float64)
+    st = load_library().bs_streamline_collapse(M, float(a_q), float(b_q), _np_ptr(rs), _np_ptr(alpha), _np_ptr(gamma),
+                                               _np_ptr(beta), _np_ptr(mu), _np_ptr(sigma), _np_ptr(a), _np_ptr(b))
+    _check(st, "bs_streamline_collapse")
+    return a, b
+
+
+def bs_streamline_thresholds(t, a, b):
+    """Host-side: integer thresholds thr [M][T] and the per-channel negate flags (numpy arrays)."""
+    import numpy as np
+    t = np.ascontiguousarray(t, dtype=np.float64)
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    b = np.ascontiguousarray(b, dtype=np.float64)
+    M, T = a.shape[0], t.shape[0]
+    thr = np.empty((M, T), dtype=np.int32)
+    neg = np.empty(M, dtype=np.uint8)
+    st = load_library().bs_streamline_thresholds(_np_ptr(t), T, _np_ptr(a), _np_ptr(b), M, _np_ptr(thr), _np_ptr(neg))
+    _check(st, "bs_streamline_thresholds")
+    return thr, neg
