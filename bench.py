@@ -37,6 +37,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line, run the W1A1 size sweep of Sec. 4.1.2 (every dimension "
+                         "from 2^6 to 2^12) and print one JSON line per (M, K, N)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run plain 256 MiB device copies, so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
                          "readings can be scaled by what the same counter reports for a copy of known size")
@@ -72,6 +75,9 @@ def main() -> int:
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3 / iters
         return e0.elapsed_time(e1) / iters, wall
+
+    if args.sweep:
+        return sweep(bs, torch)
 
     if args.calibration_copy:
         src = torch.full((256 << 20,), 3, dtype=torch.uint8, device="cuda")
@@ -145,6 +151,28 @@ def main() -> int:
         result["other_configs"] = extras(bs, workloads, dev, timed)
 
     print(json.dumps(result))
+    return 0
+
+
+def sweep(bs, torch):
+    """The paper's performance-versus-size experiment (Sec. 4.1.2, Fig. 3): W1A1 (both operands
+    bipolar) bit-serial GEMM for every M, K, N in {2^6 .. 2^12}; GOPS = 2 M N K / T with T the
+    graph-replayed kernel time.  Also prints the best and worst GOPS per depth."""
+    sizes = [1 << e for e in range(6, 13)]
+    BP = bs.BS_BIPOLAR
+    best = {}
+    for K in sizes:
+        for M in sizes:
+            Wp = torch.randint(-2 ** 62, 2 ** 62, (1, M, bs.bs_words_per_row(K)), dtype=torch.int64, device="cuda")
+            for N in sizes:
+                Ap = torch.randint(-2 ** 62, 2 ** 62, (1, N, bs.bs_words_per_row(K)), dtype=torch.int64, device="cuda")
+                C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+                ms = timed_graph([lambda: bs.bs_gemm(Wp, BP, Ap, BP, K, out=C)], 20)
+                gops = 2.0 * M * N * K / ms / 1e6
+                print(json.dumps({"sweep": "W1A1", "M": M, "K": K, "N": N, "us": round(ms * 1e3, 2), "GOPS": round(gops, 1)}))
+                lo, hi = best.get(K, (float("inf"), 0.0))
+                best[K] = (min(lo, gops), max(hi, gops))
+    print(json.dumps({"sweep_summary_GOPS_min_max_by_depth": {str(k): [round(v[0], 1), round(v[1], 1)] for k, v in best.items()}}))
     return 0
 
 

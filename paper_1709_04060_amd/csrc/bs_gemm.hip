@@ -4,10 +4,10 @@
 #include "bs_gemm_kernel.h"
 
 namespace bs {
-extern template bs_status launch_wb<1>(const GemmParams &, int, bool, bool, bool, hipStream_t);
-extern template bs_status launch_wb<2>(const GemmParams &, int, bool, bool, bool, hipStream_t);
-extern template bs_status launch_wb<3>(const GemmParams &, int, bool, bool, bool, hipStream_t);
-extern template bs_status launch_wb<4>(const GemmParams &, int, bool, bool, bool, hipStream_t);
+extern template bs_status launch_wb<1>(const GemmParams &, int, bool, bool, bool, bool, hipStream_t);
+extern template bs_status launch_wb<2>(const GemmParams &, int, bool, bool, bool, bool, hipStream_t);
+extern template bs_status launch_wb<3>(const GemmParams &, int, bool, bool, bool, bool, hipStream_t);
+extern template bs_status launch_wb<4>(const GemmParams &, int, bool, bool, bool, bool, hipStream_t);
 }
 
 namespace {
@@ -27,13 +27,13 @@ void set_coefficients(GemmParams &g, int wbits, bs_format wfmt, int abits, bs_fo
     g.c0 = ow * oa * (int)K;
 }
 
-bs_status dispatch_wb(const GemmParams &g, int wbits, int abits, bool fuse, bool corr, bool conv, hipStream_t st)
+bs_status dispatch_wb(const GemmParams &g, int wbits, int abits, bool fuse, bool corr, bool conv, bool xr, hipStream_t st)
 {
     switch (wbits) {
-    case 1: return launch_wb<1>(g, abits, fuse, corr, conv, st);
-    case 2: return launch_wb<2>(g, abits, fuse, corr, conv, st);
-    case 3: return launch_wb<3>(g, abits, fuse, corr, conv, st);
-    default: return launch_wb<4>(g, abits, fuse, corr, conv, st);
+    case 1: return launch_wb<1>(g, abits, fuse, corr, conv, xr, st);
+    case 2: return launch_wb<2>(g, abits, fuse, corr, conv, xr, st);
+    case 3: return launch_wb<3>(g, abits, fuse, corr, conv, xr, st);
+    default: return launch_wb<4>(g, abits, fuse, corr, conv, xr, st);
     }
 }
 
@@ -69,10 +69,18 @@ bs_status gemm_common(const uint64_t *Wp, int wbits, bs_format wfmt, const uint6
     g.thr = thr; g.obits = obits; g.T = fuse ? (1 << obits) - 1 : 0;
     g.Y = reinterpret_cast<uint32_t *>(Yp);
     g.Yd = (int)(2 * bs_words_per_row(M));
-    const bool corr = (wfmt == BS_BIPOLAR) || (afmt == BS_BIPOLAR);
+    // Both operands bipolar (the W1A1 case of Sec. 3.1): XOR-popcount, dot = K - 2 popcount(XOR)
+    const bool xr = (wfmt == BS_BIPOLAR) && (afmt == BS_BIPOLAR);
+    if (xr) {
+        for (int i = 0; i < 16; ++i) g.coef[i] = 0;
+        g.coef[0] = -2;
+        g.c0 = (int)K;
+        for (int i = 0; i < 4; ++i) g.crow[i] = g.ccol[i] = 0;
+    }
+    const bool corr = !xr && ((wfmt == BS_BIPOLAR) || (afmt == BS_BIPOLAR));
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (gemv_applicable(g, abits, afmt == BS_BIPOLAR)) return launch_gemv(g, wbits, abits, fuse, st);
-    return dispatch_wb(g, wbits, abits, fuse, corr, false, st);
+    if (gemv_applicable(g, abits, afmt == BS_BIPOLAR, wfmt == BS_BIPOLAR)) return launch_gemv(g, wbits, abits, fuse, xr, st);
+    return dispatch_wb(g, wbits, abits, fuse, corr, false, xr, st);
 }
 
 }  // namespace
@@ -127,5 +135,5 @@ extern "C" bs_status bs_conv_threshold(const uint64_t *in, int abits, bs_format 
     g.cH = H; g.cW = W; g.cCd = (C + 31) / 32; g.cPix = (int)pix; g.cKW = kw;
     g.cStride = stride; g.cPad = pad; g.cOW = OW; g.cKused = (int)(Kl / 32);
     const bool corr = (wfmt == BS_BIPOLAR);
-    return dispatch_wb(g, wbits, abits, true, corr, true, static_cast<hipStream_t>(stream));
+    return dispatch_wb(g, wbits, abits, true, corr, true, false, static_cast<hipStream_t>(stream));
 }

@@ -70,8 +70,8 @@ constexpr int kConvMaxLut = 2048;  // lowered dwords the implicit-lowering kerne
 // GEMV path (bs_gemv.hip): used for at most this many columns, activation planes in LDS.
 constexpr int kGemvMaxCols = 4;
 constexpr size_t kGemvMaxLds = 64 * 1024;
-bool gemv_applicable(const GemmParams &g, int abits, bool a_bipolar);
-bs_status launch_gemv(const GemmParams &g, int wbits, int abits, bool fuse, hipStream_t st);
+bool gemv_applicable(const GemmParams &g, int abits, bool a_bipolar, bool w_bipolar);
+bs_status launch_gemv(const GemmParams &g, int wbits, int abits, bool fuse, bool xr, hipStream_t st);
 
 // acc + popcount(x) in ONE instruction: v_bcnt_u32_b32 adds its second operand for
 // free.  Written as inline assembly because the optimiser otherwise re-associates a sum
@@ -91,6 +91,17 @@ __device__ __forceinline__ int popc_and4(const uint4 &a, const uint4 &b, int acc
     acc = bcnt_acc(a.y & b.y, acc);
     acc = bcnt_acc(a.z & b.z, acc);
     acc = bcnt_acc(a.w & b.w, acc);
+    return acc;
+}
+
+// The XNOR-popcount binary dot product of prior work (Sec. 3.1) in its XOR form: for +-1
+// operands dot = K - 2 popcount(a ^ b); zero padding bits agree in both operands.
+__device__ __forceinline__ int popc_xor4(const uint4 &a, const uint4 &b, int acc)
+{
+    acc = bcnt_acc(a.x ^ b.x, acc);
+    acc = bcnt_acc(a.y ^ b.y, acc);
+    acc = bcnt_acc(a.z ^ b.z, acc);
+    acc = bcnt_acc(a.w ^ b.w, acc);
     return acc;
 }
 
@@ -123,10 +134,13 @@ __device__ __forceinline__ bool tile_of_block(const GemmParams &p, int bid, int 
 // CONV: the activation operand is not a packed matrix but packed HWC image planes; the
 // loader gathers each lowered column's words from the image (Sec. 3.2's lowering folded
 // into the operand fetch, so the lowered matrix never exists in memory).
-template <int WB, int AB, int TM, int TN, int WM, int WN, int KS, bool FUSE, bool CORR, bool CONV = false>
+// XOR: both operands bipolar (W1A1): popcount(XOR) instead of popcount(AND), no correction terms.
+template <int WB, int AB, int TM, int TN, int WM, int WN, int KS, bool FUSE, bool CORR, bool CONV = false,
+          bool XOR = false>
 __global__ void __launch_bounds__(WM * WN * KS * 64)
 bs_gemm_kernel(const GemmParams p)
 {
+    static_assert(!XOR || (WB == 1 && AB == 1 && !CORR), "the XOR form exists for one plane per operand only");
     constexpr int BM = 8 * TM * WM, BN = 8 * TN * WN, NT = 64 * WM * WN * KS;
     constexpr int WROWS = WB * BM, AROWS = AB * BN, ROWS = WROWS + AROWS;
     constexpr int CHUNKS = ROWS * KCH;
@@ -280,7 +294,8 @@ bs_gemm_kernel(const GemmParams p)
                         for (int r = 0; r < TM; ++r)
 #pragma unroll
                             for (int c = 0; c < TN; ++c)
-                                acc[i * AB + j][r][c] = popc_and4(w[i][r], a[j][c], acc[i * AB + j][r][c]);
+                                acc[i * AB + j][r][c] = XOR ? popc_xor4(w[i][r], a[j][c], acc[i * AB + j][r][c])
+                                                            : popc_and4(w[i][r], a[j][c], acc[i * AB + j][r][c]);
             }
         } else {
             // Many plane pairs: one pair at a time over the whole stage into a small
@@ -379,6 +394,12 @@ bs_gemm_kernel(const GemmParams p)
         for (int r = 0; r < TM; ++r)
 #pragma unroll
             for (int c = 0; c < TN; ++c) val[r][c] += corr_row[wrow0 + r] + corr_col[acol0 + c] + p.c0;
+    }
+    if (XOR) {
+#pragma unroll
+        for (int r = 0; r < TM; ++r)
+#pragma unroll
+            for (int c = 0; c < TN; ++c) val[r][c] += p.c0;
     }
 
     if constexpr (!FUSE) {
@@ -480,7 +501,7 @@ inline long long plan_tile_order(GemmParams &g, int BM, int BN, int wbits, int a
 }
 
 template <int WB, int AB, int TM, int TN, int WM, int WN, int KS>
-bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, hipStream_t st)
+bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, bool xr, hipStream_t st)
 {
     constexpr int BM = 8 * TM * WM, BN = 8 * TN * WN;
     GemmParams g = g_in;
@@ -492,6 +513,16 @@ bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, hi
     // where WB == 1 or AB == 1.
     constexpr bool CAN_CORR = (WB == 1 || AB == 1);
     if (corr && !CAN_CORR) return BS_ERR_INVALID_ARG;
+    if (xr) {  // both operands bipolar: one plane each
+        if constexpr (WB == 1 && AB == 1) {
+            if (conv) return BS_ERR_UNSUPPORTED;
+            if (fuse) bs_gemm_kernel<1, 1, TM, TN, WM, WN, KS, true, false, false, true><<<grid, block, 0, st>>>(g);
+            else bs_gemm_kernel<1, 1, TM, TN, WM, WN, KS, false, false, false, true><<<grid, block, 0, st>>>(g);
+            return bs::after_launch();
+        } else {
+            return BS_ERR_INVALID_ARG;
+        }
+    }
     if (conv) {  // implicit lowering exists with the thresholding epilogue only
         if (!fuse) return BS_ERR_UNSUPPORTED;
         if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, true, CAN_CORR, true><<<grid, block, 0, st>>>(g);
@@ -507,24 +538,24 @@ bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, hi
 }
 
 template <int WB, int AB>
-bs_status launch_planes(const GemmParams &g, bool fuse, bool corr, bool conv, hipStream_t st)
+bs_status launch_planes(const GemmParams &g, bool fuse, bool corr, bool conv, bool xr, hipStream_t st)
 {
     // Large grids: 64 x 64 tiles, four wavefronts side by side.  Small grids: 32 x 32
     // tiles whose four wavefronts split the depth, so that more wavefronts exist.
     const long long tiles64 = (long long)((g.M + 63) / 64) * ((g.N + 63) / 64);
-    if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4>(g, fuse, corr, conv, st);
-    return launch_cfg<WB, AB, 4, 4, 2, 2, 1>(g, fuse, corr, conv, st);
+    if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4>(g, fuse, corr, conv, xr, st);
+    return launch_cfg<WB, AB, 4, 4, 2, 2, 1>(g, fuse, corr, conv, xr, st);
 }
 
 // Defined once per WB in bs_gemm_w<WB>.hip (explicit instantiation) to keep builds parallel.
 template <int WB>
-bs_status launch_wb(const GemmParams &g, int abits, bool fuse, bool corr, bool conv, hipStream_t st)
+bs_status launch_wb(const GemmParams &g, int abits, bool fuse, bool corr, bool conv, bool xr, hipStream_t st)
 {
     switch (abits) {
-    case 1: return launch_planes<WB, 1>(g, fuse, corr, conv, st);
-    case 2: return launch_planes<WB, 2>(g, fuse, corr, conv, st);
-    case 3: return launch_planes<WB, 3>(g, fuse, corr, conv, st);
-    default: return launch_planes<WB, 4>(g, fuse, corr, conv, st);
+    case 1: return launch_planes<WB, 1>(g, fuse, corr, conv, xr, st);
+    case 2: return launch_planes<WB, 2>(g, fuse, corr, conv, xr, st);
+    case 3: return launch_planes<WB, 3>(g, fuse, corr, conv, xr, st);
+    default: return launch_planes<WB, 4>(g, fuse, corr, conv, xr, st);
     }
 }
 

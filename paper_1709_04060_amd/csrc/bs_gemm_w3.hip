@@ -2,5 +2,5 @@
 #include "bs_gemm_kernel.h"
 
 namespace bs {
-template bs_status launch_wb<3>(const GemmParams &, int, bool, bool, bool, hipStream_t);
+template bs_status launch_wb<3>(const GemmParams &, int, bool, bool, bool, bool, hipStream_t);
 }

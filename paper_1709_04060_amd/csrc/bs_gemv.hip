@@ -21,7 +21,7 @@ constexpr int LANES_PER_ROW = 32;
 constexpr int GEMV_THREADS = ROWS_PER_BLOCK * LANES_PER_ROW;
 constexpr int UNROLL = 4;           // chunks per lane and plane fetched in one go
 
-template <int WB, int AB, int NC, bool FUSE>
+template <int WB, int AB, int NC, bool FUSE, bool XOR = false>
 __global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams p)
 {
     extern __shared__ uint4 ldsA[];  // [AB][NC][nch]
@@ -107,7 +107,8 @@ __global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams 
                     for (int n = 0; n < NC; ++n) {
                         const uint4 a = ldsA[(j * NC + n) * nch + c];
 #pragma unroll
-                        for (int i = 0; i < WB; ++i) acc[i * AB + j][n] = popc_and4(w[u][i], a, acc[i * AB + j][n]);
+                        for (int i = 0; i < WB; ++i)
+                            acc[i * AB + j][n] = XOR ? popc_xor4(w[u][i], a, acc[i * AB + j][n]) : popc_and4(w[u][i], a, acc[i * AB + j][n]);
                     }
             }
         }
@@ -124,7 +125,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams 
             for (int j = 0; j < AB; ++j) v += p.coef[i * 4 + j] * acc[i * AB + j][n];
 #pragma unroll
         for (int o = LANES_PER_ROW / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
-        val[n] = v + colsum_s[n];
+        val[n] = v + colsum_s[n] + p.c0;
     }
     const bool leader = (g == 0) && mvalid;
 
@@ -176,53 +177,63 @@ __global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams 
 }
 
 template <int WB, int AB, int NC>
-bs_status launch_gemv_nc(const GemmParams &g, bool fuse, size_t lds_bytes, hipStream_t st)
+bs_status launch_gemv_nc(const GemmParams &g, bool fuse, bool xr, size_t lds_bytes, hipStream_t st)
 {
     dim3 grid((unsigned)((g.M + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK));
+    if (xr) {
+        if constexpr (WB == 1 && AB == 1) {
+            if (fuse) bs_gemv_kernel<1, 1, NC, true, true><<<grid, GEMV_THREADS, lds_bytes, st>>>(g);
+            else bs_gemv_kernel<1, 1, NC, false, true><<<grid, GEMV_THREADS, lds_bytes, st>>>(g);
+            return after_launch();
+        } else {
+            return BS_ERR_INVALID_ARG;
+        }
+    }
     if (fuse) bs_gemv_kernel<WB, AB, NC, true><<<grid, GEMV_THREADS, lds_bytes, st>>>(g);
     else bs_gemv_kernel<WB, AB, NC, false><<<grid, GEMV_THREADS, lds_bytes, st>>>(g);
     return after_launch();
 }
 
 template <int WB, int AB>
-bs_status launch_gemv_ab(const GemmParams &g, bool fuse, hipStream_t st)
+bs_status launch_gemv_ab(const GemmParams &g, bool fuse, bool xr, hipStream_t st)
 {
     const int nc = g.N == 1 ? 1 : (g.N == 2 ? 2 : 4);
     const size_t lds_bytes = (size_t)AB * nc * (g.Kd >> 2) * 16;
     switch (nc) {
-    case 1: return launch_gemv_nc<WB, AB, 1>(g, fuse, lds_bytes, st);
-    case 2: return launch_gemv_nc<WB, AB, 2>(g, fuse, lds_bytes, st);
-    default: return launch_gemv_nc<WB, AB, 4>(g, fuse, lds_bytes, st);
+    case 1: return launch_gemv_nc<WB, AB, 1>(g, fuse, xr, lds_bytes, st);
+    case 2: return launch_gemv_nc<WB, AB, 2>(g, fuse, xr, lds_bytes, st);
+    default: return launch_gemv_nc<WB, AB, 4>(g, fuse, xr, lds_bytes, st);
     }
 }
 
 template <int WB>
-bs_status launch_gemv_wb(const GemmParams &g, int abits, bool fuse, hipStream_t st)
+bs_status launch_gemv_wb(const GemmParams &g, int abits, bool fuse, bool xr, hipStream_t st)
 {
     switch (abits) {
-    case 1: return launch_gemv_ab<WB, 1>(g, fuse, st);
-    case 2: return launch_gemv_ab<WB, 2>(g, fuse, st);
-    case 3: return launch_gemv_ab<WB, 3>(g, fuse, st);
-    default: return launch_gemv_ab<WB, 4>(g, fuse, st);
+    case 1: return launch_gemv_ab<WB, 1>(g, fuse, xr, st);
+    case 2: return launch_gemv_ab<WB, 2>(g, fuse, xr, st);
+    case 3: return launch_gemv_ab<WB, 3>(g, fuse, xr, st);
+    default: return launch_gemv_ab<WB, 4>(g, fuse, xr, st);
     }
 }
 
 }  // namespace
 
-bool gemv_applicable(const GemmParams &g, int abits, bool a_bipolar)
+bool gemv_applicable(const GemmParams &g, int abits, bool a_bipolar, bool w_bipolar)
 {
-    if (g.N > kGemvMaxCols || a_bipolar) return false;
+    // bipolar activations are handled in the XOR form only (both operands bipolar)
+    if (g.N > kGemvMaxCols || (a_bipolar && !w_bipolar)) return false;
     const int nc = g.N == 1 ? 1 : (g.N == 2 ? 2 : 4);
     return (size_t)abits * nc * (g.Kd >> 2) * 16 <= kGemvMaxLds;
 }
 
-bs_status launch_gemv(const GemmParams &g, int wbits, int abits, bool fuse, hipStream_t st)
+bs_status launch_gemv(const GemmParams &g, int wbits, int abits, bool fuse, bool xr, hipStream_t st)
 {
     switch (wbits) {
-    case 1: return launch_gemv_wb<1>(g, abits, fuse, st);
-    case 2: return launch_gemv_wb<2>(g, abits, fuse, st);
-    case 3: return launch_gemv_wb<3>(g, abits, fuse, st);
-    default: return launch_gemv_wb<4>(g, abits, fuse, st);
+    case 1: return launch_gemv_wb<1>(g, abits, fuse, xr, st);
+    case 2: return launch_gemv_wb<2>(g, abits, fuse, xr, st);
+    case 3: return launch_gemv_wb<3>(g, abits, fuse, xr, st);
+    default: return launch_gemv_wb<4>(g, abits, fuse, xr, st);
     }
 }
 

@@ -123,6 +123,26 @@ def test_few_column_path(N, M, K, w, wf, a, af, obits):
     assert_equal(planes_to_numpy(out), oracle.threshold_pack(want, thr, obits), "gemv fused")
 
 
+@pytest.mark.parametrize("M,K,N", [(1, 1, 1), (64, 64, 64), (65, 129, 63), (200, 3000, 130), (4, 5000, 2), (300, 100, 4),
+                                   (1024, 1024, 1024)])
+def test_w1a1_bipolar_xor_path(M, K, N):
+    """Both operands +-1: the XOR-popcount form, dot = K - 2 popcount(XOR) (tiled and few-column kernels)."""
+    rng = np.random.default_rng(M * 3 + K + N)
+    W, A = draw(rng, (M, K), 1, BP), draw(rng, (K, N), 1, BP)
+    want = oracle.gemm(W, A)
+    assert_equal(run_gemm(W, A, 1, BP, 1, BP), want, "W1A1 int32")
+    thr = make_thr(rng, want, 1)
+    Wp = bs.bs_pack_planes(dev(W), 1, bs.BS_BIPOLAR)
+    Ap = bs.bs_pack_planes(dev(A), 1, bs.BS_BIPOLAR, depth_is_strided=True)
+    got = bs.bs_gemm_threshold(Wp, bs.BS_BIPOLAR, Ap, bs.BS_BIPOLAR, K, dev(thr), 1)
+    assert_equal(planes_to_numpy(got), oracle.threshold_pack(want, thr, 1), "W1A1 fused")
+    # a binarised layer chains: the 1-bit output planes are the next layer's bipolar operand
+    W2 = draw(rng, (33, M), 1, BP)
+    want2 = oracle.gemm(W2, (2 * oracle.threshold(want, thr).astype(np.int8) - 1))
+    got2 = bs.bs_gemm(bs.bs_pack_planes(dev(W2), 1, bs.BS_BIPOLAR), bs.BS_BIPOLAR, got, bs.BS_BIPOLAR, M)
+    assert_equal(got2.cpu().numpy(), want2, "W1A1 chained")
+
+
 def test_gemm_extreme_values_and_ldc():
     M, K, N = 66, 640, 50
     for w, a in [(2, 2), (4, 4)]:
