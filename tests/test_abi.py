@@ -56,3 +56,66 @@ def test_argument_errors_are_rejected_on_the_host():
     assert lib.bs_threshold_activate(p, 4, 4, 4, p, 0, p, None) == bs.BS_ERR_INVALID_ARG
     assert lib.bs_im2col_interleaved(p, 2, 3, 3, 8, 7, 7, 1, 0, p, None) == bs.BS_ERR_INVALID_ARG  # kernel > image
     assert lib.bs_im2col_interleaved(p, 2, 3, 3, 8, 3, 3, 0, 0, p, None) == bs.BS_ERR_INVALID_ARG  # stride 0
+
+
+def test_argument_errors_of_the_later_entry_points():
+    lib = bs.load_library()
+    p = 0x1000
+    U, BP = bs.BS_UNSIGNED, bs.BS_BIPOLAR
+    # fused convolution: bipolar activations cannot be zero-padded, kernel larger than image, lowered depth too large
+    assert lib.bs_conv_threshold(p, 1, BP, 8, 8, 32, p, 1, BP, 16, 3, 3, 1, 1, p, 2, p, None) == bs.BS_ERR_UNSUPPORTED
+    assert lib.bs_conv_threshold(p, 2, U, 3, 3, 32, p, 1, BP, 16, 5, 5, 1, 0, p, 2, p, None) == bs.BS_ERR_INVALID_ARG
+    assert lib.bs_conv_threshold(p, 2, U, 64, 64, 4096, p, 1, BP, 16, 7, 7, 1, 3, p, 2, p, None) == bs.BS_ERR_UNSUPPORTED
+    assert lib.bs_conv_threshold(None, 2, U, 8, 8, 32, p, 1, BP, 16, 3, 3, 1, 1, p, 2, p, None) == bs.BS_ERR_INVALID_ARG
+    # pooling window larger than the map
+    assert lib.bs_maxpool_packed(p, 2, 2, 2, 32, 3, 2, p, None) == bs.BS_ERR_INVALID_ARG
+    assert lib.bs_maxpool_packed(p, 5, 8, 8, 32, 3, 2, p, None) == bs.BS_ERR_UNSUPPORTED
+    # dense engine: leading dimensions must be multiples of 16 and >= K; depth bound
+    assert lib.bs_gemm_i8(p, 24, p, 32, 4, 4, 20, p, 4, None) == bs.BS_ERR_ALIGNMENT
+    assert lib.bs_gemm_i8(p, 16, p, 32, 4, 4, 20, p, 4, None) == bs.BS_ERR_INVALID_ARG
+    assert lib.bs_gemm_i8(p, 1 << 17, p, 1 << 17, 4, 4, 1 << 17, p, 4, None) == bs.BS_ERR_OVERFLOW_RISK
+    assert lib.bs_gemm_i8_threshold(p, 32, p, 32, 4, 4, 20, None, 2, p, None) == bs.BS_ERR_INVALID_ARG
+    assert lib.bs_unpack_planes(p, 2, U, 4, 20, p, 16, None) == bs.BS_ERR_INVALID_ARG          # ld < 32
+    assert lib.bs_unpack_planes(p, 2, BP, 4, 20, p, 32, None) == bs.BS_ERR_INVALID_ARG         # bipolar needs 1 bit
+
+
+def test_oracle_c_part_is_clean_under_sanitizers(tmp_path):
+    """The oracle's C file built with AddressSanitizer + UBSan (host only) and driven through a
+    small main(): out-of-bounds or undefined behaviour in the reference would poison every parity claim."""
+    import subprocess
+    import textwrap
+    main_c = tmp_path / "main.c"
+    main_c.write_text(textwrap.dedent("""
+        #include <stdint.h>
+        #include <stdlib.h>
+        #include <stdio.h>
+        void oracle_gemm_i8(const int8_t*, const int8_t*, int32_t*, int64_t, int64_t, int64_t);
+        void oracle_pack(const int32_t*, int64_t, int64_t, int, int, uint64_t*, int64_t);
+        void oracle_bitserial_gemm(const uint64_t*, int, int, const uint64_t*, int, int, int64_t*, int64_t, int64_t, int64_t, int64_t, int64_t);
+        void oracle_conv_direct(const int8_t*, const int8_t*, int32_t*, int, int, int, int, int, int, int, int);
+        void oracle_im2col_plain(const int8_t*, int8_t*, int, int, int, int, int, int, int);
+        int main(void) {
+            enum { M = 7, K = 130, N = 5, S = 4 };
+            int8_t *W = malloc(M * K), *A = malloc(K * N); int32_t *C = malloc(sizeof(int32_t) * M * N);
+            int32_t *Wi = malloc(sizeof(int32_t) * M * K), *Ai = malloc(sizeof(int32_t) * N * K);
+            for (int i = 0; i < M * K; ++i) { W[i] = (int8_t)(i % 4 - 2); Wi[i] = W[i]; }
+            for (int k = 0; k < K; ++k) for (int n = 0; n < N; ++n) { A[k * N + n] = (int8_t)((k + n) % 4); Ai[n * K + k] = A[k * N + n]; }
+            oracle_gemm_i8(W, A, C, M, K, N);
+            uint64_t *Wp = malloc(8 * 2 * M * S), *Ap = malloc(8 * 2 * N * S); int64_t *R = malloc(8 * M * N);
+            oracle_pack(Wi, M, K, 2, 1, Wp, S); oracle_pack(Ai, N, K, 2, 0, Ap, S);
+            oracle_bitserial_gemm(Wp, 2, 1, Ap, 2, 0, R, M, N, S, S, S);
+            for (int i = 0; i < M * N; ++i) if (R[i] != C[i]) { puts("mismatch"); return 1; }
+            int8_t *img = calloc(6 * 6 * 3, 1), *f = calloc(4 * 3 * 3 * 3, 1); int32_t *o = malloc(4 * 6 * 6 * 4);
+            int8_t *L = malloc(27 * 36);
+            oracle_conv_direct(img, f, o, 6, 6, 3, 4, 3, 3, 1, 1);
+            oracle_im2col_plain(img, L, 6, 6, 3, 3, 3, 1, 1);
+            free(W); free(A); free(C); free(Wi); free(Ai); free(Wp); free(Ap); free(R); free(img); free(f); free(o); free(L);
+            puts("ok"); return 0;
+        }"""))
+    exe = tmp_path / "oracle_asan"
+    src = os.path.join(ROOT, "oracle", "bs_oracle.c")
+    # the sanitizer runtimes are linked statically, so no preload order matters
+    subprocess.check_call(["gcc", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                           "-static-libasan", "-static-libubsan", "-std=c11", "-o", str(exe), str(main_c), src])
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0 and "ok" in out.stdout, out.stdout + out.stderr
