@@ -100,6 +100,19 @@ bs_status bs_gemm(const uint64_t *Wp, int wbits, bs_format wfmt,
                   int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc, void *stream);
 
 /*
+ * Approximate product from the higher-order bits only (the approximate-computing use the
+ * paper's conclusion points to): the sum of Alg. 2 restricted to plane pairs with
+ * i + j >= min_shift,
+ *   C[m][n] = sum_{i+j >= min_shift} sgnW(i) sgnA(j) 2^(i+j) sum_d popcount(Wp[i][m][d] & Ap[j][n][d]).
+ * min_shift = 0 is bs_gemm; 0 <= min_shift <= wbits + abits - 2.  With many plane pairs the
+ * omitted pairs cost no time.  Operands must be BS_UNSIGNED or BS_TWOS_COMPLEMENT
+ * (BS_ERR_UNSUPPORTED otherwise); other arguments and errors as bs_gemm.
+ */
+bs_status bs_gemm_topbits(const uint64_t *Wp, int wbits, bs_format wfmt,
+                          const uint64_t *Ap, int abits, bs_format afmt,
+                          int64_t M, int64_t N, int64_t K, int min_shift, int32_t *C, int64_t ldc, void *stream);
+
+/*
  * Successive thresholding (Sec. 2.1.1; integer thresholds per Sec. 2.1.3):
  *   Y[m][n] = number of i < T with C[m][n] >= thr[m][i],  T = 2^obits - 1,
  * written as channel-interleaved bit planes, i.e. packed along m:

@@ -54,6 +54,8 @@ def _load():
         lib.oracle_pack.restype = None
         lib.oracle_bitserial_gemm.argtypes = [vp, i32, i32, vp, i32, i32, vp, i64, i64, i64, i64, i64]
         lib.oracle_bitserial_gemm.restype = None
+        lib.oracle_bitserial_gemm_from.argtypes = [vp, i32, i32, vp, i32, i32, vp, i64, i64, i64, i64, i64, i32]
+        lib.oracle_bitserial_gemm_from.restype = None
         lib.oracle_conv_direct.argtypes = [vp, vp, vp] + [i32] * 8
         lib.oracle_conv_direct.restype = None
         lib.oracle_im2col_plain.argtypes = [vp, vp] + [i32] * 7
@@ -127,6 +129,19 @@ def bitserial_gemm(Wp: np.ndarray, wsigned: bool, Ap: np.ndarray, asigned: bool)
     res = np.empty((rows, cols), dtype=np.int64)
     _load().oracle_bitserial_gemm(_p(Wp), w, int(bool(wsigned)), _p(Ap), a, int(bool(asigned)),
                                   _p(res), rows, cols, ws, ws, as_)
+    return res
+
+
+def bitserial_gemm_topbits(Wp: np.ndarray, wsigned: bool, Ap: np.ndarray, asigned: bool, min_shift: int) -> np.ndarray:
+    """Alg. 2 restricted to the plane pairs with i + j >= min_shift (approximation from the
+    higher-order bits, named as future work in the paper's conclusion).  int64 [rows][cols]."""
+    Wp = np.ascontiguousarray(Wp, dtype=np.uint64)
+    Ap = np.ascontiguousarray(Ap, dtype=np.uint64)
+    w, rows, ws = Wp.shape
+    a, cols, as_ = Ap.shape
+    res = np.empty((rows, cols), dtype=np.int64)
+    _load().oracle_bitserial_gemm_from(_p(Wp), w, int(bool(wsigned)), _p(Ap), a, int(bool(asigned)),
+                                       _p(res), rows, cols, ws, ws, as_, int(min_shift))
     return res
 
 

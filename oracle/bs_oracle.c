@@ -97,14 +97,30 @@ static void binary_gemm(const uint64_t *W, const uint64_t *A, int64_t *res,
                     (int64_t)__builtin_popcountll(W[r * wstride + d] & A[c * astride + d]);
 }
 
+/* min_shift > 0 gives the approximate product the paper's conclusion mentions: only the  */
+/* plane pairs of weight 2^(i+j) >= 2^min_shift are summed.                                */
+void oracle_bitserial_gemm_from(const uint64_t *Wp, int wbits, int wsigned,
+                                const uint64_t *Ap, int abits, int asigned,
+                                int64_t *res, int64_t rows, int64_t cols,
+                                int64_t depth_words, int64_t wstride, int64_t astride, int min_shift);
+
 void oracle_bitserial_gemm(const uint64_t *Wp, int wbits, int wsigned,
                            const uint64_t *Ap, int abits, int asigned,
                            int64_t *res, int64_t rows, int64_t cols,
                            int64_t depth_words, int64_t wstride, int64_t astride)
 {
+    oracle_bitserial_gemm_from(Wp, wbits, wsigned, Ap, abits, asigned, res, rows, cols, depth_words, wstride, astride, 0);
+}
+
+void oracle_bitserial_gemm_from(const uint64_t *Wp, int wbits, int wsigned,
+                                const uint64_t *Ap, int abits, int asigned,
+                                int64_t *res, int64_t rows, int64_t cols,
+                                int64_t depth_words, int64_t wstride, int64_t astride, int min_shift)
+{
     for (int64_t i = 0; i < rows * cols; ++i) res[i] = 0;
     for (int i = 0; i < wbits; ++i)
         for (int j = 0; j < abits; ++j) {
+            if (i + j < min_shift) continue;
             int64_t sgnW = (wsigned && i == wbits - 1) ? -1 : 1;
             int64_t sgnA = (asigned && j == abits - 1) ? -1 : 1;
             binary_gemm(Wp + (int64_t)i * rows * wstride, Ap + (int64_t)j * cols * astride,

@@ -22,7 +22,7 @@ BS_ERR_INVALID_ARG, BS_ERR_UNSUPPORTED, BS_ERR_ALIGNMENT, BS_ERR_OVERFLOW_RISK, 
 BS_UNSIGNED, BS_TWOS_COMPLEMENT, BS_BIPOLAR = 0, 1, 2
 BS_I8, BS_I32 = 0, 1
 
-EXPORTS = ("bs_words_per_row", "bs_lowered_depth", "bs_pack_planes", "bs_gemm", "bs_threshold_activate",
+EXPORTS = ("bs_words_per_row", "bs_lowered_depth", "bs_pack_planes", "bs_gemm", "bs_gemm_topbits", "bs_threshold_activate",
            "bs_gemm_threshold", "bs_im2col_interleaved", "bs_conv_threshold", "bs_maxpool_packed",
            "bs_unpack_planes", "bs_gemm_i8", "bs_gemm_i8_threshold", "bs_streamline_collapse",
            "bs_streamline_thresholds", "bs_status_string", "bs_version")
@@ -51,6 +51,7 @@ def load_library() -> ctypes.CDLL:
     lib.bs_lowered_depth.argtypes = [i64, i64, i64]; lib.bs_lowered_depth.restype = i64
     lib.bs_pack_planes.argtypes = [vp, i32, i64, i64, i64, i32, i32, i32, vp, vp]; lib.bs_pack_planes.restype = i32
     lib.bs_gemm.argtypes = [vp, i32, i32, vp, i32, i32, i64, i64, i64, vp, i64, vp]; lib.bs_gemm.restype = i32
+    lib.bs_gemm_topbits.argtypes = [vp, i32, i32, vp, i32, i32, i64, i64, i64, i32, vp, i64, vp]; lib.bs_gemm_topbits.restype = i32
     lib.bs_threshold_activate.argtypes = [vp, i64, i64, i64, vp, i32, vp, vp]; lib.bs_threshold_activate.restype = i32
     lib.bs_gemm_threshold.argtypes = [vp, i32, i32, vp, i32, i32, i64, i64, i64, vp, i32, vp, vp]
     lib.bs_gemm_threshold.restype = i32
@@ -270,3 +271,16 @@ def bs_streamline_thresholds(t, a, b):
     st = load_library().bs_streamline_thresholds(_np_ptr(t), T, _np_ptr(a), _np_ptr(b), M, _np_ptr(thr), _np_ptr(neg))
     _check(st, "bs_streamline_thresholds")
     return thr, neg
+
+
+def bs_gemm_topbits(Wp: torch.Tensor, wfmt: int, Ap: torch.Tensor, afmt: int, K: int, min_shift: int,
+                    out: torch.Tensor | None = None) -> torch.Tensor:
+    """Approximate C from the plane pairs with i + j >= min_shift only."""
+    wbits, M, _ = Wp.shape
+    abits, N, _ = Ap.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=Wp.device)
+    st = load_library().bs_gemm_topbits(_dev(Wp, "Wp"), wbits, wfmt, _dev(Ap, "Ap"), abits, afmt, M, N, K, min_shift,
+                                        _dev(out, "out"), out.stride(0), _stream())
+    _check(st, "bs_gemm_topbits")
+    return out

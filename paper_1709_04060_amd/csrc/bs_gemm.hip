@@ -39,7 +39,7 @@ bs_status dispatch_wb(const GemmParams &g, int wbits, int abits, bool fuse, bool
 
 bs_status gemm_common(const uint64_t *Wp, int wbits, bs_format wfmt, const uint64_t *Ap, int abits, bs_format afmt,
                       int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc,
-                      const int32_t *thr, int obits, uint64_t *Yp, bool fuse, void *stream)
+                      const int32_t *thr, int obits, uint64_t *Yp, bool fuse, void *stream, int min_shift = 0)
 {
     if (!Wp || !Ap || M <= 0 || N <= 0 || K <= 0) return BS_ERR_INVALID_ARG;
     if (bs_status s = bs::check_bits_fmt(wbits, wfmt)) return s;
@@ -65,6 +65,12 @@ bs_status gemm_common(const uint64_t *Wp, int wbits, bs_format wfmt, const uint6
     g.A = reinterpret_cast<const uint32_t *>(Ap);
     g.M = (int)M; g.N = (int)N; g.Kd = (int)(2 * S);
     set_coefficients(g, wbits, wfmt, abits, afmt, K);
+    if (min_shift > 0) {  // approximate mode: only plane pairs of weight 2^(i+j) >= 2^min_shift contribute
+        if (wfmt == BS_BIPOLAR || afmt == BS_BIPOLAR) return BS_ERR_UNSUPPORTED;
+        for (int i = 0; i < 4; ++i)
+            for (int j = 0; j < 4; ++j)
+                if (i + j < min_shift) g.coef[i * 4 + j] = 0;
+    }
     g.C = C; g.ldc = ldc;
     g.thr = thr; g.obits = obits; g.T = fuse ? (1 << obits) - 1 : 0;
     g.Y = reinterpret_cast<uint32_t *>(Yp);
@@ -136,4 +142,12 @@ extern "C" bs_status bs_conv_threshold(const uint64_t *in, int abits, bs_format 
     g.cStride = stride; g.cPad = pad; g.cOW = OW; g.cKused = (int)(Kl / 32);
     const bool corr = (wfmt == BS_BIPOLAR);
     return dispatch_wb(g, wbits, abits, true, corr, true, false, static_cast<hipStream_t>(stream));
+}
+
+extern "C" bs_status bs_gemm_topbits(const uint64_t *Wp, int wbits, bs_format wfmt, const uint64_t *Ap, int abits,
+                                     bs_format afmt, int64_t M, int64_t N, int64_t K, int min_shift, int32_t *C,
+                                     int64_t ldc, void *stream)
+{
+    if (min_shift < 0 || min_shift > wbits + abits - 2) return BS_ERR_INVALID_ARG;
+    return gemm_common(Wp, wbits, wfmt, Ap, abits, afmt, M, N, K, C, ldc, nullptr, 0, nullptr, false, stream, min_shift);
 }

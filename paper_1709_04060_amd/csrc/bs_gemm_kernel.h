@@ -156,6 +156,7 @@ bs_gemm_kernel(const GemmParams p)
     __shared__ int corr_row[CORR ? BM : 1];
     __shared__ int corr_col[CORR ? BN : 1];
     __shared__ int lut[CONV ? kConvMaxLut : 1];  // lowered dword -> (kernel row, kernel column, channel word)
+    __shared__ int thr_s[FUSE ? BM * 15 : 1];    // thresholds of the tile's rows, fetched while the first stage is in flight
 
     int tile_m, tile_n;
     if (!tile_of_block(p, blockIdx.x, tile_m, tile_n)) return;  // uniform for the workgroup
@@ -263,6 +264,13 @@ bs_gemm_kernel(const GemmParams p)
     const uint4 *ldsA = lds + (WROWS + acol0) * KCH;
 
     fetch(0);
+    if constexpr (FUSE) {
+        // ride on the first stage's memory latency instead of paying a round trip in the epilogue
+        for (int i = tid; i < BM * p.T; i += NT) {
+            const int r = i / p.T;
+            thr_s[i] = (m0 + r < p.M) ? p.thr[(long long)(m0 + r) * p.T + (i - r * p.T)] : 0x7fffffff;
+        }
+    }
     for (int k0 = 0; k0 < p.Kd; k0 += KT) {
         __syncthreads();  // everyone is done reading the previous stage
 #pragma unroll
@@ -304,6 +312,7 @@ bs_gemm_kernel(const GemmParams p)
             for (int i = 0; i < WB; ++i) {
 #pragma unroll 1
                 for (int j = 0; j < AB; ++j) {
+                    if (p.coef[i * 4 + j] == 0) continue;  // plane pair left out (approximate mode): no work spent on it
                     int t[TM][TN];
 #pragma unroll
                     for (int r = 0; r < TM; ++r)
@@ -432,14 +441,18 @@ bs_gemm_kernel(const GemmParams p)
 #pragma unroll
             for (int r = 0; r < TM; ++r) {
                 const int m = m0 + wrow0 + r;
-                const int32_t *th = p.thr + (long long)m * p.T;
+                const int *th = thr_s + (wrow0 + r) * p.T;
+                int y[TN];
 #pragma unroll
-                for (int c = 0; c < TN; ++c) {
-                    int y = 0;
-                    if (m < p.M)
-                        for (int t = 0; t < p.T; ++t) y += (val[r][c] >= th[t]) ? 1 : 0;
-                    ytile[(acol0 + c) * BM + wrow0 + r] = (uint8_t)y;
-                }
+                for (int c = 0; c < TN; ++c) y[c] = 0;
+                if (m < p.M)
+                    for (int t = 0; t < p.T; ++t) {
+                        const int tv = th[t];
+#pragma unroll
+                        for (int c = 0; c < TN; ++c) y[c] += (val[r][c] >= tv) ? 1 : 0;
+                    }
+#pragma unroll
+                for (int c = 0; c < TN; ++c) ytile[(acol0 + c) * BM + wrow0 + r] = (uint8_t)y[c];
             }
         }
         __syncthreads();

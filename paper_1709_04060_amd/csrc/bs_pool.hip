@@ -16,6 +16,9 @@ struct PoolParams {
     int bits, H, W, pix_d, k, stride, OH, OW;
 };
 
+// KW > 0: window size known at compile time, so all taps are loaded before the first
+// comparison (one memory round trip instead of one per tap).  KW == 0: any window size.
+template <int KW>
 __global__ void __launch_bounds__(256) maxpool_kernel(const PoolParams p)
 {
     const int idx = blockIdx.x * 256 + threadIdx.x;
@@ -26,21 +29,38 @@ __global__ void __launch_bounds__(256) maxpool_kernel(const PoolParams p)
     const size_t in_plane = (size_t)p.H * p.W * p.pix_d, out_plane = (size_t)total;
 
     uint32_t best[bs::kMaxBits] = {0, 0, 0, 0};  // codes are unsigned: zero is the identity of max
-    for (int r = 0; r < p.k; ++r)
-        for (int s = 0; s < p.k; ++s) {
-            const size_t at = ((size_t)(oh * p.stride + r) * p.W + (ow * p.stride + s)) * p.pix_d + cd;
-            uint32_t v[bs::kMaxBits] = {0, 0, 0, 0};
-            for (int b = 0; b < p.bits; ++b) v[b] = p.in[b * in_plane + at];
-            // per channel (bit lane): gt = v > best, decided at the highest differing plane
-            uint32_t gt = 0, eq = 0xFFFFFFFFu;
+    // per channel (bit lane): gt = v > best, decided at the highest differing plane
+    auto take_max = [&](const uint32_t (&v)[bs::kMaxBits]) {
+        uint32_t gt = 0, eq = 0xFFFFFFFFu;
 #pragma unroll
-            for (int b = bs::kMaxBits - 1; b >= 0; --b) {
-                gt |= eq & v[b] & ~best[b];
-                eq &= ~(v[b] ^ best[b]);
+        for (int b = bs::kMaxBits - 1; b >= 0; --b) {
+            gt |= eq & v[b] & ~best[b];
+            eq &= ~(v[b] ^ best[b]);
+        }
+#pragma unroll
+        for (int b = 0; b < bs::kMaxBits; ++b) best[b] = (gt & v[b]) | (~gt & best[b]);
+    };
+    if constexpr (KW > 0) {
+        uint32_t v[KW * KW][bs::kMaxBits];
+#pragma unroll
+        for (int r = 0; r < KW; ++r)
+#pragma unroll
+            for (int s = 0; s < KW; ++s) {
+                const size_t at = ((size_t)(oh * p.stride + r) * p.W + (ow * p.stride + s)) * p.pix_d + cd;
+#pragma unroll
+                for (int b = 0; b < bs::kMaxBits; ++b) v[r * KW + s][b] = b < p.bits ? p.in[b * in_plane + at] : 0u;
             }
 #pragma unroll
-            for (int b = 0; b < bs::kMaxBits; ++b) best[b] = (gt & v[b]) | (~gt & best[b]);
-        }
+        for (int t = 0; t < KW * KW; ++t) take_max(v[t]);
+    } else {
+        for (int r = 0; r < p.k; ++r)
+            for (int s = 0; s < p.k; ++s) {
+                const size_t at = ((size_t)(oh * p.stride + r) * p.W + (ow * p.stride + s)) * p.pix_d + cd;
+                uint32_t v[bs::kMaxBits] = {0, 0, 0, 0};
+                for (int b = 0; b < p.bits; ++b) v[b] = p.in[b * in_plane + at];
+                take_max(v);
+            }
+    }
     for (int b = 0; b < p.bits; ++b) p.out[b * out_plane + idx] = best[b];
 }
 
@@ -62,6 +82,10 @@ extern "C" bs_status bs_maxpool_packed(const uint64_t *in, int bits, int H, int 
     p.OW = (W - k) / stride + 1;
     const int64_t total = (int64_t)p.OH * p.OW * p.pix_d;
     if ((int64_t)bits * H * W * p.pix_d >= (int64_t(1) << 31)) return BS_ERR_OVERFLOW_RISK;
-    maxpool_kernel<<<dim3((unsigned)((total + 255) / 256)), 256, 0, static_cast<hipStream_t>(stream)>>>(p);
+    const dim3 grid((unsigned)((total + 255) / 256));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (k == 2) maxpool_kernel<2><<<grid, 256, 0, st>>>(p);
+    else if (k == 3) maxpool_kernel<3><<<grid, 256, 0, st>>>(p);
+    else maxpool_kernel<0><<<grid, 256, 0, st>>>(p);
     return bs::after_launch();
 }

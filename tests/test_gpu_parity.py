@@ -143,6 +143,20 @@ def test_w1a1_bipolar_xor_path(M, K, N):
     assert_equal(got2.cpu().numpy(), want2, "W1A1 chained")
 
 
+@pytest.mark.parametrize("w,wf,a,af", [(2, TC, 2, U), (4, TC, 4, U), (3, U, 4, TC), (4, U, 1, U)])
+@pytest.mark.parametrize("M,K,N", [(70, 1100, 45), (130, 2000, 3), (64, 4096, 600)])
+def test_gemm_topbits(w, wf, a, af, M, K, N):
+    rng = np.random.default_rng(w + a + M + N)
+    W, A = draw(rng, (M, K), w, wf), draw(rng, (K, N), a, af)
+    Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
+    Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
+    Wo, Ao = oracle.pack(W, w, wf), oracle.pack(A.T, a, af)
+    for s in range(0, w + a - 1):
+        got = bs.bs_gemm_topbits(Wp, FMT[wf], Ap, FMT[af], K, s).cpu().numpy()
+        want = oracle.bitserial_gemm_topbits(Wo, wf == TC, Ao, af == TC, s)
+        assert_equal(got.astype(np.int64), want, "topbits min_shift=%d" % s)
+
+
 def test_gemm_extreme_values_and_ldc():
     M, K, N = 66, 640, 50
     for w, a in [(2, 2), (4, 4)]:

@@ -147,3 +147,30 @@ def test_full_size_tiny_config_against_numpy():
     assert np.array_equal(C, d["W"].astype(np.int64) @ d["A"].astype(np.int64))
     bs = oracle.bipolar_weight_gemm(oracle.pack(d["W"], 1, BP), oracle.pack(d["A"].T, 2, U))
     assert np.array_equal(bs, C)
+
+
+@pytest.mark.parametrize("w,a", [(2, 2), (4, 4), (3, 2)])
+def test_topbits_restriction_of_alg2(w, a):
+    """Restricted plane-pair sum against the same sum written with numpy matmuls on unpacked bit
+    matrices; min_shift = 0 is the exact product; the error is bounded by the dropped weights."""
+    rng = np.random.default_rng(w * 10 + a)
+    M, K, N = 6, 200, 5
+    W, A = draw(rng, (M, K), w, TC), draw(rng, (K, N), a, U)
+    Wp, Ap = oracle.pack(W, w, TC), oracle.pack(A.T, a, U)
+    exact = oracle.gemm(W, A).astype(np.int64)
+    assert np.array_equal(oracle.bitserial_gemm_topbits(Wp, True, Ap, False, 0), exact)
+    wcode = W.astype(np.int64) & ((1 << w) - 1)
+    for s in range(1, w + a - 1):
+        want = np.zeros((M, N), dtype=np.int64)
+        dropped = 0
+        for i in range(w):
+            for j in range(a):
+                coef = (-1 if i == w - 1 else 1) << 0
+                term = coef * (1 << (i + j)) * (((wcode >> i) & 1) @ ((A.astype(np.int64) >> j) & 1))
+                if i + j >= s:
+                    want += term
+                else:
+                    dropped += (1 << (i + j)) * K
+        got = oracle.bitserial_gemm_topbits(Wp, True, Ap, False, s)
+        assert np.array_equal(got, want)
+        assert np.abs(got - exact).max() <= dropped
