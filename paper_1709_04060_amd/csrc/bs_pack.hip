@@ -15,7 +15,7 @@
 // adjacent columns (one dword per depth index, so a wavefront reads full 128-byte
 // lines), accumulates vertically along the depth, byte-transposes AFTERWARDS to split
 // the four columns, and the workgroup passes the words through LDS so that every
-// packed row leaves as a 128-byte run.
+// packed row leaves as a 128-byte (mid-sized inputs: 64-byte) run.
 // Generic one-element-per-lane kernels cover unaligned sources.
 #include "bs_common.h"
 
@@ -125,27 +125,31 @@ pack_rows_kernel(const T *__restrict__ src, int64_t rows, int64_t depth, int64_t
 }
 
 // ------------------------------------------------------------------ pack_cols (fast)
-// Workgroup tile: 128 rows (= source columns n) x 16 words (1024 depth indices).
-// Thread (tx, ty): rows 4 tx .. 4 tx + 3, words 2 ty, 2 ty + 1.
-constexpr int PC_ROWS = 128, PC_WORDS = 16;
+// Workgroup tile: 128 rows (= source columns n) x 8 WPT words (512 WPT depth indices).
+// Thread (tx, ty): rows 4 tx .. 4 tx + 3, words WPT ty .. WPT ty + WPT - 1.  WPT = 2 for large
+// inputs (128-byte output runs); WPT = 1 halves the tile so that mid-sized inputs still
+// give every compute unit a workgroup (64-byte runs).
+constexpr int PC_ROWS = 128;
 
-template <typename T, bool BIP>
+template <typename T, bool BIP, int WPT>
 __global__ void __launch_bounds__(256)
 pack_cols_kernel(const T *__restrict__ src, int64_t rows, int64_t depth, int64_t ld, int bits,
                  uint64_t *__restrict__ planes, int64_t S)
 {
-    // [plane][row][8 pairs of words], pair slot XOR-swizzled with (row / 4) & 7
-    __shared__ uint4 tile[bs::kMaxBits * PC_ROWS * (PC_WORDS / 2)];
+    constexpr int PC_WORDS = 8 * WPT;
+    constexpr int PAIRS = PC_WORDS / 2;  // 16-byte slots per row of the LDS tile
+    // [plane][row][PAIRS pairs of words], pair slot XOR-swizzled with (row / 4) & (PAIRS - 1)
+    __shared__ uint4 tile[bs::kMaxBits * PC_ROWS * PAIRS];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const int64_t r0 = (int64_t)blockIdx.x * PC_ROWS;
     const int64_t d0 = (int64_t)blockIdx.y * PC_WORDS;
     const int64_t rq = r0 + 4 * tx;                 // first of this thread's four rows
     const bool full_quad = rq + 4 <= rows;
 
-    uint32_t out[2][bs::kMaxBits][4][2];            // [word][plane][row of the quad][lo/hi dword]
+    uint32_t out[WPT][bs::kMaxBits][4][2];          // [word][plane][row of the quad][lo/hi dword]
 #pragma unroll
-    for (int wd = 0; wd < 2; ++wd) {
-        const int64_t kw = (d0 + 2 * ty + wd) * 64; // first depth index of the word
+    for (int wd = 0; wd < WPT; ++wd) {
+        const int64_t kw = (d0 + WPT * ty + wd) * 64; // first depth index of the word
         uint32_t A[bs::kMaxBits][8];                // [plane][group of 8 depth indices]
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
@@ -187,19 +191,26 @@ pack_cols_kernel(const T *__restrict__ src, int64_t rows, int64_t depth, int64_t
     for (int p = 0; p < bs::kMaxBits; ++p)
         if (p < bits) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                tile[(p * PC_ROWS + 4 * tx + c) * (PC_WORDS / 2) + (ty ^ (tx & 7))] =
-                    make_uint4(out[0][p][c][0], out[0][p][c][1], out[1][p][c][0], out[1][p][c][1]);
+            for (int c = 0; c < 4; ++c) {
+                if constexpr (WPT == 2) {
+                    tile[(p * PC_ROWS + 4 * tx + c) * PAIRS + (ty ^ (tx & (PAIRS - 1)))] =
+                        make_uint4(out[0][p][c][0], out[0][p][c][1], out[1][p][c][0], out[1][p][c][1]);
+                } else {  // one word: half of the pair slot (ty >> 1)
+                    uint2 *slot = reinterpret_cast<uint2 *>(
+                        &tile[(p * PC_ROWS + 4 * tx + c) * PAIRS + ((ty >> 1) ^ (tx & (PAIRS - 1)))]);
+                    slot[ty & 1] = make_uint2(out[0][p][c][0], out[0][p][c][1]);
+                }
+            }
         }
     __syncthreads();
-    // write out: eight consecutive threads cover the 128-byte run of one (plane, row)
-    const int pair = threadIdx.x & 7;
+    // write out: PAIRS consecutive threads cover the contiguous run of one (plane, row)
+    const int pair = threadIdx.x & (PAIRS - 1);
     for (int p = 0; p < bits; ++p)
-        for (int rr = threadIdx.x >> 3; rr < PC_ROWS; rr += 32) {
+        for (int rr = threadIdx.x / PAIRS; rr < PC_ROWS; rr += 256 / PAIRS) {
             const int64_t r = r0 + rr, d = d0 + 2 * pair;
             if (r < rows && d < S)
                 *reinterpret_cast<uint4 *>(planes + ((int64_t)p * rows + r) * S + d) =
-                    tile[(p * PC_ROWS + rr) * (PC_WORDS / 2) + (pair ^ ((rr >> 2) & 7))];
+                    tile[(p * PC_ROWS + rr) * PAIRS + (pair ^ ((rr >> 2) & (PAIRS - 1)))];
         }
 }
 
@@ -276,10 +287,18 @@ bs_status launch_pack(const T *src, int64_t rows, int64_t depth, int64_t ld, int
     } else {
         const bool fast = bs::aligned(src, quad_align) && (ld * sizeof(T)) % quad_align == 0;
         if (fast) {
-            dim3 grid((unsigned)((rows + PC_ROWS - 1) / PC_ROWS), (unsigned)((S + PC_WORDS - 1) / PC_WORDS));
+            const int64_t gx = (rows + PC_ROWS - 1) / PC_ROWS;
+            const bool big = gx * ((S + 15) / 16) >= 512;   // enough 16-word tiles to fill the chip twice
+            const int words = big ? 16 : 8;
+            dim3 grid((unsigned)gx, (unsigned)((S + words - 1) / words));
             if (grid.y > 65535) return BS_ERR_OVERFLOW_RISK;
-            if (bip) pack_cols_kernel<T, true><<<grid, 256, 0, st>>>(src, rows, depth, ld, bits, planes, S);
-            else pack_cols_kernel<T, false><<<grid, 256, 0, st>>>(src, rows, depth, ld, bits, planes, S);
+            if (big) {
+                if (bip) pack_cols_kernel<T, true, 2><<<grid, 256, 0, st>>>(src, rows, depth, ld, bits, planes, S);
+                else pack_cols_kernel<T, false, 2><<<grid, 256, 0, st>>>(src, rows, depth, ld, bits, planes, S);
+            } else {
+                if (bip) pack_cols_kernel<T, true, 1><<<grid, 256, 0, st>>>(src, rows, depth, ld, bits, planes, S);
+                else pack_cols_kernel<T, false, 1><<<grid, 256, 0, st>>>(src, rows, depth, ld, bits, planes, S);
+            }
         } else {
             dim3 grid((unsigned)((rows + 63) / 64), (unsigned)((S + 3) / 4));
             if (grid.y > 65535) return BS_ERR_OVERFLOW_RISK;
