@@ -123,7 +123,7 @@ extern "C" bs_status bs_conv_threshold(const uint64_t *in, int abits, bs_format 
     const int64_t S = bs_words_per_row(Kl);
     const int OH = (H + 2 * pad - kh) / stride + 1, OW = (W + 2 * pad - kw) / stride + 1;
     const int64_t N = (int64_t)OH * OW;
-    if (Kl / 32 > kConvMaxLut || kh > 127 || kw > 127) return BS_ERR_UNSUPPORTED;
+    if (2 * S > kConvMaxLut || kh > 127 || kw > 127) return BS_ERR_UNSUPPORTED;
     if ((Kl << (wbits + abits)) >= (int64_t(1) << 31)) return BS_ERR_OVERFLOW_RISK;
     const int64_t lim = int64_t(1) << 31;
     const int64_t pix = 2 * bs_words_per_row(C);

@@ -33,8 +33,7 @@
 
 namespace bs {
 
-constexpr int KT = 32;      // dwords of depth per packed row and stage
-constexpr int KCH = KT / 4; // 16-byte chunks per row and stage
+constexpr int kStageDwords = 32;  // dwords of depth per packed row and stage (large grids)
 
 struct GemmParams {
     const uint32_t *W;  // dword view of Wp
@@ -135,11 +134,14 @@ __device__ __forceinline__ bool tile_of_block(const GemmParams &p, int bid, int 
 // loader gathers each lowered column's words from the image (Sec. 3.2's lowering folded
 // into the operand fetch, so the lowered matrix never exists in memory).
 // XOR: both operands bipolar (W1A1): popcount(XOR) instead of popcount(AND), no correction terms.
-template <int WB, int AB, int TM, int TN, int WM, int WN, int KS, bool FUSE, bool CORR, bool CONV = false,
+// KT: dwords of depth per packed row and stage.  Small grids are latency-bound, so their
+// stages are made as deep as LDS allows: fewer stages, fewer exposed memory round trips.
+template <int WB, int AB, int TM, int TN, int WM, int WN, int KS, int KT, bool FUSE, bool CORR, bool CONV = false,
           bool XOR = false>
 __global__ void __launch_bounds__(WM * WN * KS * 64)
 bs_gemm_kernel(const GemmParams p)
 {
+    constexpr int KCH = KT / 4;  // 16-byte chunks per row and stage
     static_assert(!XOR || (WB == 1 && AB == 1 && !CORR), "the XOR form exists for one plane per operand only");
     constexpr int BM = 8 * TM * WM, BN = 8 * TN * WN, NT = 64 * WM * WN * KS;
     constexpr int WROWS = WB * BM, AROWS = AB * BN, ROWS = WROWS + AROWS;
@@ -155,7 +157,8 @@ bs_gemm_kernel(const GemmParams p)
     __shared__ uint4 lds[CHUNKS];
     __shared__ int corr_row[CORR ? BM : 1];
     __shared__ int corr_col[CORR ? BN : 1];
-    __shared__ int lut[CONV ? kConvMaxLut : 1];  // lowered dword -> (kernel row, kernel column, channel word)
+    // lowered dword -> (kernel row, kernel column, channel word), -1 past the data; 16-byte reads
+    __shared__ __attribute__((aligned(16))) int lut[CONV ? kConvMaxLut + 4 : 4];
     __shared__ int thr_s[FUSE ? BM * 15 : 1];    // thresholds of the tile's rows, fetched while the first stage is in flight
 
     int tile_m, tile_n;
@@ -209,16 +212,28 @@ bs_gemm_kernel(const GemmParams p)
         for (int i = tid; i < BN; i += NT) corr_col[i] = 0;
     }
     if constexpr (CONV) {
-        for (int q = tid; q < p.cKused; q += NT) {
+        for (int q = tid; q < p.Kd; q += NT) {
             const int tap = q / p.cCd, cd = q - tap * p.cCd;
             const int fr = tap / p.cKW, fs = tap - fr * p.cKW;
-            lut[q] = (fr << 24) | (fs << 16) | cd;
+            lut[q] = q < p.cKused ? ((fr << 24) | (fs << 16) | cd) : -1;
         }
         __syncthreads();
     }
 
     uint4 stage[CPT];
     auto fetch = [&](int k0) {
+        // CONV: the table entries of all activation chunks first (one 16-byte LDS read each),
+        // so that a single wait precedes the gathers instead of one per word
+        int4 tap4[CONV ? CPT : 1];
+        if constexpr (CONV) {
+#pragma unroll
+            for (int s = 0; s < CPT; ++s) {
+                const int c = (tid + s * NT) % KCH;
+                tap4[s] = make_int4(-1, -1, -1, -1);
+                if (s * NT >= WROWS * KCH && goff[s] >= 0 && k0 + c * 4 < p.Kd)
+                    tap4[s] = *reinterpret_cast<const int4 *>(&lut[k0 + c * 4]);
+            }
+        }
 #pragma unroll
         for (int s = 0; s < CPT; ++s) {
             const int c = (tid + s * NT) % KCH;
@@ -230,21 +245,16 @@ bs_gemm_kernel(const GemmParams p)
                 if (goff[s] >= 0 && k0 + c * 4 < p.Kd)
                     v = *reinterpret_cast<const uint4 *>(p.A + (size_t)(unsigned)goff[s] + k0);
             } else {
-                if (goff[s] >= 0) {
-                    uint32_t e[4];
+                const int l[4] = {tap4[s].x, tap4[s].y, tap4[s].z, tap4[s].w};
+                uint32_t e[4];
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const int q = k0 + c * 4 + t;
-                        e[t] = 0;
-                        if (q < p.cKused) {
-                            const int l = lut[q];
-                            const int ih = pix_h[s] + (l >> 24), iw = pix_w[s] + ((l >> 16) & 0xFF);
-                            if (ih >= 0 && ih < p.cH && iw >= 0 && iw < p.cW)
-                                e[t] = p.A[(size_t)(unsigned)goff[s] + (size_t)(ih * p.cW + iw) * p.cPix + (l & 0xFFFF)];
-                        }
-                    }
-                    v = make_uint4(e[0], e[1], e[2], e[3]);
+                for (int t = 0; t < 4; ++t) {
+                    e[t] = 0;
+                    const int ih = pix_h[s] + (l[t] >> 24), iw = pix_w[s] + ((l[t] >> 16) & 0xFF);
+                    if (l[t] >= 0 && ih >= 0 && ih < p.cH && iw >= 0 && iw < p.cW)
+                        e[t] = p.A[(size_t)(unsigned)goff[s] + (size_t)(ih * p.cW + iw) * p.cPix + (l[t] & 0xFFFF)];
                 }
+                v = make_uint4(e[0], e[1], e[2], e[3]);
             }
             stage[s] = v;
         }
@@ -285,6 +295,7 @@ bs_gemm_kernel(const GemmParams p)
 #pragma unroll
             for (int qq = 0; qq < KCH / KS; ++qq) {
                 const int q = qq * KS + ks;
+                if (KT > kStageDwords && k0 + q * 4 >= p.Kd) continue;  // deep stages: skip chunks past the depth
                 uint4 w[WB][TM], a[AB][TN];
 #pragma unroll
                 for (int i = 0; i < WB; ++i)
@@ -321,6 +332,7 @@ bs_gemm_kernel(const GemmParams p)
 #pragma unroll
                     for (int qq = 0; qq < KCH / KS; ++qq) {
                         const int q = qq * KS + ks;
+                        if (KT > kStageDwords && k0 + q * 4 >= p.Kd) continue;
                         uint4 w[TM], a[TN];
 #pragma unroll
                         for (int r = 0; r < TM; ++r) w[r] = ldsW[(i * BM + r) * KCH + (q ^ ly)];
@@ -513,7 +525,7 @@ inline long long plan_tile_order(GemmParams &g, int BM, int BN, int wbits, int a
     return best_blocks;
 }
 
-template <int WB, int AB, int TM, int TN, int WM, int WN, int KS>
+template <int WB, int AB, int TM, int TN, int WM, int WN, int KS, int KT>
 bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, bool xr, hipStream_t st)
 {
     constexpr int BM = 8 * TM * WM, BN = 8 * TN * WN;
@@ -529,8 +541,8 @@ bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, bo
     if (xr) {  // both operands bipolar: one plane each
         if constexpr (WB == 1 && AB == 1) {
             if (conv) return BS_ERR_UNSUPPORTED;
-            if (fuse) bs_gemm_kernel<1, 1, TM, TN, WM, WN, KS, true, false, false, true><<<grid, block, 0, st>>>(g);
-            else bs_gemm_kernel<1, 1, TM, TN, WM, WN, KS, false, false, false, true><<<grid, block, 0, st>>>(g);
+            if (fuse) bs_gemm_kernel<1, 1, TM, TN, WM, WN, KS, KT, true, false, false, true><<<grid, block, 0, st>>>(g);
+            else bs_gemm_kernel<1, 1, TM, TN, WM, WN, KS, KT, false, false, false, true><<<grid, block, 0, st>>>(g);
             return bs::after_launch();
         } else {
             return BS_ERR_INVALID_ARG;
@@ -538,14 +550,14 @@ bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, bo
     }
     if (conv) {  // implicit lowering exists with the thresholding epilogue only
         if (!fuse) return BS_ERR_UNSUPPORTED;
-        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, true, CAN_CORR, true><<<grid, block, 0, st>>>(g);
-        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, true, false, true><<<grid, block, 0, st>>>(g);
+        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, CAN_CORR, true><<<grid, block, 0, st>>>(g);
+        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, false, true><<<grid, block, 0, st>>>(g);
     } else if (fuse) {
-        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, true, CAN_CORR><<<grid, block, 0, st>>>(g);
-        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, true, false><<<grid, block, 0, st>>>(g);
+        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, CAN_CORR><<<grid, block, 0, st>>>(g);
+        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, false><<<grid, block, 0, st>>>(g);
     } else {
-        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, false, CAN_CORR><<<grid, block, 0, st>>>(g);
-        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, false, false><<<grid, block, 0, st>>>(g);
+        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, false, CAN_CORR><<<grid, block, 0, st>>>(g);
+        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, false, false><<<grid, block, 0, st>>>(g);
     }
     return bs::after_launch();
 }
@@ -556,8 +568,9 @@ bs_status launch_planes(const GemmParams &g, bool fuse, bool corr, bool conv, bo
     // Large grids: 64 x 64 tiles, four wavefronts side by side.  Small grids: 32 x 32
     // tiles whose four wavefronts split the depth, so that more wavefronts exist.
     const long long tiles64 = (long long)((g.M + 63) / 64) * ((g.N + 63) / 64);
-    if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4>(g, fuse, corr, conv, xr, st);
-    return launch_cfg<WB, AB, 4, 4, 2, 2, 1>(g, fuse, corr, conv, xr, st);
+    constexpr int KT_SMALL = kStageDwords;  // deeper stages were measured and bring nothing: the stage count is not what bounds small grids
+    if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4, KT_SMALL>(g, fuse, corr, conv, xr, st);
+    return launch_cfg<WB, AB, 4, 4, 2, 2, 1, kStageDwords>(g, fuse, corr, conv, xr, st);
 }
 
 // Defined once per WB in bs_gemm_w<WB>.hip (explicit instantiation) to keep builds parallel.
