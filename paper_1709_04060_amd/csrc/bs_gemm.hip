@@ -60,7 +60,7 @@ bs_status gemm_common(const uint64_t *Wp, int wbits, bs_format wfmt, const uint6
     const int64_t lim = int64_t(1) << 31;
     if (wbits * M * S * 2 >= lim || abits * N * S * 2 >= lim || M >= lim || N >= lim) return BS_ERR_OVERFLOW_RISK;
 
-    GemmParams g;
+    GemmParams g{};
     g.W = reinterpret_cast<const uint32_t *>(Wp);
     g.A = reinterpret_cast<const uint32_t *>(Ap);
     g.M = (int)M; g.N = (int)N; g.Kd = (int)(2 * S);
@@ -84,6 +84,7 @@ bs_status gemm_common(const uint64_t *Wp, int wbits, bs_format wfmt, const uint6
         for (int i = 0; i < 4; ++i) g.crow[i] = g.ccol[i] = 0;
     }
     const bool corr = !xr && ((wfmt == BS_BIPOLAR) || (afmt == BS_BIPOLAR));
+    g.stream_weights = (long long)wbits * M * S * 8 >= kStreamWeightBytes;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (gemv_applicable(g, abits, afmt == BS_BIPOLAR, wfmt == BS_BIPOLAR)) return launch_gemv(g, wbits, abits, fuse, xr, st);
     return dispatch_wb(g, wbits, abits, fuse, corr, false, xr, st);
@@ -129,7 +130,7 @@ extern "C" bs_status bs_conv_threshold(const uint64_t *in, int abits, bs_format 
     const int64_t pix = 2 * bs_words_per_row(C);
     if (wbits * (int64_t)F * S * 2 >= lim || abits * (int64_t)H * W * pix >= lim || N >= lim) return BS_ERR_OVERFLOW_RISK;
 
-    GemmParams g;
+    GemmParams g{};
     g.W = reinterpret_cast<const uint32_t *>(Fp);
     g.A = reinterpret_cast<const uint32_t *>(in);
     g.M = F; g.N = (int)N; g.Kd = (int)(2 * S);

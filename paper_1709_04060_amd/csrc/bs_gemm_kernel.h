@@ -62,7 +62,12 @@ struct GemmParams {
     int cStride, cPad;
     int cOW;            // output width (columns n = oh * cOW + ow)
     int cKused;         // dwords of a lowered column that carry data: kh * kw * cCd
+    // single-column kernel: read the weights with the non-temporal hint (set for large weight sets)
+    int stream_weights;
 };
+
+// weight bytes from which the few-column kernel streams past the caches
+constexpr long long kStreamWeightBytes = 64ll << 20;
 
 constexpr int kConvMaxLut = 2048;  // lowered dwords the implicit-lowering kernels can index (65536 depth bits)
 
