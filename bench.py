@@ -27,7 +27,7 @@ BINARY_PEAK_TOPS = VALU_LANE_OPS / 2 * 32 * 2 / 1e12           # one AND + one B
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per bs_gemm launch on the W2A2 4096^3 workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE scaled by a 256 MiB copy (profiles/pmc_fetch_write_w2a2_4096.md): 24.5 MiB + 64 MiB
-GEMM_TRAFFIC_BYTES = int((12544.4 * 2.0 + 65536.0) * 1024)
+GEMM_TRAFFIC_BYTES = int((12557.1 * 2.0 + 65536.0) * 1024)
 
 
 def main() -> int:
