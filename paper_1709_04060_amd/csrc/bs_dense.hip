@@ -59,6 +59,87 @@ __device__ __forceinline__ uint4 mask_tail(uint4 v, int k, int K)
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// Epilogue shared by the two dense kernels: int32 store, or successive thresholding with
+// the packed-plane output.  `lds` is the (no longer needed) operand space of the caller.
+template <int WTM, int WTN, bool FUSE>
+__device__ __forceinline__ void dense_epilogue(const DenseParams &p, v16i (&acc)[WTM][WTN], unsigned char *lds,
+                                               int m0, int n0, int tile_m)
+{
+    constexpr int BM = 64 * WTM;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, lg = lane >> 5;
+    (void)tile_m;
+    if constexpr (!FUSE) {
+#pragma unroll
+        for (int a = 0; a < WTM; ++a)
+#pragma unroll
+            for (int b = 0; b < WTN; ++b) {
+                const int n = n0 + (wn * WTN + b) * 32 + li;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + (wm * WTM + a) * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
+                    if (m < p.M && n < p.N) p.C[(long long)m * p.ldc + n] = acc[a][b][v];
+                }
+            }
+    } else {
+        // thresholds of the tile's rows -> LDS (the operand tiles are no longer needed),
+        // padded to 16 per row with INT_MAX (never reached) so that a row is four 16-byte reads
+        __syncthreads();
+        int4 *tl = reinterpret_cast<int4 *>(lds);  // [BM][4]
+        for (int it = tid; it < BM * 16; it += 256) {
+            const int r = it >> 4, t = it & 15;
+            reinterpret_cast<int32_t *>(tl)[it] =
+                (m0 + r < p.M && t < p.T) ? p.thr[(long long)(m0 + r) * p.T + t] : 0x7fffffff;
+        }
+        __syncthreads();
+        const int nq = (p.T + 3) >> 2;  // 16-byte groups of thresholds actually used
+#pragma unroll
+        for (int a = 0; a < WTM; ++a) {
+            const int rbase = (wm * WTM + a) * 32;  // first row of this 32-row band within the block tile
+            uint32_t word[WTN][4];
+#pragma unroll
+            for (int b = 0; b < WTN; ++b)
+#pragma unroll
+                for (int pl = 0; pl < 4; ++pl) word[b][pl] = 0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rr = 8 * (v >> 2) + 4 * lg + (v & 3);
+                uint32_t y[WTN];
+#pragma unroll
+                for (int b = 0; b < WTN; ++b) y[b] = 0;
+                // one row's thresholds serve the WTN column tiles this lane holds
+                for (int q = 0; q < nq; ++q) {
+                    const int4 th = tl[(rbase + rr) * 4 + q];
+#pragma unroll
+                    for (int b = 0; b < WTN; ++b) {
+                        const int c = acc[a][b][v];
+                        y[b] += (uint32_t)(c >= th.x) + (uint32_t)(c >= th.y) + (uint32_t)(c >= th.z) + (uint32_t)(c >= th.w);
+                    }
+                }
+                const bool live = m0 + rbase + rr < p.M;
+#pragma unroll
+                for (int b = 0; b < WTN; ++b)
+#pragma unroll
+                    for (int pl = 0; pl < 4; ++pl) word[b][pl] |= (live ? ((y[b] >> pl) & 1u) : 0u) << rr;
+            }
+            // Row bands cover a multiple of 128 rows, i.e. at least the Yd words of a column, so
+            // every word (padding included) is written by some band; words beyond Yd (a 256-row
+            // tile over a shorter column) are dropped.
+            const int wi = (m0 + rbase) / 32;
+#pragma unroll
+            for (int b = 0; b < WTN; ++b) {
+                const int n = n0 + (wn * WTN + b) * 32 + li;
+                // the two half-wavefronts hold complementary rows of the same column
+#pragma unroll
+                for (int pl = 0; pl < 4; ++pl) word[b][pl] |= __shfl_xor(word[b][pl], 32);
+                if (lg == 0 && n < p.N && wi < p.Yd)
+                    for (int pl = 0; pl < p.obits; ++pl) p.Y[((long long)pl * p.N + n) * p.Yd + wi] = word[b][pl];
+            }
+        }
+    }
+}
+
 template <int WTM, int WTN, bool FUSE>
 __global__ void __launch_bounds__(256)
 dense_gemm_kernel(const DenseParams p)
@@ -226,75 +307,140 @@ dense_gemm_kernel(const DenseParams p)
         step(P1{}, std::false_type{}, i + 1);
     }
 
-    // ---- epilogue ----
-    if constexpr (!FUSE) {
+    dense_epilogue<WTM, WTN, FUSE>(p, acc, lds, m0, n0, tile_m);
+}
+
+// ------------------------------------------------------------------ variant with direct global -> LDS loads
+// Same tiling and MFMA schedule; the operand stages go from memory straight into LDS
+// (global_load_lds_dwordx4), three stages deep, without passing through registers: no
+// ds_write instructions, no staging registers, loads issued a stage and a half ahead of
+// their use.  Such a load writes the 64 lanes' 16 bytes to consecutive LDS addresses, so
+// a row is 64 unpadded bytes; bank conflicts of the fragment reads are avoided by an XOR
+// swizzle applied on the GLOBAL side (lane l of a load fetches chunk (l % 4) ^ f(row) of
+// its row, f(row) = (row / 2) % 4) and undone by the reader.  Needs a depth that is a
+// multiple of 64 (no tail to mask); other depths use the register-staged kernel above.
+typedef __attribute__((address_space(3))) void lds_void;
+
+template <int WTM, int WTN, bool FUSE>
+__global__ void __launch_bounds__(256)
+dense_gemm_lds_kernel(const DenseParams p)
+{
+    constexpr int BM = 64 * WTM, BN = 64 * WTN;
+    constexpr int ROWS = BM + BN;
+    constexpr int TILE = ROWS * DK;              // bytes per stage, rows unpadded
+    constexpr int LPW = ROWS / 16 / 4;           // load instructions per wavefront and stage (16 rows each)
+    constexpr int NBUF = 3;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[NBUF * TILE];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, lg = lane >> 5;
+    const int tile_m = blockIdx.x / p.gx, tile_n = blockIdx.x % p.gx;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    // ---- loader: instruction j of this wavefront covers stacked rows (wave * LPW + j) * 16 .. + 15 ----
+    const int8_t *gsrc[LPW];
+#pragma unroll
+    for (int j = 0; j < LPW; ++j) {
+        const int row = (wave * LPW + j) * 16 + (lane >> 2);
+        const int c = (lane & 3) ^ ((row >> 1) & 3);
+        if (row < BM) {
+            const int m = m0 + row < p.M ? m0 + row : p.M - 1;
+            gsrc[j] = p.W + (long long)m * p.ldw + c * 16;
+        } else {
+            const int n = n0 + (row - BM) < p.N ? n0 + (row - BM) : p.N - 1;
+            gsrc[j] = p.A + (long long)n * p.lda + c * 16;
+        }
+    }
+    auto issue = [&](int buf, int k0) {
+#pragma unroll
+        for (int j = 0; j < LPW; ++j)
+            __builtin_amdgcn_global_load_lds((const void *)(gsrc[j] + k0), (lds_void *)(lds + buf * TILE + (wave * LPW + j) * 16 * DK),
+                                             16, 0, 0);
+    };
+
+    v16i acc[WTM][WTN];
+#pragma unroll
+    for (int a = 0; a < WTM; ++a)
+#pragma unroll
+        for (int b = 0; b < WTN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
+
+    // fragment addresses: row r of the tile, logical chunk c -> r * 64 + 16 * (c ^ f(r)); the
+    // tile rows of a lane differ by multiples of 32, so f(r) = (li / 2) % 4 for all of them
+    const int fsw = (li >> 1) & 3;
+    const int rowW = (wm * 32 * WTM + li) * DK, rowA = (BM + wn * 32 * WTN + li) * DK;
+    v4i fa[2][WTM], fb[2][WTN];
+    auto load_frags = [&](int set, int buf, int sub) {
+        const int off = 16 * ((2 * sub + lg) ^ fsw);
+        const unsigned char *bw = lds + buf * TILE + rowW + off, *ba = lds + buf * TILE + rowA + off;
+#pragma unroll
+        for (int a = 0; a < WTM; ++a) fa[set][a] = *reinterpret_cast<const v4i *>(bw + a * 32 * DK);
+#pragma unroll
+        for (int b = 0; b < WTN; ++b) fb[set][b] = *reinterpret_cast<const v4i *>(ba + b * 32 * DK);
+    };
+    auto mfmas = [&](int set) {
 #pragma unroll
         for (int a = 0; a < WTM; ++a)
 #pragma unroll
-            for (int b = 0; b < WTN; ++b) {
-                const int n = n0 + (wn * WTN + b) * 32 + li;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = m0 + (wm * WTM + a) * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-                    if (m < p.M && n < p.N) p.C[(long long)m * p.ldc + n] = acc[a][b][v];
-                }
-            }
-    } else {
-        // thresholds of the tile's rows -> LDS (the operand tiles are no longer needed),
-        // padded to 16 per row with INT_MAX (never reached) so that a row is four 16-byte reads
-        __syncthreads();
-        int4 *tl = reinterpret_cast<int4 *>(lds);  // [BM][4]
-        for (int it = tid; it < BM * 16; it += 256) {
-            const int r = it >> 4, t = it & 15;
-            reinterpret_cast<int32_t *>(tl)[it] =
-                (m0 + r < p.M && t < p.T) ? p.thr[(long long)(m0 + r) * p.T + t] : 0x7fffffff;
-        }
-        __syncthreads();
-        const int nq = (p.T + 3) >> 2;  // 16-byte groups of thresholds actually used
-#pragma unroll
-        for (int a = 0; a < WTM; ++a) {
-            const int rbase = (wm * WTM + a) * 32;  // first row of this 32-row band within the block tile
-            uint32_t word[WTN][4];
-#pragma unroll
             for (int b = 0; b < WTN; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][a], fb[set][b], acc[a][b], 0, 0, 0);
+    };
+
+    const int nst = p.K / DK;
+    // One stage.  MORE: stage i + 2 exists and is requested now (branch-free main loop, so that
+    // the loads can be spread between the MFMAs); the last two stages run without requests.
+    auto step = [&](auto more_t, int i, int cur) {
+        constexpr bool MORE = decltype(more_t)::value;
+        const int nxt = cur == NBUF - 1 ? 0 : cur + 1, nx2 = nxt == NBUF - 1 ? 0 : nxt + 1;
+        // buffer nx2 held stage i - 1: nobody reads it after the previous iteration's barrier
+        if constexpr (MORE) issue(nx2, (i + 2) * DK);
+        load_frags(1, cur, 1);
+        mfmas(0);
+        if constexpr (MORE) {
 #pragma unroll
-                for (int pl = 0; pl < 4; ++pl) word[b][pl] = 0;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int rr = 8 * (v >> 2) + 4 * lg + (v & 3);
-                uint32_t y[WTN];
-#pragma unroll
-                for (int b = 0; b < WTN; ++b) y[b] = 0;
-                // one row's thresholds serve the WTN column tiles this lane holds
-                for (int q = 0; q < nq; ++q) {
-                    const int4 th = tl[(rbase + rr) * 4 + q];
-#pragma unroll
-                    for (int b = 0; b < WTN; ++b) {
-                        const int c = acc[a][b][v];
-                        y[b] += (uint32_t)(c >= th.x) + (uint32_t)(c >= th.y) + (uint32_t)(c >= th.z) + (uint32_t)(c >= th.w);
-                    }
-                }
-                const bool live = m0 + rbase + rr < p.M;
-#pragma unroll
-                for (int b = 0; b < WTN; ++b)
-#pragma unroll
-                    for (int pl = 0; pl < 4; ++pl) word[b][pl] |= (live ? ((y[b] >> pl) & 1u) : 0u) << rr;
-            }
-            // Row bands cover a multiple of 128 rows, i.e. at least the Yd words of a column, so
-            // every word (padding included) is written by some band; words beyond Yd (a 256-row
-            // tile over a shorter column) are dropped.
-            const int wi = (m0 + rbase) / 32;
-#pragma unroll
-            for (int b = 0; b < WTN; ++b) {
-                const int n = n0 + (wn * WTN + b) * 32 + li;
-                // the two half-wavefronts hold complementary rows of the same column
-#pragma unroll
-                for (int pl = 0; pl < 4; ++pl) word[b][pl] |= __shfl_xor(word[b][pl], 32);
-                if (lg == 0 && n < p.N && wi < p.Yd)
-                    for (int pl = 0; pl < p.obits; ++pl) p.Y[((long long)pl * p.N + n) * p.Yd + wi] = word[b][pl];
+            for (int r = 0; r < LPW; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read (the LDS-bound loads)
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
+        // A bare s_barrier with explicit counters: __syncthreads() carries a full fence, i.e. a
+        // wait for ALL outstanding loads, including the ones just issued for stage i + 2.  Needed
+        // here: this wavefront's part of stage i + 1 has landed (at most the LPW newer loads still
+        // outstanding) and its LDS reads of the current buffer are done.
+        if constexpr (MORE) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(LPW) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        if (MORE || i + 1 < nst) load_frags(0, nxt, 0);
+        mfmas(1);
+#pragma unroll
+        for (int r = 0; r < LPW; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    issue(0, 0);
+    if (nst > 1) issue(1, DK);
+    if (nst > 1) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LPW) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    load_frags(0, 0, 0);
+    int cur = 0, i = 0;
+    for (; i + 2 < nst; ++i) {
+        step(std::true_type{}, i, cur);
+        cur = cur == NBUF - 1 ? 0 : cur + 1;
     }
+    for (; i < nst; ++i) {
+        step(std::false_type{}, i, cur);
+        cur = cur == NBUF - 1 ? 0 : cur + 1;
+    }
+
+    dense_epilogue<WTM, WTN, FUSE>(p, acc, lds, m0, n0, tile_m);
 }
 
 // ------------------------------------------------------------------ unpack (planes -> int8)
@@ -335,8 +481,13 @@ bs_status launch_dense(DenseParams &p, bool fuse, hipStream_t st)
     p.gy = (p.M + BM - 1) / BM;
     const long long blocks = (long long)p.gx * p.gy;
     if (blocks >= (1LL << 31)) return BS_ERR_UNSUPPORTED;
-    if (fuse) dense_gemm_kernel<WTM, WTN, true><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
-    else dense_gemm_kernel<WTM, WTN, false><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+    if (p.K % DK == 0) {  // no depth tail: operands can go straight from memory to LDS
+        if (fuse) dense_gemm_lds_kernel<WTM, WTN, true><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+        else dense_gemm_lds_kernel<WTM, WTN, false><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+    } else {
+        if (fuse) dense_gemm_kernel<WTM, WTN, true><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+        else dense_gemm_kernel<WTM, WTN, false><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+    }
     return bs::after_launch();
 }
 
