@@ -304,6 +304,15 @@ def extras(bs, workloads, dev, timed):
     ms = timed_graph([lambda: bs.bs_unpack_planes(Wp2, TC, 4096, out=W8)], 20)
     out["unpack_4096x4096_2_planes_to_i8"] = {"us": round(ms * 1e3, 2),
                                               "GBps": round((Wp2.numel() * 8 + W8.numel()) / ms / 1e6, 1)}
+    # stand-alone thresholding of a large int32 result (the unfused route of S5)
+    Cbig = torch.randint(-40000, -20000, (8192, 8192), dtype=torch.int32, device="cuda")
+    thb = thr_for(8192, 4) - 30000
+    Yb = torch.empty((4, 8192, bs.bs_words_per_row(8192)), dtype=torch.int64, device="cuda")
+    ms = timed_graph([lambda: bs.bs_threshold_activate(Cbig, thb, 4, out=Yb)], 10)
+    byts = Cbig.numel() * 4 + Yb.numel() * 8 + thb.numel() * 4
+    out["threshold_activate_8192x8192_4bit"] = {"us": round(ms * 1e3, 2), "GBps": round(byts / ms / 1e6, 1),
+                                                "frac_of_hbm_peak": round(byts / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    del Cbig, Yb
     # interleaved lowering of conv2 alone, and the two pack kernels
     x = planes(2, 27 * 27, 96)
     low = torch.empty((2, 729, bs.bs_words_per_row(2400)), dtype=torch.int64, device="cuda")

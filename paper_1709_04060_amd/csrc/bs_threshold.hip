@@ -2,10 +2,12 @@
 // thresholds per Sec. 2.1.3): count the thresholds each int32 accumulator reaches and
 // emit the few-bit result as channel-interleaved bit planes (packed along the rows m).
 //
-// One thread produces one 32-bit output word per plane: 32 consecutive rows of one
-// column.  Lanes run along the column index so that the int32 reads of C coalesce; the
-// 32 rows of a word are uniform across the wavefront, so their thresholds are read
-// once per wavefront through the scalar path.
+// A workgroup covers 128 rows x 64 columns: lanes run along the column index so that the
+// int32 reads of C coalesce, each wavefront produces one 32-bit output word (32 rows) per
+// plane and column.  All 32 accumulators of a thread are requested before the first
+// comparison (one memory round trip), and the thresholds of the 128 rows are staged in LDS,
+// padded to 16 per row with INT_MAX (never reached) and read as 16-byte groups that every
+// lane of a wavefront shares.
 #include "bs_common.h"
 
 namespace {
@@ -14,18 +16,34 @@ __global__ void __launch_bounds__(256)
 threshold_kernel(const int32_t *__restrict__ C, long long ldc, int M, int N, const int32_t *__restrict__ thr, int T,
                  int obits, uint32_t *__restrict__ Y, int Yd)
 {
-    const int n = blockIdx.x * 64 + (threadIdx.x & 63);
-    const int wi = blockIdx.y * 4 + (threadIdx.x >> 6);   // output dword index within the column
-    if (wi >= Yd || n >= N) return;
-    uint32_t w[bs::kMaxBits] = {0, 0, 0, 0};
+    __shared__ int4 tl[128 * 4];  // [row of the block][4 groups of 4 thresholds]
+    const int tid = threadIdx.x;
+    const int n = blockIdx.x * 64 + (tid & 63);
+    const int wi = blockIdx.y * 4 + (tid >> 6);       // output dword index within the column
+    const int mblock = blockIdx.y * 128;
+    for (int it = tid; it < 128 * 16; it += 256) {
+        const int r = it >> 4, t = it & 15;
+        reinterpret_cast<int32_t *>(tl)[it] =
+            (mblock + r < M && t < T) ? thr[(long long)(mblock + r) * T + t] : 0x7fffffff;
+    }
     const int mbase = wi * 32;
+    int32_t c[32];
+    if (wi < Yd && n < N) {
+#pragma unroll
+        for (int r = 0; r < 32; ++r) c[r] = (mbase + r < M) ? C[(long long)(mbase + r) * ldc + n] : 0;
+    }
+    __syncthreads();
+    if (wi >= Yd || n >= N) return;
+    const int nq = (T + 3) >> 2;
+    uint32_t w[bs::kMaxBits] = {0, 0, 0, 0};
+#pragma unroll
     for (int r = 0; r < 32; ++r) {
-        const int m = mbase + r;
-        if (m >= M) break;
-        const int32_t c = C[(long long)m * ldc + n];
-        const int32_t *th = thr + (long long)m * T;
         uint32_t y = 0;
-        for (int t = 0; t < T; ++t) y += (c >= th[t]) ? 1u : 0u;
+        for (int q = 0; q < nq; ++q) {
+            const int4 th = tl[((tid >> 6) * 32 + r) * 4 + q];
+            y += (uint32_t)(c[r] >= th.x) + (uint32_t)(c[r] >= th.y) + (uint32_t)(c[r] >= th.z) + (uint32_t)(c[r] >= th.w);
+        }
+        if (mbase + r >= M) y = 0;
 #pragma unroll
         for (int p = 0; p < bs::kMaxBits; ++p) w[p] |= ((y >> p) & 1u) << r;
     }
