@@ -329,7 +329,7 @@ dense_gemm_lds_kernel(const DenseParams p)
     constexpr int ROWS = BM + BN;
     constexpr int TILE = ROWS * DK;              // bytes per stage, rows unpadded
     constexpr int LPW = ROWS / 16 / 4;           // load instructions per wavefront and stage (16 rows each)
-    constexpr int NBUF = 3;
+    constexpr int NBUF = 3;                      // stage i + NBUF - 1 is requested while stage i is consumed (4 measured: no gain)
     __shared__ __attribute__((aligned(16))) unsigned char lds[NBUF * TILE];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -393,9 +393,9 @@ dense_gemm_lds_kernel(const DenseParams p)
     // the loads can be spread between the MFMAs); the last two stages run without requests.
     auto step = [&](auto more_t, int i, int cur) {
         constexpr bool MORE = decltype(more_t)::value;
-        const int nxt = cur == NBUF - 1 ? 0 : cur + 1, nx2 = nxt == NBUF - 1 ? 0 : nxt + 1;
-        // buffer nx2 held stage i - 1: nobody reads it after the previous iteration's barrier
-        if constexpr (MORE) issue(nx2, (i + 2) * DK);
+        const int nxt = cur == NBUF - 1 ? 0 : cur + 1, last = cur == 0 ? NBUF - 1 : cur - 1;
+        // buffer `last` held stage i - 1: nobody reads it after the previous iteration's barrier
+        if constexpr (MORE) issue(last, (i + NBUF - 1) * DK);
         load_frags(1, cur, 1);
         mfmas(0);
         if constexpr (MORE) {
@@ -409,10 +409,10 @@ dense_gemm_lds_kernel(const DenseParams p)
         }
         __builtin_amdgcn_sched_barrier(0);
         // A bare s_barrier with explicit counters: __syncthreads() carries a full fence, i.e. a
-        // wait for ALL outstanding loads, including the ones just issued for stage i + 2.  Needed
-        // here: this wavefront's part of stage i + 1 has landed (at most the LPW newer loads still
-        // outstanding) and its LDS reads of the current buffer are done.
-        if constexpr (MORE) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(LPW) : "memory");
+        // wait for ALL outstanding loads, including the ones issued for later stages.  Needed
+        // here: this wavefront's part of stage i + 1 has landed (the (NBUF - 2) * LPW newer loads
+        // may stay outstanding) and its LDS reads of the current buffer are done.
+        if constexpr (MORE) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NBUF - 2) * LPW) : "memory");
         else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
         if (MORE || i + 1 < nst) load_frags(0, nxt, 0);
@@ -425,13 +425,14 @@ dense_gemm_lds_kernel(const DenseParams p)
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    issue(0, 0);
-    if (nst > 1) issue(1, DK);
-    if (nst > 1) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LPW) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    // prologue: stages 0 .. NBUF - 2 requested, stage 0 awaited
+#pragma unroll
+    for (int st = 0; st < NBUF - 1; ++st)
+        if (st < nst) issue(st, st * DK);
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
     load_frags(0, 0, 0);
     int cur = 0, i = 0;
-    for (; i + 2 < nst; ++i) {
+    for (; i + NBUF - 1 < nst; ++i) {
         step(std::true_type{}, i, cur);
         cur = cur == NBUF - 1 ? 0 : cur + 1;
     }
