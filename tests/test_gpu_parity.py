@@ -157,6 +157,27 @@ def test_gemm_topbits(w, wf, a, af, M, K, N):
         assert_equal(got.astype(np.int64), want, "topbits min_shift=%d" % s)
 
 
+@pytest.mark.parametrize("N", [1, 6])
+def test_gemm_very_deep_extreme_values(N):
+    """Depth 2^22 with extremal W4A4 values: |C| = 8 * 15 * 2^22 = 5.03e8, a quarter of the int32 range,
+    through thousands of depth stages (few-column kernel for N = 1, tiled kernel for N = 6)."""
+    K, M = 1 << 22, 5
+    rng = np.random.default_rng(N)
+    W = np.full((M, K), -8, dtype=np.int8)
+    A = np.full((K, N), 15, dtype=np.int8)
+    W[1] = draw(rng, (K,), 4, TC)
+    if N > 1:
+        A[:, -1] = draw(rng, (K,), 4, U)
+    Wp = bs.bs_pack_planes(dev(W), 4, bs.BS_TWOS_COMPLEMENT)
+    Ap = bs.bs_pack_planes(dev(A), 4, bs.BS_UNSIGNED, depth_is_strided=True)
+    got = bs.bs_gemm(Wp, bs.BS_TWOS_COMPLEMENT, Ap, bs.BS_UNSIGNED, K).cpu().numpy()
+    assert_equal(got, oracle.gemm(W, A), "deep W4A4")
+    assert got[0, 0] == -8 * 15 * K
+    # one more doubling of the depth would be refused
+    assert bs.load_library().bs_gemm(Wp.data_ptr(), 4, 1, Ap.data_ptr(), 4, 0, M, N, 1 << 23, got.ctypes.data, N, None) \
+        == bs.BS_ERR_OVERFLOW_RISK
+
+
 def test_gemm_extreme_values_and_ldc():
     M, K, N = 66, 640, 50
     for w, a in [(2, 2), (4, 4)]:
