@@ -33,7 +33,7 @@
 
 namespace bs {
 
-constexpr int kStageDwords = 32;  // dwords of depth per packed row and stage (large grids)
+constexpr int kStageDwords = 32;  // dwords of depth per packed row and stage
 
 struct GemmParams {
     const uint32_t *W;  // dword view of Wp
@@ -139,8 +139,8 @@ __device__ __forceinline__ bool tile_of_block(const GemmParams &p, int bid, int 
 // loader gathers each lowered column's words from the image (Sec. 3.2's lowering folded
 // into the operand fetch, so the lowered matrix never exists in memory).
 // XOR: both operands bipolar (W1A1): popcount(XOR) instead of popcount(AND), no correction terms.
-// KT: dwords of depth per packed row and stage.  Small grids are latency-bound, so their
-// stages are made as deep as LDS allows: fewer stages, fewer exposed memory round trips.
+// KT: dwords of depth per packed row and stage (a multiple of 32; both configurations use
+// 32: deeper stages were measured on the small, latency-bound grids and bring nothing).
 template <int WB, int AB, int TM, int TN, int WM, int WN, int KS, int KT, bool FUSE, bool CORR, bool CONV = false,
           bool XOR = false>
 __global__ void __launch_bounds__(WM * WN * KS * 64)
