@@ -125,92 +125,83 @@ pack_rows_kernel(const T *__restrict__ src, int64_t rows, int64_t depth, int64_t
 }
 
 // ------------------------------------------------------------------ pack_cols (fast)
-// Workgroup tile: 128 rows (= source columns n) x 8 WPT words (512 WPT depth indices).
-// Thread (tx, ty): rows 4 tx .. 4 tx + 3, words WPT ty .. WPT ty + WPT - 1.  WPT = 2 for large
-// inputs (128-byte output runs); WPT = 1 halves the tile so that mid-sized inputs still
-// give every compute unit a workgroup (64-byte runs).
+// Workgroup tile: 128 rows (= source columns n) x 8 words (512 depth indices).
+// Thread (tx, ty): rows 4 tx .. 4 tx + 3, word ty.  The planes of the tile pass through LDS
+// (bits x 8 KiB, sized at launch) so that they leave as 64-byte runs per (plane, row).
+// A tile of twice the depth (128-byte runs) measured slower at every size: the smaller
+// tile keeps more workgroups resident per compute unit.
 constexpr int PC_ROWS = 128;
+constexpr int PC_WORDS = 8;
+constexpr int PC_PAIRS = PC_WORDS / 2;  // 16-byte slots per row of the LDS tile
 
-template <typename T, bool BIP, int WPT>
+template <typename T, bool BIP>
 __global__ void __launch_bounds__(256)
 pack_cols_kernel(const T *__restrict__ src, int64_t rows, int64_t depth, int64_t ld, int bits,
                  uint64_t *__restrict__ planes, int64_t S)
 {
-    constexpr int PC_WORDS = 8 * WPT;
-    constexpr int PAIRS = PC_WORDS / 2;  // 16-byte slots per row of the LDS tile
-    // [plane][row][PAIRS pairs of words], pair slot XOR-swizzled with (row / 4) & (PAIRS - 1)
-    __shared__ uint4 tile[bs::kMaxBits * PC_ROWS * PAIRS];
+    // [plane][row][PC_PAIRS pairs of words], pair slot XOR-swizzled with (row / 4) & (PC_PAIRS - 1)
+    extern __shared__ uint4 tile[];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const int64_t r0 = (int64_t)blockIdx.x * PC_ROWS;
     const int64_t d0 = (int64_t)blockIdx.y * PC_WORDS;
     const int64_t rq = r0 + 4 * tx;                 // first of this thread's four rows
     const bool full_quad = rq + 4 <= rows;
 
-    uint32_t out[WPT][bs::kMaxBits][4][2];          // [word][plane][row of the quad][lo/hi dword]
+    uint32_t out[bs::kMaxBits][4][2];               // [plane][row of the quad][lo/hi dword]
+    const int64_t kw = (d0 + ty) * 64;              // first depth index of the word
+    uint32_t A[bs::kMaxBits][8];                    // [plane][group of 8 depth indices]
 #pragma unroll
-    for (int wd = 0; wd < WPT; ++wd) {
-        const int64_t kw = (d0 + WPT * ty + wd) * 64; // first depth index of the word
-        uint32_t A[bs::kMaxBits][8];                // [plane][group of 8 depth indices]
+    for (int g = 0; g < 8; ++g) {
+        uint32_t X[8];
 #pragma unroll
-        for (int g = 0; g < 8; ++g) {
-            uint32_t X[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int64_t k = kw + 8 * g + i;
-                uint32_t x = 0;
-                if (k < depth) {
-                    const T *e = src + k * ld + rq;
-                    if (full_quad) {
-                        if constexpr (sizeof(T) == 1) x = codes_of_i8x4<BIP>(*reinterpret_cast<const uint32_t *>(e));
-                        else {
-                            const int4 v = *reinterpret_cast<const int4 *>(e);
-                            x = codes_of_i32x4<BIP>(v.x, v.y, v.z, v.w);
-                        }
-                    } else {
-                        int v[4];
-#pragma unroll
-                        for (int b = 0; b < 4; ++b) v[b] = (rq + b < rows) ? (int)e[b] : 0;
-                        x = codes_of_i32x4<BIP>(v[0], v[1], v[2], v[3]);
+        for (int i = 0; i < 8; ++i) {
+            const int64_t k = kw + 8 * g + i;
+            uint32_t x = 0;
+            if (k < depth) {
+                const T *e = src + k * ld + rq;
+                if (full_quad) {
+                    if constexpr (sizeof(T) == 1) x = codes_of_i8x4<BIP>(*reinterpret_cast<const uint32_t *>(e));
+                    else {
+                        const int4 v = *reinterpret_cast<const int4 *>(e);
+                        x = codes_of_i32x4<BIP>(v.x, v.y, v.z, v.w);
                     }
+                } else {
+                    int v[4];
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) v[b] = (rq + b < rows) ? (int)e[b] : 0;
+                    x = codes_of_i32x4<BIP>(v[0], v[1], v[2], v[3]);
                 }
-                X[i] = x;
             }
-#pragma unroll
-            for (int p = 0; p < bs::kMaxBits; ++p) A[p][g] = (p < bits) ? vertical8(X, p) : 0u;
+            X[i] = x;
         }
-        // A[p][g].byte c = bits 8 g .. 8 g + 7 of row c: split the four rows
 #pragma unroll
-        for (int p = 0; p < bs::kMaxBits; ++p) {
-            transpose_bytes_4x4(A[p][0], A[p][1], A[p][2], A[p][3],
-                                out[wd][p][0][0], out[wd][p][1][0], out[wd][p][2][0], out[wd][p][3][0]);
-            transpose_bytes_4x4(A[p][4], A[p][5], A[p][6], A[p][7],
-                                out[wd][p][0][1], out[wd][p][1][1], out[wd][p][2][1], out[wd][p][3][1]);
-        }
+        for (int p = 0; p < bs::kMaxBits; ++p) A[p][g] = (p < bits) ? vertical8(X, p) : 0u;
+    }
+    // A[p][g].byte c = bits 8 g .. 8 g + 7 of row c: split the four rows
+#pragma unroll
+    for (int p = 0; p < bs::kMaxBits; ++p) {
+        transpose_bytes_4x4(A[p][0], A[p][1], A[p][2], A[p][3], out[p][0][0], out[p][1][0], out[p][2][0], out[p][3][0]);
+        transpose_bytes_4x4(A[p][4], A[p][5], A[p][6], A[p][7], out[p][0][1], out[p][1][1], out[p][2][1], out[p][3][1]);
     }
 #pragma unroll
     for (int p = 0; p < bs::kMaxBits; ++p)
         if (p < bits) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if constexpr (WPT == 2) {
-                    tile[(p * PC_ROWS + 4 * tx + c) * PAIRS + (ty ^ (tx & (PAIRS - 1)))] =
-                        make_uint4(out[0][p][c][0], out[0][p][c][1], out[1][p][c][0], out[1][p][c][1]);
-                } else {  // one word: half of the pair slot (ty >> 1)
-                    uint2 *slot = reinterpret_cast<uint2 *>(
-                        &tile[(p * PC_ROWS + 4 * tx + c) * PAIRS + ((ty >> 1) ^ (tx & (PAIRS - 1)))]);
-                    slot[ty & 1] = make_uint2(out[0][p][c][0], out[0][p][c][1]);
-                }
+            for (int c = 0; c < 4; ++c) {  // one word: half of the pair slot (ty >> 1)
+                uint2 *slot = reinterpret_cast<uint2 *>(
+                    &tile[(p * PC_ROWS + 4 * tx + c) * PC_PAIRS + ((ty >> 1) ^ (tx & (PC_PAIRS - 1)))]);
+                slot[ty & 1] = make_uint2(out[p][c][0], out[p][c][1]);
             }
         }
     __syncthreads();
-    // write out: PAIRS consecutive threads cover the contiguous run of one (plane, row)
-    const int pair = threadIdx.x & (PAIRS - 1);
+    // write out: PC_PAIRS consecutive threads cover the contiguous run of one (plane, row)
+    const int pair = threadIdx.x & (PC_PAIRS - 1);
     for (int p = 0; p < bits; ++p)
-        for (int rr = threadIdx.x / PAIRS; rr < PC_ROWS; rr += 256 / PAIRS) {
+        for (int rr = threadIdx.x / PC_PAIRS; rr < PC_ROWS; rr += 256 / PC_PAIRS) {
             const int64_t r = r0 + rr, d = d0 + 2 * pair;
             if (r < rows && d < S)
                 *reinterpret_cast<uint4 *>(planes + ((int64_t)p * rows + r) * S + d) =
-                    tile[(p * PC_ROWS + rr) * PAIRS + (pair ^ ((rr >> 2) & (PAIRS - 1)))];
+                    tile[(p * PC_ROWS + rr) * PC_PAIRS + (pair ^ ((rr >> 2) & (PC_PAIRS - 1)))];
         }
 }
 
@@ -287,18 +278,11 @@ bs_status launch_pack(const T *src, int64_t rows, int64_t depth, int64_t ld, int
     } else {
         const bool fast = bs::aligned(src, quad_align) && (ld * sizeof(T)) % quad_align == 0;
         if (fast) {
-            const int64_t gx = (rows + PC_ROWS - 1) / PC_ROWS;
-            const bool big = gx * ((S + 15) / 16) >= 512;   // enough 16-word tiles to fill the chip twice
-            const int words = big ? 16 : 8;
-            dim3 grid((unsigned)gx, (unsigned)((S + words - 1) / words));
+            dim3 grid((unsigned)((rows + PC_ROWS - 1) / PC_ROWS), (unsigned)((S + PC_WORDS - 1) / PC_WORDS));
             if (grid.y > 65535) return BS_ERR_OVERFLOW_RISK;
-            if (big) {
-                if (bip) pack_cols_kernel<T, true, 2><<<grid, 256, 0, st>>>(src, rows, depth, ld, bits, planes, S);
-                else pack_cols_kernel<T, false, 2><<<grid, 256, 0, st>>>(src, rows, depth, ld, bits, planes, S);
-            } else {
-                if (bip) pack_cols_kernel<T, true, 1><<<grid, 256, 0, st>>>(src, rows, depth, ld, bits, planes, S);
-                else pack_cols_kernel<T, false, 1><<<grid, 256, 0, st>>>(src, rows, depth, ld, bits, planes, S);
-            }
+            const size_t lds = (size_t)bits * PC_ROWS * PC_PAIRS * sizeof(uint4);
+            if (bip) pack_cols_kernel<T, true><<<grid, 256, lds, st>>>(src, rows, depth, ld, bits, planes, S);
+            else pack_cols_kernel<T, false><<<grid, 256, lds, st>>>(src, rows, depth, ld, bits, planes, S);
         } else {
             dim3 grid((unsigned)((rows + 63) / 64), (unsigned)((S + 3) / 4));
             if (grid.y > 65535) return BS_ERR_OVERFLOW_RISK;
