@@ -21,13 +21,16 @@ import time
 import numpy as np
 
 # chip figures used for the rooflines
-CUS, LANES_PER_CU_CLK, CLOCK_HZ = 256, 64, 2.4e9
-VALU_LANE_OPS = CUS * LANES_PER_CU_CLK * CLOCK_HZ            # 32-bit integer lane-ops / s
-BINARY_PEAK_TOPS = VALU_LANE_OPS / 2 * 32 * 2 / 1e12           # one AND + one BCNT per 32 binary MACs, 2 ops / MAC
+CUS, SIMDS_PER_CU, LANES, CLOCK_HZ = 256, 4, 64, 2.4e9
+# One product of Alg. 1's inner loop = 32 binary MACs per lane = one v_and_b32 + one v_bcnt_u32_b32.  A SIMD executes the
+# AND at 32 lanes per clock (the rate behind the chip's 157.3 TFLOP/s fp32 vector figure) and the popcount at 16 lanes
+# per clock: 2 + 4 = 6 clocks per wavefront-wide product.
+CLOCKS_PER_PRODUCT = 6
+BINARY_PEAK_TOPS = CUS * SIMDS_PER_CU * LANES * 32 * 2 / CLOCKS_PER_PRODUCT * CLOCK_HZ / 1e12   # 1677.7
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per bs_gemm launch on the W2A2 4096^3 workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE scaled by a 256 MiB copy (profiles/pmc_fetch_write_w2a2_4096.md): 24.5 MiB + 64 MiB
-GEMM_TRAFFIC_BYTES = int((12557.1 * 2.0 + 65536.0) * 1024)
+GEMM_TRAFFIC_BYTES = 92_817_916
 
 
 def main() -> int:
@@ -110,6 +113,14 @@ def main() -> int:
     pack_ms, _ = timed(lambda: bs.bs_pack_planes(Ad, a, bs.BS_UNSIGNED, depth_is_strided=True, out=Ap), args.steps, 2)
     binary_tops = w * a * 2.0 * M * N * K / (gemm_ms * 1e-3) / 1e12
 
+    # the chip's measured ceiling for the AND + popcount pair (register operands, all compute units,
+    # eight wavefronts per SIMD), next to the theoretical peak
+    sink = torch.empty(8 * CUS, dtype=torch.int32, device="cuda")
+    probe_passes = 20000
+    probe_ms, _ = timed(lambda: bs.bs_probe_popcount_rate(sink, probe_passes), 3, 1)
+    probe_lane_ops = sink.numel() * 256 * probe_passes * 32
+    measured_peak_tops = probe_lane_ops / 2 * 32 * 2 / (probe_ms * 1e-3) / 1e12
+
     # spot check against the oracle (sampled outputs; the full comparison is in tests/)
     import oracle
     Ch = C.cpu().numpy()
@@ -127,6 +138,8 @@ def main() -> int:
                                "GEMM to int32; weights pre-packed", "M": M, "N": N, "K": K, "wbits": w, "abits": a},
         "roofline": {"bound": "alu", "kernel": "bs_gemm_kernel<2,2,...>", "achieved": round(binary_tops, 1),
                      "peak": round(BINARY_PEAK_TOPS, 1), "unit": "binary TOP/s", "frac": round(binary_tops / BINARY_PEAK_TOPS, 4),
+                     "measured_peak": round(measured_peak_tops, 1),
+                     "frac_of_measured_peak": round(binary_tops / measured_peak_tops, 4),
                      "kernel_ms": round(gemm_ms, 4), "traffic": GEMM_TRAFFIC_BYTES,
                      "algorithmic_bytes": 2 * (w * M * K // 8) // 1 + 4 * M * N},
         "breakdown_ms": {"pack_activations": round(pack_ms, 4), "bs_gemm": round(gemm_ms, 4)},

@@ -227,6 +227,17 @@ bs_status bs_streamline_collapse(int64_t M, double a_q, double b_q, const int64_
 bs_status bs_streamline_thresholds(const double *t, int T, const double *a, const double *b, int64_t M,
                                    int32_t *thr, uint8_t *negate);
 
+/*
+ * Diagnostic: rate probe for the instruction pair of Alg. 1's inner loop (AND, popcount-accumulate).
+ * Launches `workgroups` workgroups of 256 lanes; every lane executes passes * 16 AND and passes * 16
+ * popcount-add instructions on registers (no memory traffic, one idle issue slot per pair as in the
+ * GEMM's inner loop) and the workgroup stores one word to sink [workgroups] (device memory,
+ * caller-owned) so that the work is observable.  passes must be a positive multiple of 4.
+ * Lane-operations per launch: workgroups * 256 * passes * 32.  Timed by the caller, it gives the
+ * measured ceiling that goes beside the theoretical VALU popcount peak.  Asynchronous on `stream`.
+ */
+bs_status bs_probe_popcount_rate(uint32_t *sink, int workgroups, int passes, void *stream);
+
 const char *bs_status_string(bs_status s);
 int bs_version(void);
 

@@ -25,7 +25,7 @@ BS_I8, BS_I32 = 0, 1
 EXPORTS = ("bs_words_per_row", "bs_lowered_depth", "bs_pack_planes", "bs_gemm", "bs_gemm_topbits", "bs_threshold_activate",
            "bs_gemm_threshold", "bs_im2col_interleaved", "bs_conv_threshold", "bs_maxpool_packed",
            "bs_unpack_planes", "bs_gemm_i8", "bs_gemm_i8_threshold", "bs_streamline_collapse",
-           "bs_streamline_thresholds", "bs_status_string", "bs_version")
+           "bs_streamline_thresholds", "bs_probe_popcount_rate", "bs_status_string", "bs_version")
 
 
 class BsError(RuntimeError):
@@ -68,6 +68,7 @@ def load_library() -> ctypes.CDLL:
     lib.bs_streamline_collapse.argtypes = [i64, f64, f64, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.bs_streamline_collapse.restype = i32
     lib.bs_streamline_thresholds.argtypes = [vp, i32, vp, vp, i64, vp, vp]; lib.bs_streamline_thresholds.restype = i32
+    lib.bs_probe_popcount_rate.argtypes = [vp, i32, i32, vp]; lib.bs_probe_popcount_rate.restype = i32
     lib.bs_status_string.argtypes = [i32]; lib.bs_status_string.restype = ctypes.c_char_p
     lib.bs_version.argtypes = []; lib.bs_version.restype = i32
     _lib = lib
@@ -239,6 +240,15 @@ def bs_gemm_i8_threshold(W: torch.Tensor, At: torch.Tensor, K: int, thr: torch.T
                                              _dev(thr, "thr"), obits, _dev(out, "out"), _stream())
     _check(st, "bs_gemm_i8_threshold")
     return out
+
+
+def bs_probe_popcount_rate(sink: torch.Tensor, passes: int) -> int:
+    """Launch the AND + popcount rate probe with one workgroup per element of sink (int32, device);
+    returns the lane-operations of the launch (the caller times it)."""
+    wgs = sink.numel()
+    st = load_library().bs_probe_popcount_rate(_dev(sink, "sink"), wgs, passes, _stream())
+    _check(st, "bs_probe_popcount_rate")
+    return wgs * 256 * passes * 32
 
 
 def _np_ptr(a):

@@ -34,6 +34,7 @@
 namespace bs {
 
 constexpr int kStageDwords = 32;  // dwords of depth per packed row and stage
+constexpr long long kIdleMinBlocks = 257;  // more workgroups than compute units (measured: 10.9 vs 12.5 us at 320, 10.7 vs 9.6 us at 256)
 
 struct GemmParams {
     const uint32_t *W;  // dword view of Wp
@@ -109,6 +110,52 @@ __device__ __forceinline__ int popc_xor4(const uint4 &a, const uint4 &b, int acc
     return acc;
 }
 
+__device__ __forceinline__ uint32_t dword_of(const uint4 &v, int d) { return d == 0 ? v.x : d == 1 ? v.y : d == 2 ? v.z : v.w; }
+
+// Alg. 1's inner statement for a lane's TM x TN outputs on one 16-byte chunk of TM weight rows and TN
+// activation columns, as one chain of two-instruction steps: the AND (or XOR) of the next product, then
+// the popcount-accumulate of the current one.
+//
+// The order decides the speed.  A SIMD of this chip executes the AND in two cycles and the popcount in
+// four, but one wavefront issues at most one instruction per four cycles, so a lone wavefront needs 8
+// cycles per product.  Every step reads the register its predecessor wrote from inside an asm
+// statement; for that the compiler leaves one idle issue slot (s_nop 0) between the steps, and in that
+// rhythm - AND, popcount, idle - the two resident wavefronts of a SIMD interleave, the AND of one in
+// the shadow of the other's popcount: about 6.9 cycles per product measured instead of 8.  Spelling the
+// idle slot out inside the statements, or making the popcount depend on the AND directly before it, was
+// measured slower (the compiler then adds slots of its own, or the rhythm breaks at statement edges).
+template <bool XOR, bool IDLE, int TM, int TN>
+__device__ __forceinline__ void mac_block(const uint4 (&w)[TM], const uint4 (&a)[TN], int (&acc)[TM][TN])
+{
+    if constexpr (!IDLE) {
+        // A wavefront alone on its SIMD has nobody to interleave with: plain AND + popcount pairs,
+        // 8 cycles per product instead of the 12 the idle slot would make it.
+#pragma unroll
+        for (int r = 0; r < TM; ++r)
+#pragma unroll
+            for (int c = 0; c < TN; ++c) acc[r][c] = XOR ? popc_xor4(w[r], a[c], acc[r][c]) : popc_and4(w[r], a[c], acc[r][c]);
+        return;
+    }
+    constexpr int NP = 4 * TM * TN;  // products, dword-major: an accumulator returns every TM * TN steps
+    auto wd = [&](int n) { return dword_of(w[(n / TN) % TM], n / (TM * TN)); };
+    auto ad = [&](int n) { return dword_of(a[n % TN], n / (TM * TN)); };
+    uint32_t t = XOR ? (wd(0) ^ ad(0)) : (wd(0) & ad(0));
+#pragma unroll
+    for (int n = 0; n < NP; ++n) {
+        int &o = acc[(n / TN) % TM][n % TN];
+        if (n + 1 < NP) {
+            uint32_t tn;
+            if constexpr (XOR)
+                asm("v_xor_b32 %0, %3, %4\n\tv_bcnt_u32_b32 %1, %2, %1" : "=&v"(tn), "+v"(o) : "v"(t), "v"(wd(n + 1)), "v"(ad(n + 1)));
+            else
+                asm("v_and_b32 %0, %3, %4\n\tv_bcnt_u32_b32 %1, %2, %1" : "=&v"(tn), "+v"(o) : "v"(t), "v"(wd(n + 1)), "v"(ad(n + 1)));
+            t = tn;
+        } else {
+            asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(o) : "v"(t));
+        }
+    }
+}
+
 __device__ __forceinline__ int popc4(const uint4 &a)
 {
     return __builtin_popcount(a.x) + __builtin_popcount(a.y) + __builtin_popcount(a.z) + __builtin_popcount(a.w);
@@ -142,7 +189,7 @@ __device__ __forceinline__ bool tile_of_block(const GemmParams &p, int bid, int 
 // KT: dwords of depth per packed row and stage (a multiple of 32; both configurations use
 // 32: deeper stages were measured on the small, latency-bound grids and bring nothing).
 template <int WB, int AB, int TM, int TN, int WM, int WN, int KS, int KT, bool FUSE, bool CORR, bool CONV = false,
-          bool XOR = false>
+          bool XOR = false, bool IDLE = true>
 __global__ void __launch_bounds__(WM * WN * KS * 64)
 bs_gemm_kernel(const GemmParams p)
 {
@@ -313,13 +360,7 @@ bs_gemm_kernel(const GemmParams p)
 #pragma unroll
                 for (int i = 0; i < WB; ++i)
 #pragma unroll
-                    for (int j = 0; j < AB; ++j)
-#pragma unroll
-                        for (int r = 0; r < TM; ++r)
-#pragma unroll
-                            for (int c = 0; c < TN; ++c)
-                                acc[i * AB + j][r][c] = XOR ? popc_xor4(w[i][r], a[j][c], acc[i * AB + j][r][c])
-                                                            : popc_and4(w[i][r], a[j][c], acc[i * AB + j][r][c]);
+                    for (int j = 0; j < AB; ++j) mac_block<XOR, IDLE, TM, TN>(w[i], a[j], acc[i * AB + j]);
             }
         } else {
             // Many plane pairs: one pair at a time over the whole stage into a small
@@ -343,10 +384,7 @@ bs_gemm_kernel(const GemmParams p)
                         for (int r = 0; r < TM; ++r) w[r] = ldsW[(i * BM + r) * KCH + (q ^ ly)];
 #pragma unroll
                         for (int c = 0; c < TN; ++c) a[c] = ldsA[(j * BN + c) * KCH + (q ^ lx)];
-#pragma unroll
-                        for (int r = 0; r < TM; ++r)
-#pragma unroll
-                            for (int c = 0; c < TN; ++c) t[r][c] = popc_and4(w[r], a[c], t[r][c]);
+                        mac_block<false, IDLE, TM, TN>(w, a, t);
                     }
                     const int cf = p.coef[i * 4 + j];
 #pragma unroll
@@ -530,14 +568,9 @@ inline long long plan_tile_order(GemmParams &g, int BM, int BN, int wbits, int a
     return best_blocks;
 }
 
-template <int WB, int AB, int TM, int TN, int WM, int WN, int KS, int KT>
-bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, bool xr, hipStream_t st)
+template <int WB, int AB, int TM, int TN, int WM, int WN, int KS, int KT, bool IDLE>
+bs_status launch_variant(const GemmParams &g, dim3 grid, bool fuse, bool corr, bool conv, bool xr, hipStream_t st)
 {
-    constexpr int BM = 8 * TM * WM, BN = 8 * TN * WN;
-    GemmParams g = g_in;
-    const long long blocks = plan_tile_order(g, BM, BN, WB, AB);
-    if (blocks >= (1LL << 31)) return BS_ERR_UNSUPPORTED;
-    dim3 grid((unsigned)blocks);
     dim3 block(WM * WN * KS * 64);
     // A bipolar operand has exactly one plane, so the correction variant only exists
     // where WB == 1 or AB == 1.
@@ -546,8 +579,8 @@ bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, bo
     if (xr) {  // both operands bipolar: one plane each
         if constexpr (WB == 1 && AB == 1) {
             if (conv) return BS_ERR_UNSUPPORTED;
-            if (fuse) bs_gemm_kernel<1, 1, TM, TN, WM, WN, KS, KT, true, false, false, true><<<grid, block, 0, st>>>(g);
-            else bs_gemm_kernel<1, 1, TM, TN, WM, WN, KS, KT, false, false, false, true><<<grid, block, 0, st>>>(g);
+            if (fuse) bs_gemm_kernel<1, 1, TM, TN, WM, WN, KS, KT, true, false, false, true, IDLE><<<grid, block, 0, st>>>(g);
+            else bs_gemm_kernel<1, 1, TM, TN, WM, WN, KS, KT, false, false, false, true, IDLE><<<grid, block, 0, st>>>(g);
             return bs::after_launch();
         } else {
             return BS_ERR_INVALID_ARG;
@@ -555,16 +588,33 @@ bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, bo
     }
     if (conv) {  // implicit lowering exists with the thresholding epilogue only
         if (!fuse) return BS_ERR_UNSUPPORTED;
-        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, CAN_CORR, true><<<grid, block, 0, st>>>(g);
-        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, false, true><<<grid, block, 0, st>>>(g);
+        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, CAN_CORR, true, false, IDLE><<<grid, block, 0, st>>>(g);
+        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, false, true, false, IDLE><<<grid, block, 0, st>>>(g);
     } else if (fuse) {
-        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, CAN_CORR><<<grid, block, 0, st>>>(g);
-        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, false><<<grid, block, 0, st>>>(g);
+        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, CAN_CORR, false, false, IDLE><<<grid, block, 0, st>>>(g);
+        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, false, false, false, IDLE><<<grid, block, 0, st>>>(g);
     } else {
-        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, false, CAN_CORR><<<grid, block, 0, st>>>(g);
-        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, false, false><<<grid, block, 0, st>>>(g);
+        if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, false, CAN_CORR, false, false, IDLE><<<grid, block, 0, st>>>(g);
+        else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, false, false, false, false, IDLE><<<grid, block, 0, st>>>(g);
     }
     return bs::after_launch();
+}
+
+template <int WB, int AB, int TM, int TN, int WM, int WN, int KS, int KT>
+bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, bool xr, hipStream_t st)
+{
+    constexpr int BM = 8 * TM * WM, BN = 8 * TN * WN;
+    GemmParams g = g_in;
+    const long long blocks = plan_tile_order(g, BM, BN, WB, AB);
+    if (blocks >= (1LL << 31)) return BS_ERR_UNSUPPORTED;
+    dim3 grid((unsigned)blocks);
+    // The inner loop's idle-slot rhythm pays when at least two wavefronts share a SIMD.  The small-grid
+    // configuration (one wavefront per SIMD and workgroup) gets there only with more workgroups than
+    // the chip has compute units.
+    if constexpr (KS > 1) {
+        if (blocks < kIdleMinBlocks) return launch_variant<WB, AB, TM, TN, WM, WN, KS, KT, false>(g, grid, fuse, corr, conv, xr, st);
+    }
+    return launch_variant<WB, AB, TM, TN, WM, WN, KS, KT, true>(g, grid, fuse, corr, conv, xr, st);
 }
 
 template <int WB, int AB>
