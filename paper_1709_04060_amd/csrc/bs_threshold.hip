@@ -5,49 +5,65 @@
 // A workgroup covers 128 rows x 64 columns: lanes run along the column index so that the
 // int32 reads of C coalesce, each wavefront produces one 32-bit output word (32 rows) per
 // plane and column.  All 32 accumulators of a thread are requested before the first
-// comparison (one memory round trip), and the thresholds of the 128 rows are staged in LDS,
-// padded to 16 per row with INT_MAX (never reached) and read as 16-byte groups that every
-// lane of a wavefront shares.
+// comparison (one memory round trip).  A row's thresholds are the same for every lane of
+// the wavefront, so they are fetched with scalar loads and compared from scalar registers:
+// no LDS traffic for them (staged in LDS they cost one 16-byte broadcast read per four
+// comparisons, which bounded the 4-bit case).  The four wavefronts' words of a column
+// meet in LDS and leave as one 16-byte store per plane and column.
 #include "bs_common.h"
 
 namespace {
 
+template <int OB>
 __global__ void __launch_bounds__(256)
-threshold_kernel(const int32_t *__restrict__ C, long long ldc, int M, int N, const int32_t *__restrict__ thr, int T,
-                 int obits, uint32_t *__restrict__ Y, int Yd)
+threshold_kernel(const int32_t *__restrict__ C, long long ldc, int M, int N, const int32_t *__restrict__ thr,
+                 uint32_t *__restrict__ Y, int Yd)
 {
-    __shared__ int4 tl[128 * 4];  // [row of the block][4 groups of 4 thresholds]
+    constexpr int T = (1 << OB) - 1;
+    __shared__ uint4 yt[OB * 64];  // [plane][column]: the four words of the workgroup's 128 rows
     const int tid = threadIdx.x;
     const int n = blockIdx.x * 64 + (tid & 63);
-    const int wi = blockIdx.y * 4 + (tid >> 6);       // output dword index within the column
-    const int mblock = blockIdx.y * 128;
-    for (int it = tid; it < 128 * 16; it += 256) {
-        const int r = it >> 4, t = it & 15;
-        reinterpret_cast<int32_t *>(tl)[it] =
-            (mblock + r < M && t < T) ? thr[(long long)(mblock + r) * T + t] : 0x7fffffff;
-    }
-    const int mbase = wi * 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps the threshold addresses scalar
+    const int mbase = (blockIdx.y * 4 + wave) * 32;
+    // rows past the end read the last valid row (any valid address does: their result is dropped)
+    const int last = M - 1 - mbase;  // uniform; negative when the whole word lies past the end (row M - 1 then)
     int32_t c[32];
-    if (wi < Yd && n < N) {
+    if (n < N) {
 #pragma unroll
-        for (int r = 0; r < 32; ++r) c[r] = (mbase + r < M) ? C[(long long)(mbase + r) * ldc + n] : 0;
-    }
-    __syncthreads();
-    if (wi >= Yd || n >= N) return;
-    const int nq = (T + 3) >> 2;
-    uint32_t w[bs::kMaxBits] = {0, 0, 0, 0};
-#pragma unroll
-    for (int r = 0; r < 32; ++r) {
-        uint32_t y = 0;
-        for (int q = 0; q < nq; ++q) {
-            const int4 th = tl[((tid >> 6) * 32 + r) * 4 + q];
-            y += (uint32_t)(c[r] >= th.x) + (uint32_t)(c[r] >= th.y) + (uint32_t)(c[r] >= th.z) + (uint32_t)(c[r] >= th.w);
+        for (int r = 0; r < 32; ++r) {
+            const int row = mbase + (r < last ? r : last);
+            c[r] = C[(long long)row * ldc + n];
         }
-        if (mbase + r >= M) y = 0;
-#pragma unroll
-        for (int p = 0; p < bs::kMaxBits; ++p) w[p] |= ((y >> p) & 1u) << r;
     }
-    for (int p = 0; p < obits; ++p) Y[((long long)p * N + n) * Yd + wi] = w[p];
+    uint32_t w[OB];
+#pragma unroll
+    for (int p = 0; p < OB; ++p) w[p] = 0;
+    if (n < N) {
+#pragma unroll
+        for (int r = 0; r < 32; ++r) {
+            const int row = mbase + (r < last ? r : last);
+            const int32_t *tr = thr + (long long)row * T;
+            uint32_t y = 0;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const int32_t th = tr[t];  // uniform address: a scalar load
+                // y += (c >= th): compare into the carry mask, add the carry
+                asm("v_cmp_le_i32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, 0, %0, vcc" : "+v"(y) : "v"(c[r]), "s"(th) : "vcc");
+            }
+            if (r > last) y = 0;
+#pragma unroll
+            for (int p = 0; p < OB; ++p) w[p] |= ((y >> p) & 1u) << r;
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < OB; ++p) reinterpret_cast<uint32_t *>(yt)[(p * 64 + (tid & 63)) * 4 + wave] = w[p];
+    __syncthreads();
+    for (int it = tid; it < OB * 64; it += 256) {
+        const int p = it >> 6, nn = blockIdx.x * 64 + (it & 63);
+        if (nn >= N) continue;
+        // Yd is a multiple of 4 and the workgroup owns words 4 blockIdx.y .. + 3: a 16-byte aligned store
+        *reinterpret_cast<uint4 *>(Y + ((long long)p * N + nn) * Yd + blockIdx.y * 4) = yt[it];
+    }
 }
 
 }  // namespace
@@ -63,7 +79,13 @@ extern "C" bs_status bs_threshold_activate(const int32_t *C, int64_t ldc, int64_
         return BS_ERR_OVERFLOW_RISK;
     dim3 grid((unsigned)((N + 63) / 64), (unsigned)((Yd + 3) / 4));
     if (grid.y > 65535) return BS_ERR_UNSUPPORTED;
-    threshold_kernel<<<grid, 256, 0, static_cast<hipStream_t>(stream)>>>(
-        C, ldc, (int)M, (int)N, thr, (1 << obits) - 1, obits, reinterpret_cast<uint32_t *>(Yp), (int)Yd);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint32_t *Y = reinterpret_cast<uint32_t *>(Yp);
+    switch (obits) {
+    case 1: threshold_kernel<1><<<grid, 256, 0, st>>>(C, ldc, (int)M, (int)N, thr, Y, (int)Yd); break;
+    case 2: threshold_kernel<2><<<grid, 256, 0, st>>>(C, ldc, (int)M, (int)N, thr, Y, (int)Yd); break;
+    case 3: threshold_kernel<3><<<grid, 256, 0, st>>>(C, ldc, (int)M, (int)N, thr, Y, (int)Yd); break;
+    default: threshold_kernel<4><<<grid, 256, 0, st>>>(C, ldc, (int)M, (int)N, thr, Y, (int)Yd); break;
+    }
     return bs::after_launch();
 }
