@@ -317,6 +317,29 @@ def extras(bs, workloads, dev, timed):
     ms = timed_graph([lambda: bs.bs_unpack_planes(Wp2, TC, 4096, out=W8)], 20)
     out["unpack_4096x4096_2_planes_to_i8"] = {"us": round(ms * 1e3, 2),
                                               "GBps": round((Wp2.numel() * 8 + W8.numel()) / ms / 1e6, 1)}
+    # per-layer engine choice (Sec. 4.1.1 / 4.2): both engines timed on the same fused product, the dense one
+    # including the unpack of its activations, beside what bs_choose_engine picks
+    choice = {}
+    for (w_, a_, M_, N_, K_) in [(1, 2, 256, 729, 2400), (1, 2, 4096, 1024, 4096), (2, 2, 1024, 1024, 4096),
+                                 (4, 4, 8192, 64, 8192), (4, 4, 1024, 256, 1024)]:
+        wf_ = BP if w_ == 1 else TC
+        Wq, Aq = planes(w_, M_, K_), planes(a_, N_, K_)
+        th_ = thr_for(M_, a_)
+        Yq = torch.empty((a_, N_, bs.bs_words_per_row(M_)), dtype=torch.int64, device="cuda")
+        t_bs = timed_graph([lambda: bs.bs_gemm_threshold(Wq, wf_, Aq, U, K_, th_, a_, out=Yq)], 10)
+        W8q = bs.bs_unpack_planes(Wq, wf_, K_)
+        A8q = torch.empty((N_, W8q.shape[1]), dtype=torch.int8, device="cuda")
+
+        def dense_route():
+            bs.bs_unpack_planes(Aq, U, K_, out=A8q)
+            bs.bs_gemm_i8_threshold(W8q, A8q, K_, th_, a_, out=Yq)
+        t_d = timed_graph([dense_route], 10)
+        pick = bs.bs_choose_engine(w_, a_, M_, N_, K_)
+        choice["W%dA%d_%dx%dx%d" % (w_, a_, M_, K_, N_)] = {
+            "bitserial_us": round(t_bs * 1e3, 2), "dense_us": round(t_d * 1e3, 2),
+            "chosen": "dense" if pick == bs.BS_ENGINE_DENSE_I8 else "bitserial",
+            "faster": "dense" if t_d < t_bs else "bitserial"}
+    out["engine_choice"] = choice
     # stand-alone thresholding of a large int32 result (the unfused route of S5)
     Cbig = torch.randint(-40000, -20000, (8192, 8192), dtype=torch.int32, device="cuda")
     thb = thr_for(8192, 4) - 30000

@@ -25,7 +25,7 @@ BS_I8, BS_I32 = 0, 1
 EXPORTS = ("bs_words_per_row", "bs_lowered_depth", "bs_pack_planes", "bs_gemm", "bs_gemm_topbits", "bs_threshold_activate",
            "bs_gemm_threshold", "bs_im2col_interleaved", "bs_conv_threshold", "bs_maxpool_packed",
            "bs_unpack_planes", "bs_gemm_i8", "bs_gemm_i8_threshold", "bs_streamline_collapse",
-           "bs_streamline_thresholds", "bs_probe_popcount_rate", "bs_status_string", "bs_version")
+           "bs_streamline_thresholds", "bs_choose_engine", "bs_probe_popcount_rate", "bs_status_string", "bs_version")
 
 
 class BsError(RuntimeError):
@@ -68,6 +68,7 @@ def load_library() -> ctypes.CDLL:
     lib.bs_streamline_collapse.argtypes = [i64, f64, f64, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.bs_streamline_collapse.restype = i32
     lib.bs_streamline_thresholds.argtypes = [vp, i32, vp, vp, i64, vp, vp]; lib.bs_streamline_thresholds.restype = i32
+    lib.bs_choose_engine.argtypes = [i32, i32, i64, i64, i64]; lib.bs_choose_engine.restype = i32
     lib.bs_probe_popcount_rate.argtypes = [vp, i32, i32, vp]; lib.bs_probe_popcount_rate.restype = i32
     lib.bs_status_string.argtypes = [i32]; lib.bs_status_string.restype = ctypes.c_char_p
     lib.bs_version.argtypes = []; lib.bs_version.restype = i32
@@ -240,6 +241,14 @@ def bs_gemm_i8_threshold(W: torch.Tensor, At: torch.Tensor, K: int, thr: torch.T
                                              _dev(thr, "thr"), obits, _dev(out, "out"), _stream())
     _check(st, "bs_gemm_i8_threshold")
     return out
+
+
+BS_ENGINE_BITSERIAL, BS_ENGINE_DENSE_I8 = 0, 1
+
+
+def bs_choose_engine(wbits: int, abits: int, M: int, N: int, K: int) -> int:
+    """Host-only: BS_ENGINE_BITSERIAL or BS_ENGINE_DENSE_I8 for a wbits x abits product of shape M x K x N."""
+    return load_library().bs_choose_engine(wbits, abits, M, N, K)
 
 
 def bs_probe_popcount_rate(sink: torch.Tensor, passes: int) -> int:

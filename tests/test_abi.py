@@ -119,3 +119,26 @@ def test_oracle_c_part_is_clean_under_sanitizers(tmp_path):
                            "-static-libasan", "-static-libubsan", "-std=c11", "-o", str(exe), str(main_c), src])
     out = subprocess.run([str(exe)], capture_output=True, text=True)
     assert out.returncode == 0 and "ok" in out.stdout, out.stdout + out.stderr
+
+
+def test_engine_choice_rules():
+    """bs_choose_engine (host-only): the fixed rules and the monotone behaviour of the fitted model."""
+    E = bs.bs_choose_engine
+    BSER, DENSE = bs.BS_ENGINE_BITSERIAL, bs.BS_ENGINE_DENSE_I8
+    # few columns: weights are streamed once, the packed form always wins
+    for n in (1, 2, 4):
+        assert E(4, 4, 8192, n, 8192) == BSER
+    # invalid arguments fall back to the bit-serial engine
+    assert E(0, 2, 64, 64, 64) == BSER and E(2, 5, 64, 64, 64) == BSER and E(2, 2, 0, 64, 64) == BSER
+    # large compute-bound products of many plane pairs go to the matrix cores, tiny binary ones do not
+    assert E(4, 4, 8192, 8192, 8192) == DENSE
+    assert E(2, 2, 4096, 4096, 4096) == DENSE
+    assert E(1, 1, 256, 256, 1024) == BSER
+    assert E(1, 2, 256, 729, 2400) == BSER      # the conv2 layer of the paper's AlexNet at batch 1
+    # once dense is chosen, more plane pairs or more columns never switch back
+    for (m, n, k) in [(1024, 1024, 4096), (4096, 256, 4096), (256, 4096, 1024)]:
+        seen = False
+        for pairs in [(1, 1), (1, 2), (2, 2), (2, 4), (4, 4)]:
+            d = E(pairs[0], pairs[1], m, n, k) == DENSE
+            assert d or not seen
+            seen = seen or d
