@@ -185,9 +185,10 @@ bs_status bs_maxpool_packed(const uint64_t *in, int bits, int H, int W, int C, i
 /*
  * Dense engine.  The paper configures each quantized layer to run on either its
  * bit-serial engine or an 8-bit engine (Sec. 4.2) and gives the break-even rule (Sec.
- * 4.1.1).  On this chip the 8-bit matrix cores win every compute-bound shape, so the
+ * 4.1.1).  On this chip the 8-bit matrix cores win the large compute-bound shapes, so the
  * same product C = W . A (Sec. 3.1) is also offered from unpacked int8 operands; the
- * bit-serial calls remain the choice for bandwidth-bound shapes (few columns).
+ * bit-serial calls remain the choice for bandwidth-bound shapes (few columns) and small
+ * layers.  bs_choose_engine below makes the choice per layer.
  *
  * bs_unpack_planes: inverse of bs_pack_planes.  planes [bits][rows][bs_words_per_row(depth)]
  *   -> dst int8 [rows][ld], logical values, depth-contiguous; ld a multiple of 16 and

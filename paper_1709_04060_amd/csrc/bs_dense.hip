@@ -445,33 +445,48 @@ dense_gemm_lds_kernel(const DenseParams p)
 }
 
 // ------------------------------------------------------------------ unpack (planes -> int8)
+// One thread turns one 32-bit word per plane (32 depth indices of one row) into 32 int8 values.
+// Four elements at a time: a nibble of a plane becomes four 0/1 bytes with one multiply
+// (n * 0x00204081 puts bit i of n at bit 8 i; the four shifted copies do not overlap), the planes
+// add up byte-wise without carries (codes stay below 16), and the sign is filled in with bit
+// operations (two's complement: the bits above the code, where the top plane is set; bipolar
+// 2 b - 1: 0xFF ^ 0xFE b).
+template <int FMT>
 __global__ void __launch_bounds__(256)
-unpack_kernel(const uint32_t *__restrict__ planes, int bits, int coef0, int coef1, int coef2, int coef3, int offset,
-              long long rows, long long depth, int Kd, int8_t *__restrict__ dst, long long ld, long long chunks_per_row)
+unpack_kernel(const uint32_t *__restrict__ planes, int bits, long long rows, long long depth, int Kd,
+              int8_t *__restrict__ dst, long long ld, long long words_per_row)
 {
     const long long item = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (item >= rows * chunks_per_row) return;
-    const long long r = item / chunks_per_row, c = item - r * chunks_per_row;  // chunk = 16 depth indices
-    const int coef[4] = {coef0, coef1, coef2, coef3};
-    uint32_t half[4] = {0, 0, 0, 0};
-    for (int pl = 0; pl < bits; ++pl)
-        half[pl] = (planes[((long long)pl * rows + r) * Kd + (c >> 1)] >> (16 * (int)(c & 1))) & 0xFFFFu;
-    uint32_t out[4];
+    if (item >= rows * words_per_row) return;
+    const long long r = item / words_per_row, dw = item - r * words_per_row;
+    uint32_t x[4] = {0, 0, 0, 0};
 #pragma unroll
-    for (int d = 0; d < 4; ++d) {
-        uint32_t w = 0;
+    for (int pl = 0; pl < 4; ++pl)
+        if (pl < bits) x[pl] = planes[((long long)pl * rows + r) * Kd + dw];
+    const uint32_t sign_fill = 0x100u - (1u << bits);  // the byte's bits above a bits-wide code
+    uint32_t out[8];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int e = 4 * d + b;
-            int v = offset;
+    for (int g = 0; g < 8; ++g) {
+        uint32_t sp[4];
 #pragma unroll
-            for (int pl = 0; pl < 4; ++pl) v += coef[pl] * (int)((half[pl] >> e) & 1u);
-            if (c * 16 + e >= depth) v = 0;
-            w |= ((uint32_t)v & 0xFFu) << (8 * b);
+        for (int pl = 0; pl < 4; ++pl) sp[pl] = (((x[pl] >> (4 * g)) & 0xFu) * 0x00204081u) & 0x01010101u;
+        uint32_t v;
+        if (FMT == BS_BIPOLAR) {
+            v = 0xFFFFFFFFu ^ (sp[0] * 0xFEu);
+        } else {
+            v = sp[0] + 2 * sp[1] + 4 * sp[2] + 8 * sp[3];
+            if (FMT == BS_TWOS_COMPLEMENT) {
+                const uint32_t top = bits == 1 ? sp[0] : bits == 2 ? sp[1] : bits == 3 ? sp[2] : sp[3];
+                v |= top * sign_fill;
+            }
         }
-        out[d] = w;
+        const long long e0 = dw * 32 + 4 * g;  // elements past the depth read as 0 (matters for bipolar: code 0 is -1)
+        if (e0 + 4 > depth) v = e0 >= depth ? 0u : v & ((1u << (8 * (int)(depth - e0))) - 1u);
+        out[g] = v;
     }
-    *reinterpret_cast<uint4 *>(dst + r * ld + c * 16) = make_uint4(out[0], out[1], out[2], out[3]);
+    int8_t *o = dst + r * ld + dw * 32;
+    *reinterpret_cast<uint4 *>(o) = make_uint4(out[0], out[1], out[2], out[3]);
+    if (dw * 32 + 16 < ((depth + 15) / 16) * 16) *reinterpret_cast<uint4 *>(o + 16) = make_uint4(out[4], out[5], out[6], out[7]);
 }
 
 template <int WTM, int WTN>
@@ -534,13 +549,14 @@ extern "C" bs_status bs_unpack_planes(const uint64_t *planes, int bits, bs_forma
     if (!bs::aligned(planes, 16) || !bs::aligned(dst, 16) || (ld & 15)) return BS_ERR_ALIGNMENT;
     const int64_t S = bs_words_per_row(depth);
     if (rows * S * 2 * bits >= (int64_t(1) << 31)) return BS_ERR_OVERFLOW_RISK;
-    int coef[4] = {0, 0, 0, 0}, offset = 0;
-    for (int i = 0; i < bits; ++i) coef[i] = (fmt == BS_TWOS_COMPLEMENT && i == bits - 1) ? -(1 << i) : (1 << i);
-    if (fmt == BS_BIPOLAR) { coef[0] = 2; offset = -1; }
-    const int64_t items = rows * chunks;
-    unpack_kernel<<<dim3((unsigned)((items + 255) / 256)), 256, 0, static_cast<hipStream_t>(stream)>>>(
-        reinterpret_cast<const uint32_t *>(planes), bits, coef[0], coef[1], coef[2], coef[3], offset, rows, depth,
-        (int)(2 * S), dst, ld, chunks);
+    const int64_t words = (depth + 31) / 32, items = rows * words;
+    const dim3 grid((unsigned)((items + 255) / 256));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint32_t *pw = reinterpret_cast<const uint32_t *>(planes);
+    if (fmt == BS_BIPOLAR) unpack_kernel<BS_BIPOLAR><<<grid, 256, 0, st>>>(pw, bits, rows, depth, (int)(2 * S), dst, ld, words);
+    else if (fmt == BS_TWOS_COMPLEMENT)
+        unpack_kernel<BS_TWOS_COMPLEMENT><<<grid, 256, 0, st>>>(pw, bits, rows, depth, (int)(2 * S), dst, ld, words);
+    else unpack_kernel<BS_UNSIGNED><<<grid, 256, 0, st>>>(pw, bits, rows, depth, (int)(2 * S), dst, ld, words);
     return bs::after_launch();
 }
 

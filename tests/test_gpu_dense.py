@@ -22,7 +22,7 @@ def padded(X, mult=16):
 
 
 @pytest.mark.parametrize("rows,depth", [(1, 1), (5, 63), (7, 64), (33, 130), (128, 1024), (300, 2400)])
-@pytest.mark.parametrize("bits,fmt", [(1, U), (2, U), (4, U), (2, TC), (4, TC), (1, BP)])
+@pytest.mark.parametrize("bits,fmt", [(1, U), (2, U), (3, U), (4, U), (1, TC), (2, TC), (3, TC), (4, TC), (1, BP)])
 def test_unpack_is_the_inverse_of_pack(rows, depth, bits, fmt):
     rng = np.random.default_rng(rows + depth + bits)
     X = draw(rng, (rows, depth), bits, fmt)
@@ -30,6 +30,21 @@ def test_unpack_is_the_inverse_of_pack(rows, depth, bits, fmt):
     got = bs.bs_unpack_planes(planes, FMT[fmt], depth).cpu().numpy()
     assert_equal(got[:, :depth], X, "unpack")
     assert not got[:, depth:].any()
+
+
+@pytest.mark.parametrize("depth", [1, 15, 16, 17, 31, 33, 48, 100])
+def test_unpack_leaves_the_row_padding_alone(depth):
+    """A leading dimension wider than the depth: bytes up to the next multiple of 16 become 0, the rest stays."""
+    import torch
+    rng = np.random.default_rng(depth)
+    X = draw(rng, (9, depth), 1, BP)
+    planes = bs.bs_pack_planes(dev(X.astype(np.int32)), 1, FMT[BP])
+    out = torch.full((9, 160), 77, dtype=torch.int8, device="cuda")
+    got = bs.bs_unpack_planes(planes, FMT[BP], depth, out=out).cpu().numpy()
+    edge = 16 * ((depth + 15) // 16)
+    assert_equal(got[:, :depth], X, "unpack")
+    assert not got[:, depth:edge].any()
+    assert (got[:, edge:] == 77).all()
 
 
 @pytest.mark.parametrize("M,K,N", [(1, 1, 1), (32, 32, 32), (64, 64, 64), (100, 70, 45), (130, 1000, 257),
