@@ -158,6 +158,19 @@ def main() -> int:
                                   "cores": oracle.num_threads(), "kind": "oracle",
                                   "sample": "the full 4096^3 integer product (no packing), mean of %d runs, %.2f s each"
                                             % (reps, dt)}
+        # the oracle on the small configurations, once each (milliseconds), beside the GPU times below
+        def once(fn):
+            t = time.perf_counter()
+            fn()
+            return round((time.perf_counter() - t) * 1e3, 2)
+        c3, c4 = workloads.cfg3_fc_chain(), workloads.cfg4_conv2()
+        result["cpu_baseline"]["other_configs_ms"] = {
+            "fc6_W1A2_4096x9216x1": once(lambda: oracle.threshold(oracle.gemm(c3["W6"], c3["x"]), c3["thr6"])),
+            "fc7_W1A2_4096x4096x1": once(lambda: oracle.threshold(
+                oracle.gemm(c3["W7"], np.zeros((c3["W7"].shape[1], 1), dtype=np.int8)), c3["thr7"])),
+            "conv2_W1A2_direct_convolution_and_thresholds": once(lambda: oracle.threshold(
+                oracle.conv_direct(c4["x"], c4["filt"], c4["stride"], c4["pad"]).reshape(-1, c4["filt"].shape[0]).T.copy(),
+                c4["thr"]))}
 
     # ------------------------------------------------------------- other configurations, per kernel
     if not args.no_extras:

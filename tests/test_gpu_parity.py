@@ -96,6 +96,16 @@ def test_gemm_all_precisions_and_formats(w, wf, a, af):
     assert_equal(run_gemm(W, A, w, wf, a, af), oracle.gemm(W, A), "gemm W%dA%d" % (w, a))
 
 
+@pytest.mark.parametrize("M,K,N", [(530, 1100, 610), (1500, 1100, 1480)])
+@pytest.mark.parametrize("w,wf,a,af", ALL_WA + BIP)
+def test_gemm_all_precisions_on_larger_grids(w, wf, a, af, M, K, N):
+    """The launch configurations that small shapes do not reach: 340 workgroups of 32 x 32 (depth split over
+    the wavefronts, more workgroups than compute units) and 576 tiles of 64 x 64; ragged in every dimension."""
+    rng = np.random.default_rng(w * 64 + a * 16 + wf * 4 + af + M)
+    W, A = draw(rng, (M, K), w, wf), draw(rng, (K, N), a, af)
+    assert_equal(run_gemm(W, A, w, wf, a, af), oracle.gemm(W, A), "gemm W%dA%d %dx%dx%d" % (w, a, M, K, N))
+
+
 @pytest.mark.parametrize("M,K,N", [(1, 1, 1), (1, 64, 1), (64, 256, 64), (65, 129, 63), (200, 3000, 130),
                                    (257, 1024, 129), (31, 2049, 700), (1000, 100, 3), (3, 5000, 1000)])
 @pytest.mark.parametrize("w,wf,a,af", [(1, BP, 2, U), (2, TC, 2, U), (4, TC, 4, U), (3, TC, 3, TC)])
