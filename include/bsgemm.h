@@ -207,6 +207,32 @@ bs_status bs_gemm_i8_threshold(const int8_t *W, int64_t ldw, const int8_t *At, i
                                int64_t K, const int32_t *thr, int obits, uint64_t *Yp, void *stream);
 
 /*
+ * Dense engine, 4-bit floating-point flavour, for operands of at most 2 bits (any format) and
+ * 3-bit two's complement: every such value is a number of the E2M1 format (0, 0.5, 1, 1.5, 2, 3,
+ * 4, 6 and their negatives), whose matrix-core instruction runs at twice the int8 rate and half
+ * the operand bytes.  Products and partial sums are integers below 2^24, so the fp32 accumulation
+ * is exact and the results equal bs_gemm / bs_gemm_threshold bit for bit (the product of Sec. 3.1,
+ * the thresholds of Sec. 2.1.1).
+ *
+ * bs_unpack_planes_fp4: planes [bits][rows][bs_words_per_row(depth)] -> dst uint8 [rows][ld], two
+ *   E2M1 codes per byte (sign, two exponent bits, one mantissa bit; low nibble = even depth
+ *   index); ld in bytes, a multiple of 16 and >= 16 * ceil(depth / 32); codes from depth up to the
+ *   next multiple of 32 are written as +0.  UNSUPPORTED for formats with a value outside E2M1
+ *   (3-bit unsigned, every 4-bit format).
+ * bs_gemm_fp4 / bs_gemm_fp4_threshold: W [M][ldw], At [N][lda] in that layout (device, 16-byte
+ *   aligned, ldw and lda multiples of 16 and >= ceil(K / 2)); bytes beyond ceil(K / 2) are ignored,
+ *   and for odd K the high nibble of the last byte must be +0 (bs_unpack_planes_fp4 writes it so).
+ *   Outputs exactly as bs_gemm_i8 / bs_gemm_i8_threshold.
+ * Errors: INVALID_ARG, UNSUPPORTED, ALIGNMENT, OVERFLOW_RISK (K >= 2^18), LAUNCH.
+ */
+bs_status bs_unpack_planes_fp4(const uint64_t *planes, int bits, bs_format fmt, int64_t rows, int64_t depth,
+                               uint8_t *dst, int64_t ld, void *stream);
+bs_status bs_gemm_fp4(const uint8_t *W, int64_t ldw, const uint8_t *At, int64_t lda, int64_t M, int64_t N, int64_t K,
+                      int32_t *C, int64_t ldc, void *stream);
+bs_status bs_gemm_fp4_threshold(const uint8_t *W, int64_t ldw, const uint8_t *At, int64_t lda, int64_t M, int64_t N,
+                                int64_t K, const int32_t *thr, int obits, uint64_t *Yp, void *stream);
+
+/*
  * Streamlining, host side (Sec. 2.1).  HOST pointers, double precision, no GPU work.
  *
  * bs_streamline_collapse (Sec. 2.1.2): collapses, per output channel m, the chain

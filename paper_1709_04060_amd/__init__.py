@@ -24,7 +24,8 @@ BS_I8, BS_I32 = 0, 1
 
 EXPORTS = ("bs_words_per_row", "bs_lowered_depth", "bs_pack_planes", "bs_gemm", "bs_gemm_topbits", "bs_threshold_activate",
            "bs_gemm_threshold", "bs_im2col_interleaved", "bs_conv_threshold", "bs_maxpool_packed",
-           "bs_unpack_planes", "bs_gemm_i8", "bs_gemm_i8_threshold", "bs_streamline_collapse",
+           "bs_unpack_planes", "bs_gemm_i8", "bs_gemm_i8_threshold", "bs_unpack_planes_fp4", "bs_gemm_fp4",
+           "bs_gemm_fp4_threshold", "bs_streamline_collapse",
            "bs_streamline_thresholds", "bs_choose_engine", "bs_probe_popcount_rate", "bs_status_string", "bs_version")
 
 
@@ -65,6 +66,10 @@ def load_library() -> ctypes.CDLL:
     lib.bs_gemm_i8_threshold.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i32, vp, vp]
     lib.bs_gemm_i8_threshold.restype = i32
     f64 = ctypes.c_double
+    lib.bs_unpack_planes_fp4.argtypes = [vp, i32, i32, i64, i64, vp, i64, vp]; lib.bs_unpack_planes_fp4.restype = i32
+    lib.bs_gemm_fp4.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i64, vp]; lib.bs_gemm_fp4.restype = i32
+    lib.bs_gemm_fp4_threshold.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i32, vp, vp]
+    lib.bs_gemm_fp4_threshold.restype = i32
     lib.bs_streamline_collapse.argtypes = [i64, f64, f64, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.bs_streamline_collapse.restype = i32
     lib.bs_streamline_thresholds.argtypes = [vp, i32, vp, vp, i64, vp, vp]; lib.bs_streamline_thresholds.restype = i32
@@ -258,6 +263,40 @@ def bs_probe_popcount_rate(sink: torch.Tensor, passes: int) -> int:
     st = load_library().bs_probe_popcount_rate(_dev(sink, "sink"), wgs, passes, _stream())
     _check(st, "bs_probe_popcount_rate")
     return wgs * 256 * passes * 32
+
+
+def bs_unpack_planes_fp4(planes: torch.Tensor, fmt: int, depth: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """planes [bits][rows][S] -> uint8 [rows][ld] of E2M1 codes, two per byte (ld = 16 * ceil(depth / 32))."""
+    bits, rows, _ = planes.shape
+    if out is None:
+        out = torch.empty((rows, 16 * ((depth + 31) // 32)), dtype=torch.uint8, device=planes.device)
+    st = load_library().bs_unpack_planes_fp4(_dev(planes, "planes"), bits, fmt, rows, depth, _dev(out, "out"),
+                                             out.stride(0), _stream())
+    _check(st, "bs_unpack_planes_fp4")
+    return out
+
+
+def bs_gemm_fp4(W: torch.Tensor, At: torch.Tensor, K: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Dense fp4 engine: C[M][N] (int32) from E2M1-coded W [M][>= K/2 bytes] and At [N][>= K/2 bytes]."""
+    M, N = W.shape[0], At.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=W.device)
+    st = load_library().bs_gemm_fp4(_dev(W, "W"), W.stride(0), _dev(At, "At"), At.stride(0), M, N, K,
+                                    _dev(out, "out"), out.stride(0), _stream())
+    _check(st, "bs_gemm_fp4")
+    return out
+
+
+def bs_gemm_fp4_threshold(W: torch.Tensor, At: torch.Tensor, K: int, thr: torch.Tensor, obits: int,
+                          out: torch.Tensor | None = None) -> torch.Tensor:
+    """Dense fp4 engine with the fused thresholding epilogue; output planes as bs_gemm_threshold."""
+    M, N = W.shape[0], At.shape[0]
+    if out is None:
+        out = _planes(obits, N, M, W.device)
+    st = load_library().bs_gemm_fp4_threshold(_dev(W, "W"), W.stride(0), _dev(At, "At"), At.stride(0), M, N, K,
+                                              _dev(thr, "thr"), obits, _dev(out, "out"), _stream())
+    _check(st, "bs_gemm_fp4_threshold")
+    return out
 
 
 def _np_ptr(a):

@@ -25,7 +25,32 @@
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// Operand kinds.  I8: one int8 per depth index, v_mfma_i32_32x32x32_i8 (32 depth indices per
+// instruction).  FP4: two 4-bit E2M1 floating-point codes per byte (low nibble = even depth index),
+// v_mfma_f32_32x32x64_f8f6f4 with both formats set to fp4 (64 depth indices per instruction, the same
+// 16 operand bytes per lane, twice the int8 rate); every value of a <= 2-bit operand (and of a 3-bit
+// two's-complement one) is an E2M1 number, products and sums stay integers below 2^24, so the fp32
+// accumulators are exact and convert to int32 without rounding.  Lane l supplies the 16 bytes
+// [16 (l / 32), 16 (l / 32) + 16) of row l % 32 of the instruction's depth step in both kinds, and
+// the accumulator layout is the same.
+template <bool FP4> struct AccOf { using type = v16i; };
+template <> struct AccOf<true> { using type = v16f; };
+
+template <bool FP4>
+__device__ __forceinline__ typename AccOf<FP4>::type mma(v4i a, v4i b, typename AccOf<FP4>::type c)
+{
+    if constexpr (FP4) {
+        const v8i a8 = {a.x, a.y, a.z, a.w, 0, 0, 0, 0}, b8 = {b.x, b.y, b.z, b.w, 0, 0, 0, 0};
+        // format selectors 4 = fp4 for both operands; zero scale operands select the unscaled instruction
+        return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+    }
+}
 
 constexpr int DK = 64;        // depth bytes per row and stage
 constexpr int DROW = 80;      // LDS row stride in bytes (64 + 16 pad)
@@ -35,7 +60,7 @@ struct DenseParams {
     const int8_t *W;   // [M][ldw]
     const int8_t *A;   // [N][lda]  (activations, depth-contiguous)
     long long ldw, lda;
-    int M, N, K;
+    int M, N, K;       // K: depth in operand BYTES (int8: depth indices; fp4: half as many)
     int32_t *C;
     long long ldc;
     const int32_t *thr;
@@ -61,9 +86,9 @@ __device__ __forceinline__ uint4 mask_tail(uint4 v, int k, int K)
 
 // Epilogue shared by the two dense kernels: int32 store, or successive thresholding with
 // the packed-plane output.  `lds` is the (no longer needed) operand space of the caller.
-template <int WTM, int WTN, bool FUSE>
-__device__ __forceinline__ void dense_epilogue(const DenseParams &p, v16i (&acc)[WTM][WTN], unsigned char *lds,
-                                               int m0, int n0, int tile_m)
+template <int WTM, int WTN, bool FUSE, bool FP4>
+__device__ __forceinline__ void dense_epilogue(const DenseParams &p, typename AccOf<FP4>::type (&acc)[WTM][WTN],
+                                               unsigned char *lds, int m0, int n0, int tile_m)
 {
     constexpr int BM = 64 * WTM;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -79,7 +104,7 @@ __device__ __forceinline__ void dense_epilogue(const DenseParams &p, v16i (&acc)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int m = m0 + (wm * WTM + a) * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-                    if (m < p.M && n < p.N) p.C[(long long)m * p.ldc + n] = acc[a][b][v];
+                    if (m < p.M && n < p.N) p.C[(long long)m * p.ldc + n] = (int)acc[a][b][v];
                 }
             }
     } else {
@@ -113,7 +138,7 @@ __device__ __forceinline__ void dense_epilogue(const DenseParams &p, v16i (&acc)
                     const int4 th = tl[(rbase + rr) * 4 + q];
 #pragma unroll
                     for (int b = 0; b < WTN; ++b) {
-                        const int c = acc[a][b][v];
+                        const int c = (int)acc[a][b][v];
                         y[b] += (uint32_t)(c >= th.x) + (uint32_t)(c >= th.y) + (uint32_t)(c >= th.z) + (uint32_t)(c >= th.w);
                     }
                 }
@@ -140,7 +165,7 @@ __device__ __forceinline__ void dense_epilogue(const DenseParams &p, v16i (&acc)
     }
 }
 
-template <int WTM, int WTN, bool FUSE>
+template <int WTM, int WTN, bool FUSE, bool FP4>
 __global__ void __launch_bounds__(256)
 dense_gemm_kernel(const DenseParams p)
 {
@@ -200,7 +225,7 @@ dense_gemm_kernel(const DenseParams p)
         }
     };
 
-    v16i acc[WTM][WTN];
+    typename AccOf<FP4>::type acc[WTM][WTN];
 #pragma unroll
     for (int a = 0; a < WTM; ++a)
 #pragma unroll
@@ -231,7 +256,7 @@ dense_gemm_kernel(const DenseParams p)
         for (int a = 0; a < WTM; ++a)
 #pragma unroll
             for (int b = 0; b < WTN; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][a], fb[set][b], acc[a][b], 0, 0, 0);
+                acc[a][b] = mma<FP4>(fa[set][a], fb[set][b], acc[a][b]);
     };
 
     // One stage of the pipeline.  PAR = parity of the stage index = LDS buffer it is read
@@ -307,7 +332,7 @@ dense_gemm_kernel(const DenseParams p)
         step(P1{}, std::false_type{}, i + 1);
     }
 
-    dense_epilogue<WTM, WTN, FUSE>(p, acc, lds, m0, n0, tile_m);
+    dense_epilogue<WTM, WTN, FUSE, FP4>(p, acc, lds, m0, n0, tile_m);
 }
 
 // ------------------------------------------------------------------ variant with direct global -> LDS loads
@@ -321,7 +346,7 @@ dense_gemm_kernel(const DenseParams p)
 // multiple of 64 (no tail to mask); other depths use the register-staged kernel above.
 typedef __attribute__((address_space(3))) void lds_void;
 
-template <int WTM, int WTN, bool FUSE>
+template <int WTM, int WTN, bool FUSE, bool FP4>
 __global__ void __launch_bounds__(256)
 dense_gemm_lds_kernel(const DenseParams p)
 {
@@ -359,7 +384,7 @@ dense_gemm_lds_kernel(const DenseParams p)
                                              16, 0, 0);
     };
 
-    v16i acc[WTM][WTN];
+    typename AccOf<FP4>::type acc[WTM][WTN];
 #pragma unroll
     for (int a = 0; a < WTM; ++a)
 #pragma unroll
@@ -385,7 +410,7 @@ dense_gemm_lds_kernel(const DenseParams p)
         for (int a = 0; a < WTM; ++a)
 #pragma unroll
             for (int b = 0; b < WTN; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[set][a], fb[set][b], acc[a][b], 0, 0, 0);
+                acc[a][b] = mma<FP4>(fa[set][a], fb[set][b], acc[a][b]);
     };
 
     const int nst = p.K / DK;
@@ -441,7 +466,7 @@ dense_gemm_lds_kernel(const DenseParams p)
         cur = cur == NBUF - 1 ? 0 : cur + 1;
     }
 
-    dense_epilogue<WTM, WTN, FUSE>(p, acc, lds, m0, n0, tile_m);
+    dense_epilogue<WTM, WTN, FUSE, FP4>(p, acc, lds, m0, n0, tile_m);
 }
 
 // ------------------------------------------------------------------ unpack (planes -> int8)
@@ -489,7 +514,7 @@ unpack_kernel(const uint32_t *__restrict__ planes, int bits, long long rows, lon
     if (dw * 32 + 16 < ((depth + 15) / 16) * 16) *reinterpret_cast<uint4 *>(o + 16) = make_uint4(out[4], out[5], out[6], out[7]);
 }
 
-template <int WTM, int WTN>
+template <int WTM, int WTN, bool FP4>
 bs_status launch_dense(DenseParams &p, bool fuse, hipStream_t st)
 {
     constexpr int BM = 64 * WTM, BN = 64 * WTN;
@@ -498,19 +523,22 @@ bs_status launch_dense(DenseParams &p, bool fuse, hipStream_t st)
     const long long blocks = (long long)p.gx * p.gy;
     if (blocks >= (1LL << 31)) return BS_ERR_UNSUPPORTED;
     if (p.K % DK == 0) {  // no depth tail: operands can go straight from memory to LDS
-        if (fuse) dense_gemm_lds_kernel<WTM, WTN, true><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
-        else dense_gemm_lds_kernel<WTM, WTN, false><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+        if (fuse) dense_gemm_lds_kernel<WTM, WTN, true, FP4><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+        else dense_gemm_lds_kernel<WTM, WTN, false, FP4><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
     } else {
-        if (fuse) dense_gemm_kernel<WTM, WTN, true><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
-        else dense_gemm_kernel<WTM, WTN, false><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+        if (fuse) dense_gemm_kernel<WTM, WTN, true, FP4><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+        else dense_gemm_kernel<WTM, WTN, false, FP4><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
     }
     return bs::after_launch();
 }
 
-bs_status dense_common(const int8_t *W, int64_t ldw, const int8_t *At, int64_t lda, int64_t M, int64_t N, int64_t K,
+// K counts depth indices; the operands hold one (int8) or half a (fp4) byte per index.
+template <bool FP4>
+bs_status dense_common(const void *W, int64_t ldw, const void *At, int64_t lda, int64_t M, int64_t N, int64_t K,
                        int32_t *C, int64_t ldc, const int32_t *thr, int obits, uint64_t *Yp, bool fuse, void *stream)
 {
-    if (!W || !At || M <= 0 || N <= 0 || K <= 0 || ldw < K || lda < K) return BS_ERR_INVALID_ARG;
+    const int64_t Kbytes = FP4 ? (K + 1) / 2 : K;
+    if (!W || !At || M <= 0 || N <= 0 || K <= 0 || ldw < Kbytes || lda < Kbytes) return BS_ERR_INVALID_ARG;
     if (!bs::aligned(W, 16) || !bs::aligned(At, 16) || (ldw & 15) || (lda & 15)) return BS_ERR_ALIGNMENT;
     if (fuse) {
         if (!thr || !Yp || obits < 1) return BS_ERR_INVALID_ARG;
@@ -520,12 +548,13 @@ bs_status dense_common(const int8_t *W, int64_t ldw, const int8_t *At, int64_t l
         if (!C || ldc < N) return BS_ERR_INVALID_ARG;
         if (!bs::aligned(C, 4)) return BS_ERR_ALIGNMENT;
     }
-    // |w|, |a| <= 128: every partial sum stays below 2^31 while K < 2^17
-    if (K >= (int64_t(1) << 17)) return BS_ERR_OVERFLOW_RISK;
+    // int8: |w|, |a| <= 128, every partial sum stays below 2^31 while K < 2^17.
+    // fp4: |w|, |a| <= 6, every partial sum stays below 2^24 (exact in fp32) while K < 2^18.
+    if (K >= (int64_t(1) << (FP4 ? 18 : 17))) return BS_ERR_OVERFLOW_RISK;
     if (M >= (int64_t(1) << 31) || N >= (int64_t(1) << 31)) return BS_ERR_OVERFLOW_RISK;
     DenseParams p;
-    p.W = W; p.A = At; p.ldw = ldw; p.lda = lda;
-    p.M = (int)M; p.N = (int)N; p.K = (int)K;
+    p.W = static_cast<const int8_t *>(W); p.A = static_cast<const int8_t *>(At); p.ldw = ldw; p.lda = lda;
+    p.M = (int)M; p.N = (int)N; p.K = (int)Kbytes;
     p.C = C; p.ldc = ldc;
     p.thr = thr; p.obits = obits; p.T = fuse ? (1 << obits) - 1 : 0;
     p.Y = reinterpret_cast<uint32_t *>(Yp);
@@ -533,8 +562,57 @@ bs_status dense_common(const int8_t *W, int64_t ldw, const int8_t *At, int64_t l
     hipStream_t st = static_cast<hipStream_t>(stream);
     // 256 x 256 tiles when they still give every compute unit work, else 128 x 128
     const long long big = (long long)((M + 255) / 256) * ((N + 255) / 256);
-    if (big >= 256) return launch_dense<4, 4>(p, fuse, st);
-    return launch_dense<2, 2>(p, fuse, st);
+    if (big >= 256) return launch_dense<4, 4, FP4>(p, fuse, st);
+    return launch_dense<2, 2, FP4>(p, fuse, st);
+}
+
+// ------------------------------------------------------------------ unpack (planes -> fp4 codes)
+// One thread turns one 32-bit word per plane (32 depth indices of one row) into 32 E2M1 codes
+// (16 bytes, low nibble = even index).  lut holds the code of every plane-bit combination c
+// (bit i of c = bit of plane i) in its nibble c.
+__global__ void __launch_bounds__(256)
+unpack_fp4_kernel(const uint32_t *__restrict__ planes, int bits, unsigned long long lut, long long rows,
+                  long long depth, int Kd, uint8_t *__restrict__ dst, long long ld, long long words_per_row)
+{
+    const long long item = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (item >= rows * words_per_row) return;
+    const long long r = item / words_per_row, dw = item - r * words_per_row;
+    uint32_t x[3] = {0, 0, 0};
+#pragma unroll
+    for (int pl = 0; pl < 3; ++pl)
+        if (pl < bits) x[pl] = planes[((long long)pl * rows + r) * Kd + dw];
+    uint32_t out[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        uint32_t o = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int k = 8 * g + e;
+            const uint32_t c = ((x[0] >> k) & 1u) | (((x[1] >> k) & 1u) << 1) | (((x[2] >> k) & 1u) << 2);
+            uint32_t code = (uint32_t)(lut >> (4 * c)) & 0xFu;
+            if (dw * 32 + k >= depth) code = 0;  // +0.0 past the depth
+            o |= code << (4 * e);
+        }
+        out[g] = o;
+    }
+    *reinterpret_cast<uint4 *>(dst + r * ld + dw * 16) = make_uint4(out[0], out[1], out[2], out[3]);
+}
+
+// E2M1 code of a small integer, -1 if it is not representable (the format holds 0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives)
+int fp4_code_of(int v)
+{
+    const int mag = v < 0 ? -v : v;
+    int code;
+    switch (mag) {
+    case 0: code = 0x0; break;
+    case 1: code = 0x2; break;
+    case 2: code = 0x4; break;
+    case 3: code = 0x5; break;
+    case 4: code = 0x6; break;
+    case 6: code = 0x7; break;
+    default: return -1;
+    }
+    return v < 0 ? code | 0x8 : code;
 }
 
 }  // namespace
@@ -563,12 +641,50 @@ extern "C" bs_status bs_unpack_planes(const uint64_t *planes, int bits, bs_forma
 extern "C" bs_status bs_gemm_i8(const int8_t *W, int64_t ldw, const int8_t *At, int64_t lda, int64_t M, int64_t N,
                                 int64_t K, int32_t *C, int64_t ldc, void *stream)
 {
-    return dense_common(W, ldw, At, lda, M, N, K, C, ldc, nullptr, 0, nullptr, false, stream);
+    return dense_common<false>(W, ldw, At, lda, M, N, K, C, ldc, nullptr, 0, nullptr, false, stream);
 }
 
 extern "C" bs_status bs_gemm_i8_threshold(const int8_t *W, int64_t ldw, const int8_t *At, int64_t lda, int64_t M,
                                           int64_t N, int64_t K, const int32_t *thr, int obits, uint64_t *Yp,
                                           void *stream)
 {
-    return dense_common(W, ldw, At, lda, M, N, K, nullptr, 0, thr, obits, Yp, true, stream);
+    return dense_common<false>(W, ldw, At, lda, M, N, K, nullptr, 0, thr, obits, Yp, true, stream);
+}
+
+extern "C" bs_status bs_unpack_planes_fp4(const uint64_t *planes, int bits, bs_format fmt, int64_t rows, int64_t depth,
+                                          uint8_t *dst, int64_t ld, void *stream)
+{
+    if (!planes || !dst || rows <= 0 || depth <= 0) return BS_ERR_INVALID_ARG;
+    if (bs_status s = bs::check_bits_fmt(bits, fmt)) return s;
+    const int64_t words = (depth + 31) / 32;
+    if (ld < words * 16) return BS_ERR_INVALID_ARG;
+    if (!bs::aligned(planes, 16) || !bs::aligned(dst, 16) || (ld & 15)) return BS_ERR_ALIGNMENT;
+    const int64_t S = bs_words_per_row(depth);
+    if (rows * S * 2 * bits >= (int64_t(1) << 31)) return BS_ERR_OVERFLOW_RISK;
+    unsigned long long lut = 0;
+    for (int c = 0; c < (1 << bits); ++c) {
+        int v = c;
+        if (fmt == BS_BIPOLAR) v = 2 * c - 1;
+        else if (fmt == BS_TWOS_COMPLEMENT && c >= (1 << (bits - 1))) v = c - (1 << bits);
+        const int code = fp4_code_of(v);
+        if (code < 0) return BS_ERR_UNSUPPORTED;  // 3-bit unsigned (5, 7) and every 4-bit format
+        lut |= (unsigned long long)code << (4 * c);
+    }
+    const int64_t items = rows * words;
+    unpack_fp4_kernel<<<dim3((unsigned)((items + 255) / 256)), 256, 0, static_cast<hipStream_t>(stream)>>>(
+        reinterpret_cast<const uint32_t *>(planes), bits, lut, rows, depth, (int)(2 * S), dst, ld, words);
+    return bs::after_launch();
+}
+
+extern "C" bs_status bs_gemm_fp4(const uint8_t *W, int64_t ldw, const uint8_t *At, int64_t lda, int64_t M, int64_t N,
+                                 int64_t K, int32_t *C, int64_t ldc, void *stream)
+{
+    return dense_common<true>(W, ldw, At, lda, M, N, K, C, ldc, nullptr, 0, nullptr, false, stream);
+}
+
+extern "C" bs_status bs_gemm_fp4_threshold(const uint8_t *W, int64_t ldw, const uint8_t *At, int64_t lda, int64_t M,
+                                           int64_t N, int64_t K, const int32_t *thr, int obits, uint64_t *Yp,
+                                           void *stream)
+{
+    return dense_common<true>(W, ldw, At, lda, M, N, K, nullptr, 0, thr, obits, Yp, true, stream);
 }
