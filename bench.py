@@ -330,8 +330,26 @@ def extras(bs, workloads, dev, timed):
     ms = timed_graph([lambda: bs.bs_unpack_planes(Wp2, TC, 4096, out=W8)], 20)
     out["unpack_4096x4096_2_planes_to_i8"] = {"us": round(ms * 1e3, 2),
                                               "GBps": round((Wp2.numel() * 8 + W8.numel()) / ms / 1e6, 1)}
-    # per-layer engine choice (Sec. 4.1.1 / 4.2): both engines timed on the same fused product, the dense one
-    # including the unpack of its activations, beside what bs_choose_engine picks
+    # the fp4 flavour of the dense engine (operands of at most 2 bits as E2M1 codes, twice the int8 MFMA rate)
+    def dense_fp4(name, M, N, K, obits):
+        Wd = torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device="cuda") & 0x55   # nibbles 0, 1, 4, 5: 0, 0.5, 2, 3
+        Ad = torch.randint(0, 256, (N, K // 2), dtype=torch.uint8, device="cuda") & 0x55
+        if obits:
+            th = thr_for(M, obits)
+            Y = torch.empty((obits, N, bs.bs_words_per_row(M)), dtype=torch.int64, device="cuda")
+            f = lambda: bs.bs_gemm_fp4_threshold(Wd, Ad, K, th, obits, out=Y)
+        else:
+            Cd = torch.empty((M, N), dtype=torch.int32, device="cuda")
+            f = lambda: bs.bs_gemm_fp4(Wd, Ad, K, out=Cd)
+        ms, _ = timed(f, 10, 3)
+        tops = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+        out[name] = {"us": round(ms * 1e3, 2), "GOPS": round(tops * 1e3, 1),
+                     "roofline": {"bound": "mfma", "achieved": round(tops, 1), "peak": 10100.0, "unit": "fp4 TFLOP/s",
+                                  "frac": round(tops / 10100.0, 4)}}
+    dense_fp4("dense_fp4_engine_4096x4096x4096_int32_out", 4096, 4096, 4096, 0)
+    dense_fp4("dense_fp4_engine_8192x8192x8192_fused_2bit_out", 8192, 8192, 8192, 2)
+    # per-layer engine choice (Sec. 4.1.1 / 4.2): the engines timed on the same fused product, the dense ones
+    # including the unpack of their activations, beside what bs_choose_engine picks
     choice = {}
     for (w_, a_, M_, N_, K_) in [(1, 2, 256, 729, 2400), (1, 2, 4096, 1024, 4096), (2, 2, 1024, 1024, 4096),
                                  (4, 4, 8192, 64, 8192), (4, 4, 1024, 256, 1024)]:
@@ -339,19 +357,27 @@ def extras(bs, workloads, dev, timed):
         Wq, Aq = planes(w_, M_, K_), planes(a_, N_, K_)
         th_ = thr_for(M_, a_)
         Yq = torch.empty((a_, N_, bs.bs_words_per_row(M_)), dtype=torch.int64, device="cuda")
-        t_bs = timed_graph([lambda: bs.bs_gemm_threshold(Wq, wf_, Aq, U, K_, th_, a_, out=Yq)], 10)
+        times = {"bitserial": timed_graph([lambda: bs.bs_gemm_threshold(Wq, wf_, Aq, U, K_, th_, a_, out=Yq)], 10)}
         W8q = bs.bs_unpack_planes(Wq, wf_, K_)
         A8q = torch.empty((N_, W8q.shape[1]), dtype=torch.int8, device="cuda")
 
-        def dense_route():
+        def int8_route():
             bs.bs_unpack_planes(Aq, U, K_, out=A8q)
             bs.bs_gemm_i8_threshold(W8q, A8q, K_, th_, a_, out=Yq)
-        t_d = timed_graph([dense_route], 10)
-        pick = bs.bs_choose_engine(w_, a_, M_, N_, K_)
-        choice["W%dA%d_%dx%dx%d" % (w_, a_, M_, K_, N_)] = {
-            "bitserial_us": round(t_bs * 1e3, 2), "dense_us": round(t_d * 1e3, 2),
-            "chosen": "dense" if pick == bs.BS_ENGINE_DENSE_I8 else "bitserial",
-            "faster": "dense" if t_d < t_bs else "bitserial"}
+        times["dense_int8"] = timed_graph([int8_route], 10)
+        if w_ <= 2 and a_ <= 2:
+            W4q = bs.bs_unpack_planes_fp4(Wq, wf_, K_)
+            A4q = torch.empty((N_, W4q.shape[1]), dtype=torch.uint8, device="cuda")
+
+            def fp4_route():
+                bs.bs_unpack_planes_fp4(Aq, U, K_, out=A4q)
+                bs.bs_gemm_fp4_threshold(W4q, A4q, K_, th_, a_, out=Yq)
+            times["dense_fp4"] = timed_graph([fp4_route], 10)
+        pick = bs.bs_choose_engine(w_, wf_, a_, U, M_, N_, K_)
+        row = {k + "_us": round(v * 1e3, 2) for k, v in times.items()}
+        row["chosen"] = ["bitserial", "dense_int8", "dense_fp4"][pick]
+        row["fastest"] = min(times, key=times.get)
+        choice["W%dA%d_%dx%dx%d" % (w_, a_, M_, K_, N_)] = row
     out["engine_choice"] = choice
     # stand-alone thresholding of a large int32 result (the unfused route of S5)
     Cbig = torch.randint(-40000, -20000, (8192, 8192), dtype=torch.int32, device="cuda")

@@ -257,17 +257,21 @@ bs_status bs_streamline_thresholds(const double *t, int T, const double *a, cons
 /*
  * Per-layer engine choice (Sec. 4.1.1 and 4.2 of the paper: bit-serial pays below a break-even
  * precision, and each layer should run on the faster engine).  Host-only, no GPU work.
- * Returns BS_ENGINE_BITSERIAL (bs_gemm / bs_gemm_threshold on packed planes) or BS_ENGINE_DENSE_I8
- * (bs_unpack_planes of the activations + bs_gemm_i8 / bs_gemm_i8_threshold on int8 weights) for a
- * wbits x abits product of shape M x K x N, from a time model fitted to measurements on MI355X:
- *   bit-serial  5.0 us + 0.565 us * (K/1024) * wbits*abits + 2MNK * wbits*abits / 1.27e15 s
- *   dense       8.5 us + 4.7 us * (K/1024) + 1.8 us * abits + 2MNK / 3.38e15 s + M*N / 0.75e12 s
- *               (activation unpack and the thresholding epilogue included)
- * N <= 4 is always bit-serial (weights are read once: wbits/8 byte per weight instead of 1).
- * Invalid arguments (bits outside 1..4, non-positive sizes) return BS_ENGINE_BITSERIAL.
+ * Returns, for a wbits x abits product of shape M x K x N in the given formats,
+ *   BS_ENGINE_BITSERIAL  bs_gemm / bs_gemm_threshold on packed planes,
+ *   BS_ENGINE_DENSE_I8   bs_unpack_planes of the activations + bs_gemm_i8* on int8 weights, or
+ *   BS_ENGINE_DENSE_FP4  bs_unpack_planes_fp4 of the activations + bs_gemm_fp4* on E2M1-coded weights
+ *                        (only when both operands have at most 2 bits or are 3-bit two's complement),
+ * whichever is fastest under a time model fitted to measurements on MI355X (microseconds, p = wbits * abits,
+ * k = K / 1024, activation unpack and the thresholding epilogue included):
+ *   bit-serial  5.0 + 0.565 k p + 2MNK p / 1.27e9
+ *   dense int8  8.5 + 4.7 k + 1.8 abits + 2MNK / 3.38e9 + MN / 0.75e6
+ *   dense fp4   11.0 + 2.4 k + 0.4 abits + 2MNK / 4.35e9 + MN / 1.35e6
+ * N <= 4 is always bit-serial (weights are read once: wbits/8 byte per weight instead of 1 or 1/2).
+ * Invalid arguments (bits outside 1..4, bipolar with bits != 1, non-positive sizes) return BS_ENGINE_BITSERIAL.
  */
-typedef enum { BS_ENGINE_BITSERIAL = 0, BS_ENGINE_DENSE_I8 = 1 } bs_engine;
-bs_engine bs_choose_engine(int wbits, int abits, int64_t M, int64_t N, int64_t K);
+typedef enum { BS_ENGINE_BITSERIAL = 0, BS_ENGINE_DENSE_I8 = 1, BS_ENGINE_DENSE_FP4 = 2 } bs_engine;
+bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_format afmt, int64_t M, int64_t N, int64_t K);
 
 /*
  * Diagnostic: rate probe for the instruction pair of Alg. 1's inner loop (AND, popcount-accumulate).

@@ -73,7 +73,7 @@ def load_library() -> ctypes.CDLL:
     lib.bs_streamline_collapse.argtypes = [i64, f64, f64, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.bs_streamline_collapse.restype = i32
     lib.bs_streamline_thresholds.argtypes = [vp, i32, vp, vp, i64, vp, vp]; lib.bs_streamline_thresholds.restype = i32
-    lib.bs_choose_engine.argtypes = [i32, i32, i64, i64, i64]; lib.bs_choose_engine.restype = i32
+    lib.bs_choose_engine.argtypes = [i32, i32, i32, i32, i64, i64, i64]; lib.bs_choose_engine.restype = i32
     lib.bs_probe_popcount_rate.argtypes = [vp, i32, i32, vp]; lib.bs_probe_popcount_rate.restype = i32
     lib.bs_status_string.argtypes = [i32]; lib.bs_status_string.restype = ctypes.c_char_p
     lib.bs_version.argtypes = []; lib.bs_version.restype = i32
@@ -248,12 +248,12 @@ def bs_gemm_i8_threshold(W: torch.Tensor, At: torch.Tensor, K: int, thr: torch.T
     return out
 
 
-BS_ENGINE_BITSERIAL, BS_ENGINE_DENSE_I8 = 0, 1
+BS_ENGINE_BITSERIAL, BS_ENGINE_DENSE_I8, BS_ENGINE_DENSE_FP4 = 0, 1, 2
 
 
-def bs_choose_engine(wbits: int, abits: int, M: int, N: int, K: int) -> int:
-    """Host-only: BS_ENGINE_BITSERIAL or BS_ENGINE_DENSE_I8 for a wbits x abits product of shape M x K x N."""
-    return load_library().bs_choose_engine(wbits, abits, M, N, K)
+def bs_choose_engine(wbits: int, wfmt: int, abits: int, afmt: int, M: int, N: int, K: int) -> int:
+    """Host-only: the engine (BS_ENGINE_*) expected to be fastest for a wbits x abits product of shape M x K x N."""
+    return load_library().bs_choose_engine(wbits, wfmt, abits, afmt, M, N, K)
 
 
 def bs_probe_popcount_rate(sink: torch.Tensor, passes: int) -> int:

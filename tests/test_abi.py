@@ -124,21 +124,27 @@ def test_oracle_c_part_is_clean_under_sanitizers(tmp_path):
 def test_engine_choice_rules():
     """bs_choose_engine (host-only): the fixed rules and the monotone behaviour of the fitted model."""
     E = bs.bs_choose_engine
-    BSER, DENSE = bs.BS_ENGINE_BITSERIAL, bs.BS_ENGINE_DENSE_I8
+    U, TC, BP = bs.BS_UNSIGNED, bs.BS_TWOS_COMPLEMENT, bs.BS_BIPOLAR
+    BSER, I8, FP4 = bs.BS_ENGINE_BITSERIAL, bs.BS_ENGINE_DENSE_I8, bs.BS_ENGINE_DENSE_FP4
     # few columns: weights are streamed once, the packed form always wins
     for n in (1, 2, 4):
-        assert E(4, 4, 8192, n, 8192) == BSER
+        assert E(4, TC, 4, U, 8192, n, 8192) == BSER and E(2, TC, 2, U, 8192, n, 8192) == BSER
     # invalid arguments fall back to the bit-serial engine
-    assert E(0, 2, 64, 64, 64) == BSER and E(2, 5, 64, 64, 64) == BSER and E(2, 2, 0, 64, 64) == BSER
-    # large compute-bound products of many plane pairs go to the matrix cores, tiny binary ones do not
-    assert E(4, 4, 8192, 8192, 8192) == DENSE
-    assert E(2, 2, 4096, 4096, 4096) == DENSE
-    assert E(1, 1, 256, 256, 1024) == BSER
-    assert E(1, 2, 256, 729, 2400) == BSER      # the conv2 layer of the paper's AlexNet at batch 1
-    # once dense is chosen, more plane pairs or more columns never switch back
+    assert E(0, U, 2, U, 64, 64, 64) == BSER and E(2, U, 5, U, 64, 64, 64) == BSER and E(2, U, 2, U, 0, 64, 64) == BSER
+    assert E(2, BP, 2, U, 4096, 4096, 4096) == BSER
+    # large compute-bound products go to the matrix cores: fp4 where every value is an E2M1 number, else int8
+    assert E(4, TC, 4, U, 8192, 8192, 8192) == I8
+    assert E(2, TC, 2, U, 4096, 4096, 4096) == FP4
+    assert E(1, BP, 2, U, 4096, 4096, 4096) == FP4
+    assert E(3, TC, 2, U, 4096, 4096, 4096) == FP4
+    assert E(3, U, 2, U, 4096, 4096, 4096) == I8       # 5 and 7 are not E2M1 numbers
+    # small layers stay bit-serial
+    assert E(1, BP, 1, BP, 256, 256, 1024) == BSER
+    assert E(1, BP, 2, U, 256, 729, 2400) == BSER      # the conv2 layer of the paper's AlexNet at batch 1
+    # once a dense engine is chosen, more plane pairs never switch back
     for (m, n, k) in [(1024, 1024, 4096), (4096, 256, 4096), (256, 4096, 1024)]:
         seen = False
-        for pairs in [(1, 1), (1, 2), (2, 2), (2, 4), (4, 4)]:
-            d = E(pairs[0], pairs[1], m, n, k) == DENSE
+        for (w, a) in [(1, 1), (1, 2), (2, 2), (2, 4), (4, 4)]:
+            d = E(w, TC, a, U, m, n, k) != BSER
             assert d or not seen
             seen = seen or d
