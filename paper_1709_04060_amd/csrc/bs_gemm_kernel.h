@@ -72,8 +72,12 @@ constexpr long long kStreamWeightBytes = 64ll << 20;
 
 constexpr int kConvMaxLut = 2048;  // lowered dwords the implicit-lowering kernels can index (65536 depth bits)
 
-// GEMV path (bs_gemv.hip): used for at most this many columns, activation planes in LDS.
+// GEMV path (bs_gemv.hip): a workgroup handles at most kGemvMaxCols columns, activation planes in LDS; up to
+// kGemvMaxGroupedCols columns run as groups of four side by side (each group streams the weights again, from
+// L2 as the groups run together): 32 x 32 tiles would leave 3/4 or more of their columns empty there
+// (W4A4 8192 x 8192: 89 us tiled for 5..32 columns, 36 / 53 / 67 us grouped for 8 / 12 / 16).
 constexpr int kGemvMaxCols = 4;
+constexpr int kGemvMaxGroupedCols = 16;
 constexpr size_t kGemvMaxLds = 64 * 1024;
 bool gemv_applicable(const GemmParams &g, int abits, bool a_bipolar, bool w_bipolar);
 bs_status launch_gemv(const GemmParams &g, int wbits, int abits, bool fuse, bool xr, hipStream_t st);

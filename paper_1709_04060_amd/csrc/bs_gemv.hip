@@ -33,6 +33,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams 
 
     const int g = tid & (LANES_PER_ROW - 1), r = tid / LANES_PER_ROW;
     const int m = blockIdx.x * ROWS_PER_BLOCK + r;
+    const int n0 = blockIdx.y * NC;  // first column of this workgroup's group (more than NC columns: several groups)
     const bool mvalid = m < p.M;
     const uint4 *Wg = reinterpret_cast<const uint4 *>(p.W);
 
@@ -85,7 +86,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams 
             const int c = id % nch, jn = id / nch;
             const int n = jn % NC, j = jn / NC;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (n < p.N) v = Ag[(size_t)(j * p.N + n) * nch + c];
+            if (n0 + n < p.N) v = Ag[(size_t)(j * p.N + n0 + n) * nch + c];
             ldsA[id] = v;
             const int pc = popc4(v) * p.ccol[j];
 #pragma unroll
@@ -146,7 +147,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams 
         if (leader) {
 #pragma unroll
             for (int n = 0; n < NC; ++n)
-                if (n < p.N) p.C[(long long)m * p.ldc + n] = val[n];
+                if (n0 + n < p.N) p.C[(long long)m * p.ldc + n0 + n] = val[n];
         }
     } else {
         uint8_t *Yb = reinterpret_cast<uint8_t *>(p.Y);
@@ -171,15 +172,15 @@ __global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams 
         // thread (pl, n) assembles the byte of plane pl, column n from the eight rows
         if (tid < p.obits * NC) {
             const int pl = tid / NC, n = tid % NC;
-            if (n < p.N) {
+            if (n0 + n < p.N) {
                 unsigned byte = 0;
 #pragma unroll
                 for (int rr = 0; rr < ROWS_PER_BLOCK; ++rr) byte |= ((yrow[rr][n] >> pl) & 1u) << rr;
-                Yb[((long long)pl * p.N + n) * col_bytes + blockIdx.x] = (uint8_t)byte;
+                Yb[((long long)pl * p.N + n0 + n) * col_bytes + blockIdx.x] = (uint8_t)byte;
             }
         }
-        // the last workgroup clears the padding bytes of every column
-        if (blockIdx.x == gridDim.x - 1) {
+        // the last workgroup (of the first column group) clears the padding bytes of every column
+        if (blockIdx.x == gridDim.x - 1 && blockIdx.y == 0) {
             const int first = gridDim.x, npad = (int)col_bytes - first;
             for (int it = tid; it < npad * p.obits * p.N; it += GEMV_THREADS) {
                 const int z = it % npad, cn = it / npad;
@@ -192,7 +193,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams 
 template <int WB, int AB, int NC>
 bs_status launch_gemv_nc(const GemmParams &g, bool fuse, bool xr, size_t lds_bytes, hipStream_t st)
 {
-    dim3 grid((unsigned)((g.M + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK));
+    dim3 grid((unsigned)((g.M + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), (unsigned)((g.N + NC - 1) / NC));
     if (xr) {
         if constexpr (WB == 1 && AB == 1) {
             if (fuse) bs_gemv_kernel<1, 1, NC, true, true><<<grid, GEMV_THREADS, lds_bytes, st>>>(g);
@@ -242,7 +243,7 @@ bs_status launch_gemv_wb(const GemmParams &g, int abits, bool fuse, bool xr, hip
 bool gemv_applicable(const GemmParams &g, int abits, bool a_bipolar, bool w_bipolar)
 {
     // bipolar activations are handled in the XOR form only (both operands bipolar)
-    if (g.N > kGemvMaxCols || (a_bipolar && !w_bipolar)) return false;
+    if (g.N > kGemvMaxGroupedCols || (a_bipolar && !w_bipolar)) return false;
     const int nc = g.N == 1 ? 1 : (g.N == 2 ? 2 : 4);
     return (size_t)abits * nc * (g.Kd >> 2) * 16 <= kGemvMaxLds;
 }

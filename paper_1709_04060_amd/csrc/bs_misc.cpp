@@ -31,7 +31,9 @@ extern "C" bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_f
     if (N <= 4) return BS_ENGINE_BITSERIAL;  // weights streamed once: wbits/8 byte per weight beats a byte or half a byte
     const double pairs = (double)wbits * abits, kk = (double)K / 1024.0;
     const double mnk2 = 2.0 * (double)M * (double)N * (double)K, mn = (double)M * (double)N;
-    const double t_bitserial = 5.0 + 0.565 * kk * pairs + mnk2 * pairs / 1.27e9;
+    // up to 16 columns the bit-serial call is the streaming kernel in groups of four columns
+    const double t_bitserial = N <= 16 ? 5.4 + 2.0 * (double)M * (double)(4 * ((N + 3) / 4)) * (double)K * pairs / 0.354e9
+                                       : 5.0 + 0.565 * kk * pairs + mnk2 * pairs / 1.27e9;
     if (fp4_representable(wbits, wfmt) && fp4_representable(abits, afmt)) {
         const double t_fp4 = 11.0 + 2.4 * kk + 0.4 * abits + mnk2 / 4.35e9 + mn / 1.35e6;
         return t_fp4 < t_bitserial ? BS_ENGINE_DENSE_FP4 : BS_ENGINE_BITSERIAL;  // measured 1.1 - 1.5 x faster than int8 everywhere

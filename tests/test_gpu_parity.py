@@ -115,12 +115,12 @@ def test_gemm_shapes(M, K, N, w, wf, a, af):
     assert_equal(run_gemm(W, A, w, wf, a, af), oracle.gemm(W, A), "gemm %dx%dx%d" % (M, K, N))
 
 
-@pytest.mark.parametrize("N", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 6, 7, 8, 9, 13, 16, 17])
 @pytest.mark.parametrize("M,K", [(1, 1), (7, 64), (8, 130), (9, 1000), (100, 9216), (333, 4100)])
 @pytest.mark.parametrize("w,wf,a,af,obits", [(1, BP, 2, U, 2), (4, TC, 4, U, 4), (2, U, 3, TC, 1), (3, TC, 1, U, 3),
                                              (1, U, 1, BP, 2)])
 def test_few_column_path(N, M, K, w, wf, a, af, obits):
-    """N <= 4 takes the streaming (GEMV) kernel; N = 5 and bipolar activations the tiled one."""
+    """N <= 16 takes the streaming (GEMV) kernel, in groups of four columns; N = 17 and bipolar activations the tiled one."""
     rng = np.random.default_rng(N * 100 + M + K + w)
     W, A = draw(rng, (M, K), w, wf), draw(rng, (K, N), a, af)
     want = oracle.gemm(W, A)
