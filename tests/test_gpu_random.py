@@ -1,0 +1,119 @@
+"""Seeded random sweep over shapes, precisions, formats and engines: every case compares the int32 product and the
+fused thresholded planes of the GPU path with the oracle, element by element.  The draws put extra weight on the
+sizes where the launch configuration changes (few columns, tile and word boundaries)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1709_04060_amd as bs
+from gpu_util import FMT, assert_equal, dev, draw, planes_to_numpy
+
+pytestmark = pytest.mark.gpu
+U, TC, BP = oracle.UNSIGNED, oracle.TWOS_COMPLEMENT, oracle.BIPOLAR
+EDGES = [1, 2, 3, 4, 5, 8, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257]
+
+
+def draw_size(rng, hi):
+    return int(rng.choice(EDGES)) if rng.random() < 0.5 else int(rng.integers(1, hi + 1))
+
+
+def draw_operand(rng):
+    fmt = [U, TC, BP][int(rng.integers(3))]
+    bits = 1 if fmt == BP else int(rng.integers(1, 5))
+    return bits, fmt
+
+
+def make_case(seed):
+    rng = np.random.default_rng([20240611, seed])
+    (w, wf), (a, af) = draw_operand(rng), draw_operand(rng)
+    M, N = draw_size(rng, 600), draw_size(rng, 600)
+    K = int(rng.choice([1, 31, 32, 33, 64, 127, 128, 129, 1024, 1025])) if rng.random() < 0.4 else int(rng.integers(1, 4000))
+    obits = int(rng.integers(1, 5))
+    W, A = draw(rng, (M, K), w, wf), draw(rng, (K, N), a, af)
+    C = oracle.gemm(W, A)
+    T = (1 << obits) - 1
+    thr = np.sort(rng.integers(int(C.min()) - 2, int(C.max()) + 3, size=(M, T)), axis=1).astype(np.int32)
+    return rng, w, wf, a, af, M, K, N, obits, W, A, C, thr
+
+
+@pytest.mark.parametrize("seed", range(120))
+def test_random_bit_serial(seed):
+    rng, w, wf, a, af, M, K, N, obits, W, A, C, thr = make_case(seed)
+    what = "seed %d W%d(%d)A%d(%d) %dx%dx%d o=%d" % (seed, w, wf, a, af, M, K, N, obits)
+    Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
+    Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
+    assert_equal(bs.bs_gemm(Wp, FMT[wf], Ap, FMT[af], K).cpu().numpy(), C, "bs_gemm " + what)
+    out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
+    bs.bs_gemm_threshold(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits, out=out)
+    want = oracle.threshold_pack(C, thr, obits)
+    assert_equal(planes_to_numpy(out), want, "bs_gemm_threshold " + what)
+    out2 = torch.full_like(out, -1)
+    bs.bs_threshold_activate(dev(C), dev(thr), obits, out=out2)
+    assert_equal(planes_to_numpy(out2), want, "bs_threshold_activate " + what)
+
+
+@pytest.mark.parametrize("seed", range(120, 180))
+def test_random_dense_engines(seed):
+    """The int8 engine on every drawn case, the fp4 engine where both operands are E2M1-representable; both fed through
+    the plane unpackers, so that the route bs_choose_engine may pick is the one under test."""
+    rng, w, wf, a, af, M, K, N, obits, W, A, C, thr = make_case(seed)
+    what = "seed %d W%d(%d)A%d(%d) %dx%dx%d o=%d" % (seed, w, wf, a, af, M, K, N, obits)
+    Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
+    Ap = bs.bs_pack_planes(dev(A.T.copy()), a, FMT[af])
+    want = oracle.threshold_pack(C, thr, obits)
+    W8, A8 = bs.bs_unpack_planes(Wp, FMT[wf], K), bs.bs_unpack_planes(Ap, FMT[af], K)
+    assert_equal(bs.bs_gemm_i8(W8, A8, K).cpu().numpy(), C, "bs_gemm_i8 " + what)
+    out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
+    bs.bs_gemm_i8_threshold(W8, A8, K, dev(thr), obits, out=out)
+    assert_equal(planes_to_numpy(out), want, "bs_gemm_i8_threshold " + what)
+    rep = lambda b, f: b <= 2 or (b == 3 and f == TC)
+    if rep(w, wf) and rep(a, af):
+        W4, A4 = bs.bs_unpack_planes_fp4(Wp, FMT[wf], K), bs.bs_unpack_planes_fp4(Ap, FMT[af], K)
+        assert_equal(bs.bs_gemm_fp4(W4, A4, K).cpu().numpy(), C, "bs_gemm_fp4 " + what)
+        out.fill_(-1)
+        bs.bs_gemm_fp4_threshold(W4, A4, K, dev(thr), obits, out=out)
+        assert_equal(planes_to_numpy(out), want, "bs_gemm_fp4_threshold " + what)
+
+
+@pytest.mark.parametrize("seed", range(200, 240))
+def test_random_convolution_and_pooling(seed):
+    """Random geometries for the fused convolution (implicit lowering), the two-call route through the lowered matrix,
+    and max pooling of the resulting packed map, against the direct convolution of the oracle."""
+    rng = np.random.default_rng([20240611, seed])
+    (w, wf), (a, af) = draw_operand(rng), draw_operand(rng)
+    if af == BP:
+        a, af = int(rng.integers(1, 5)), U         # image planes are unsigned or two's complement
+    k = int(rng.choice([1, 2, 3, 5]))
+    s, p = int(rng.integers(1, 4)), int(rng.integers(0, 3))
+    H, W = int(rng.integers(k, 22)), int(rng.integers(k, 22))
+    C = int(rng.choice([1, 3, 31, 32, 33, 64, 96, 130])) if rng.random() < 0.6 else int(rng.integers(1, 140))
+    F = draw_size(rng, 300)
+    obits = int(rng.integers(1, 5))
+    x, filt = draw(rng, (H, W, C), a, af), draw(rng, (F, k, k, C), w, wf)
+    conv = oracle.conv_direct(x, filt, s, p)
+    OH, OW, _ = conv.shape
+    Cmat = conv.reshape(OH * OW, F).T.copy()
+    T = (1 << obits) - 1
+    thr = np.sort(rng.integers(int(conv.min()) - 2, int(conv.max()) + 3, size=(F, T)), axis=1).astype(np.int32)
+    want = oracle.threshold_pack(Cmat, thr, obits)
+    what = "seed %d W%d(%d)A%d(%d) %dx%dx%d F=%d k=%d s=%d p=%d o=%d" % (seed, w, wf, a, af, H, W, C, F, k, s, p, obits)
+    Cp = 32 * ((C + 31) // 32)
+    fpad = np.zeros((F, k, k, Cp), dtype=filt.dtype)
+    fpad[..., :C] = filt
+    if wf == BP:
+        fpad[..., C:] = -1                          # any value does: the activation pad bits are zero
+    xp = bs.bs_pack_planes(dev(x.reshape(H * W, C)), a, FMT[af])
+    Fp = bs.bs_pack_planes(dev(fpad.reshape(F, -1)), w, FMT[wf])
+    out = torch.full((obits, OH * OW, bs.bs_words_per_row(F)), -1, dtype=torch.int64, device="cuda")
+    bs.bs_conv_threshold(xp, FMT[af], H, W, C, Fp, FMT[wf], k, k, s, p, dev(thr), obits, out=out)
+    assert_equal(planes_to_numpy(out), want, "bs_conv_threshold " + what)
+    low = bs.bs_im2col_interleaved(xp, H, W, C, k, k, s, p)
+    two = bs.bs_gemm_threshold(Fp, FMT[wf], low, FMT[af], bs.bs_lowered_depth(C, k, k), dev(thr), obits)
+    assert_equal(planes_to_numpy(two), want, "bs_im2col_interleaved + bs_gemm_threshold " + what)
+    pk = int(rng.integers(1, 4))
+    if pk <= min(OH, OW):
+        ps = int(rng.integers(1, 3))
+        Y = oracle.threshold(Cmat, thr).T.reshape(OH, OW, F)
+        pooled = bs.bs_maxpool_packed(out, OH, OW, F, pk, ps)
+        assert_equal(planes_to_numpy(pooled), oracle.pack(oracle.maxpool(Y, pk, ps).reshape(-1, F), obits, U), "bs_maxpool_packed " + what)
