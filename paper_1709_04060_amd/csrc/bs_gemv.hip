@@ -1,7 +1,9 @@
 // Bit-serial GEMV: the bit-serial GEMM of Alg. 2 for a handful of columns (batch-1
-// fully-connected layers, Table 2's (4096, 9216, 1) and (4096, 4096, 1)).  Every weight
-// bit is read exactly once and used for N <= 4 columns, so the kernel is a stream over
-// the packed weight planes bound by HBM, not by popcount throughput.
+// fully-connected layers, Table 2's (4096, 9216, 1) and (4096, 4096, 1)).  A workgroup
+// reads every weight bit of its rows exactly once and uses it for up to four columns, so
+// the kernel is a stream over the packed weight planes bound by HBM, not by popcount
+// throughput.  Five to sixteen columns run as groups of four in the grid's second
+// dimension; the groups run side by side and find the weights of the others in L2.
 //
 // Shape: a workgroup of four wavefronts owns eight rows (one output byte per plane and
 // column); 32 lanes share a row and read consecutive 16-byte chunks, so one load
