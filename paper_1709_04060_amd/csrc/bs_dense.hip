@@ -9,8 +9,9 @@
 // 1024 MACs per cycle and SIMD.  For compute-bound shapes the dense contraction therefore
 // belongs on MFMA; bit-serial keeps the bandwidth-bound shapes, where bytes scale with bits.
 //
-// Kernel shape.  A workgroup of four wavefronts (2 x 2) owns a BM x BN tile of C; each
-// wavefront owns WTM x WTN tiles of 32 x 32 accumulated with v_mfma_i32_32x32x32_i8.
+// Kernel shape.  A workgroup of four wavefronts (2 x 2) - eight (2 x 4) for the 256 x 256 tile of
+// the direct-to-LDS kernel - owns a BM x BN tile of C; each wavefront owns WTM x WTN tiles of
+// 32 x 32 accumulated with v_mfma_i32_32x32x32_i8.
 // Operands are depth-contiguous int8 rows; 64 bytes of depth per row and stage are
 // fetched global -> registers one stage ahead, then written to LDS with an 80-byte row
 // stride so that the 16-byte fragment reads of 32 consecutive rows spread over all banks.
@@ -86,13 +87,13 @@ __device__ __forceinline__ uint4 mask_tail(uint4 v, int k, int K)
 
 // Epilogue shared by the two dense kernels: int32 store, or successive thresholding with
 // the packed-plane output.  `lds` is the (no longer needed) operand space of the caller.
-template <int WTM, int WTN, bool FUSE, bool FP4>
+template <int WTM, int WTN, bool FUSE, bool FP4, int WGM = 2, int WGN = 2>
 __device__ __forceinline__ void dense_epilogue(const DenseParams &p, typename AccOf<FP4>::type (&acc)[WTM][WTN],
                                                unsigned char *lds, int m0, int n0, int tile_m)
 {
-    constexpr int BM = 64 * WTM;
+    constexpr int BM = 32 * WTM * WGM, NT = 64 * WGM * WGN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int li = lane & 31, lg = lane >> 5;
     (void)tile_m;
     if constexpr (!FUSE) {
@@ -112,7 +113,7 @@ __device__ __forceinline__ void dense_epilogue(const DenseParams &p, typename Ac
         // padded to 16 per row with INT_MAX (never reached) so that a row is four 16-byte reads
         __syncthreads();
         int4 *tl = reinterpret_cast<int4 *>(lds);  // [BM][4]
-        for (int it = tid; it < BM * 16; it += 256) {
+        for (int it = tid; it < BM * 16; it += NT) {
             const int r = it >> 4, t = it & 15;
             reinterpret_cast<int32_t *>(tl)[it] =
                 (m0 + r < p.M && t < p.T) ? p.thr[(long long)(m0 + r) * p.T + t] : 0x7fffffff;
@@ -346,19 +347,20 @@ dense_gemm_kernel(const DenseParams p)
 // multiple of 64 (no tail to mask); other depths use the register-staged kernel above.
 typedef __attribute__((address_space(3))) void lds_void;
 
-template <int WTM, int WTN, bool FUSE, bool FP4>
-__global__ void __launch_bounds__(256)
+template <int WTM, int WTN, bool FUSE, bool FP4, int WGM = 2, int WGN = 2>
+__global__ void __launch_bounds__(64 * WGM * WGN)
 dense_gemm_lds_kernel(const DenseParams p)
 {
-    constexpr int BM = 64 * WTM, BN = 64 * WTN;
+    constexpr int NBUF = 3;                      // stage i + NBUF - 1 is requested while stage i is consumed (4 measured: no gain)
+    constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
     constexpr int ROWS = BM + BN;
     constexpr int TILE = ROWS * DK;              // bytes per stage, rows unpadded
-    constexpr int LPW = ROWS / 16 / 4;           // load instructions per wavefront and stage (16 rows each)
-    constexpr int NBUF = 3;                      // stage i + NBUF - 1 is requested while stage i is consumed (4 measured: no gain)
+    constexpr int LPW = ROWS / 16 / (WGM * WGN); // load instructions per wavefront and stage (16 rows each)
+    static_assert(ROWS % (16 * WGM * WGN) == 0, "every wavefront issues the same number of loads");
     __shared__ __attribute__((aligned(16))) unsigned char lds[NBUF * TILE];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int li = lane & 31, lg = lane >> 5;
     const int tile_m = blockIdx.x / p.gx, tile_n = blockIdx.x % p.gx;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -466,7 +468,7 @@ dense_gemm_lds_kernel(const DenseParams p)
         cur = cur == NBUF - 1 ? 0 : cur + 1;
     }
 
-    dense_epilogue<WTM, WTN, FUSE, FP4>(p, acc, lds, m0, n0, tile_m);
+    dense_epilogue<WTM, WTN, FUSE, FP4, WGM, WGN>(p, acc, lds, m0, n0, tile_m);
 }
 
 // ------------------------------------------------------------------ unpack (planes -> int8)
@@ -523,8 +525,15 @@ bs_status launch_dense(DenseParams &p, bool fuse, hipStream_t st)
     const long long blocks = (long long)p.gx * p.gy;
     if (blocks >= (1LL << 31)) return BS_ERR_UNSUPPORTED;
     if (p.K % DK == 0) {  // no depth tail: operands can go straight from memory to LDS
-        if (fuse) dense_gemm_lds_kernel<WTM, WTN, true, FP4><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
-        else dense_gemm_lds_kernel<WTM, WTN, false, FP4><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+        if constexpr (WTM == 4) {
+            // the 256 x 256 tile on eight wavefronts of 128 x 64 (two per SIMD): while one waits at the stage
+            // barrier or for its fragments the other keeps the matrix pipe busy (8192^3 int8: 559 -> 452 us)
+            if (fuse) dense_gemm_lds_kernel<4, 2, true, FP4, 2, 4><<<dim3((unsigned)blocks), 512, 0, st>>>(p);
+            else dense_gemm_lds_kernel<4, 2, false, FP4, 2, 4><<<dim3((unsigned)blocks), 512, 0, st>>>(p);
+        } else {
+            if (fuse) dense_gemm_lds_kernel<WTM, WTN, true, FP4><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+            else dense_gemm_lds_kernel<WTM, WTN, false, FP4><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+        }
     } else {
         if (fuse) dense_gemm_kernel<WTM, WTN, true, FP4><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
         else dense_gemm_kernel<WTM, WTN, false, FP4><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
