@@ -516,29 +516,47 @@ unpack_kernel(const uint32_t *__restrict__ planes, int bits, long long rows, lon
     if (dw * 32 + 16 < ((depth + 15) / 16) * 16) *reinterpret_cast<uint4 *>(o + 16) = make_uint4(out[4], out[5], out[6], out[7]);
 }
 
-template <int WTM, int WTN, bool FP4>
+// Tile shapes: WTM x WTN MFMA tiles per wavefront, WGM x WGN wavefronts per workgroup.
+template <int WTM, int WTN, int WGM, int WGN, bool FP4>
 bs_status launch_dense(DenseParams &p, bool fuse, hipStream_t st)
 {
-    constexpr int BM = 64 * WTM, BN = 64 * WTN;
+    constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN, NT = 64 * WGM * WGN;
     p.gx = (p.N + BN - 1) / BN;
     p.gy = (p.M + BM - 1) / BM;
     const long long blocks = (long long)p.gx * p.gy;
     if (blocks >= (1LL << 31)) return BS_ERR_UNSUPPORTED;
+    // four wavefronts of 128 x 128 exist in the register-staged kernel only (the direct-to-LDS kernel runs that tile on eight)
+    constexpr bool DIRECT = !(WTM == 4 && WTN == 4);
     if (p.K % DK == 0) {  // no depth tail: operands can go straight from memory to LDS
-        if constexpr (WTM == 4) {
-            // the 256 x 256 tile on eight wavefronts of 128 x 64 (two per SIMD): while one waits at the stage
-            // barrier or for its fragments the other keeps the matrix pipe busy (8192^3 int8: 559 -> 452 us)
-            if (fuse) dense_gemm_lds_kernel<4, 2, true, FP4, 2, 4><<<dim3((unsigned)blocks), 512, 0, st>>>(p);
-            else dense_gemm_lds_kernel<4, 2, false, FP4, 2, 4><<<dim3((unsigned)blocks), 512, 0, st>>>(p);
-        } else {
-            if (fuse) dense_gemm_lds_kernel<WTM, WTN, true, FP4><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
-            else dense_gemm_lds_kernel<WTM, WTN, false, FP4><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+        if constexpr (DIRECT) {
+            if (fuse) dense_gemm_lds_kernel<WTM, WTN, true, FP4, WGM, WGN><<<dim3((unsigned)blocks), NT, 0, st>>>(p);
+            else dense_gemm_lds_kernel<WTM, WTN, false, FP4, WGM, WGN><<<dim3((unsigned)blocks), NT, 0, st>>>(p);
+            return bs::after_launch();
         }
-    } else {
+    }
+    if constexpr (WGM == 2 && WGN == 2) {  // the register-staged kernel is written for four wavefronts
         if (fuse) dense_gemm_kernel<WTM, WTN, true, FP4><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
         else dense_gemm_kernel<WTM, WTN, false, FP4><<<dim3((unsigned)blocks), 256, 0, st>>>(p);
+        return bs::after_launch();
     }
-    return bs::after_launch();
+    return BS_ERR_UNSUPPORTED;
+}
+
+// Largest tile that still gives every compute unit a workgroup.  With the direct-to-LDS kernel the two large tiles
+// run on eight wavefronts (two per SIMD: while one waits at the stage barrier or for its fragments the other keeps
+// the matrix pipe busy; 8192^3 int8: 559 -> 452 us, 8192 x 8192 x 1024: 104 -> 83 us); depths with a tail use the
+// register-staged kernel and its four-wavefront tiles.
+template <bool FP4>
+bs_status choose_tile(DenseParams &p, bool fuse, hipStream_t st)
+{
+    auto tiles = [&](int bm, int bn) { return (long long)((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn); };
+    if (p.K % DK == 0) {
+        if (tiles(256, 256) >= 256) return launch_dense<4, 2, 2, 4, FP4>(p, fuse, st);
+        if (tiles(128, 256) >= 256) return launch_dense<2, 2, 2, 4, FP4>(p, fuse, st);
+        return launch_dense<2, 2, 2, 2, FP4>(p, fuse, st);
+    }
+    if (tiles(256, 256) >= 256) return launch_dense<4, 4, 2, 2, FP4>(p, fuse, st);
+    return launch_dense<2, 2, 2, 2, FP4>(p, fuse, st);
 }
 
 // K counts depth indices; the operands hold one (int8) or half a (fp4) byte per index.
@@ -569,10 +587,7 @@ bs_status dense_common(const void *W, int64_t ldw, const void *At, int64_t lda, 
     p.Y = reinterpret_cast<uint32_t *>(Yp);
     p.Yd = (int)(2 * bs_words_per_row(M));
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // 256 x 256 tiles when they still give every compute unit work, else 128 x 128
-    const long long big = (long long)((M + 255) / 256) * ((N + 255) / 256);
-    if (big >= 256) return launch_dense<4, 4, FP4>(p, fuse, st);
-    return launch_dense<2, 2, FP4>(p, fuse, st);
+    return choose_tile<FP4>(p, fuse, st);
 }
 
 // ------------------------------------------------------------------ unpack (planes -> fp4 codes)

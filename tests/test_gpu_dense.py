@@ -101,3 +101,22 @@ def test_dense_engine_large_tiles_and_packed_route():
     y_bits = bs.bs_gemm_threshold(Wp, bs.BS_TWOS_COMPLEMENT, Ap, bs.BS_UNSIGNED, n, dev(thr), 2)
     assert_equal(planes_to_numpy(y_dense), oracle.threshold_pack(want, thr, 2), "dense fused")
     assert_equal(planes_to_numpy(y_bits), planes_to_numpy(y_dense), "engines agree")
+
+
+def test_dense_engines_middle_tile():
+    """4096 x 2304 outputs: too few 256 x 256 tiles for every compute unit, enough 128 x 256 ones (eight wavefronts);
+    int8 and fp4, int32 output and fused thresholds, ragged last tiles."""
+    rng = np.random.default_rng(77)
+    M, K, N = 4096 - 3, 128, 2304 - 5
+    W, A = draw(rng, (M, K), 2, TC), draw(rng, (K, N), 2, U)
+    want = oracle.gemm(W, A)
+    thr = workloads.thresholds(rng, M, 2, float(want.mean()), float(want.std()))
+    wantp = oracle.threshold_pack(want, thr, 2)
+    Wp = bs.bs_pack_planes(dev(W), 2, bs.BS_TWOS_COMPLEMENT)
+    Ap = bs.bs_pack_planes(dev(A), 2, bs.BS_UNSIGNED, depth_is_strided=True)
+    W8, A8 = bs.bs_unpack_planes(Wp, bs.BS_TWOS_COMPLEMENT, K), bs.bs_unpack_planes(Ap, bs.BS_UNSIGNED, K)
+    assert_equal(bs.bs_gemm_i8(W8, A8, K).cpu().numpy(), want, "int8, 128 x 256 tiles")
+    assert_equal(planes_to_numpy(bs.bs_gemm_i8_threshold(W8, A8, K, dev(thr), 2)), wantp, "int8 fused, 128 x 256 tiles")
+    W4, A4 = bs.bs_unpack_planes_fp4(Wp, bs.BS_TWOS_COMPLEMENT, K), bs.bs_unpack_planes_fp4(Ap, bs.BS_UNSIGNED, K)
+    assert_equal(bs.bs_gemm_fp4(W4, A4, K).cpu().numpy(), want, "fp4, 128 x 256 tiles")
+    assert_equal(planes_to_numpy(bs.bs_gemm_fp4_threshold(W4, A4, K, dev(thr), 2)), wantp, "fp4 fused, 128 x 256 tiles")
