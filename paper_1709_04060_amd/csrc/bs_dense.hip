@@ -135,13 +135,17 @@ __device__ __forceinline__ void dense_epilogue(const DenseParams &p, typename Ac
 #pragma unroll
                 for (int b = 0; b < WTN; ++b) y[b] = 0;
                 // one row's thresholds serve the WTN column tiles this lane holds
+                int c[WTN];
+#pragma unroll
+                for (int b = 0; b < WTN; ++b) c[b] = (int)acc[a][b][v];
                 for (int q = 0; q < nq; ++q) {
                     const int4 th = tl[(rbase + rr) * 4 + q];
+                    const int t4[4] = {th.x, th.y, th.z, th.w};
 #pragma unroll
-                    for (int b = 0; b < WTN; ++b) {
-                        const int c = (int)acc[a][b][v];
-                        y[b] += (uint32_t)(c >= th.x) + (uint32_t)(c >= th.y) + (uint32_t)(c >= th.z) + (uint32_t)(c >= th.w);
-                    }
+                    for (int b = 0; b < WTN; ++b)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)  // y += (c >= t): compare into the carry mask, add the carry
+                            asm("v_cmp_le_i32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, 0, %0, vcc" : "+v"(y[b]) : "v"(c[b]), "v"(t4[e]) : "vcc");
                 }
                 const bool live = m0 + rbase + rr < p.M;
 #pragma unroll
