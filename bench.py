@@ -301,8 +301,22 @@ def extras(bs, workloads, dev, timed):
                     "_out", torch.empty((2, 1, bs.bs_words_per_row(M)), dtype=torch.int64, device="cuda")))
         return cur
     ms = timed_graph([frame], 20)
+    # every layer alone on the input the chain gives it (Table 2's rows; lowering is inside the convolution kernels)
+    def one_layer(L, Wp, th, cur):
+        if L["kind"] == "conv":
+            H, W, C, F, k, s, p = L["geom"]
+            return lambda: bs.bs_conv_threshold(cur, U, H, W, C, Wp, BP, k, k, s, p, th, 2, out=L["_out"])
+        if L["kind"] == "pool":
+            H, W, C, k, s = L["geom"]
+            return lambda: bs.bs_maxpool_packed(cur, H, W, C, k, s, out=L["_out"])
+        return lambda: bs.bs_gemm_threshold(Wp, BP, cur.reshape(2, 1, -1), U, L["geom"][1], th, 2, out=L["_out"])
+    per_layer, cur = {}, x0
+    for L, Wp, th in prepared:
+        per_layer[L["name"]] = round(timed_graph([one_layer(L, Wp, th, cur)], 20) * 1e3, 2)
+        cur = L["_out"]
     out["alexnet_W1A2_layers_conv2_to_fc7_chain"] = {
         "us_per_frame": round(ms * 1e3, 2), "frames_per_s": round(1e3 / ms, 1), "kernels_per_frame": len(prepared),
+        "us_per_layer_alone": per_layer,
         "context": "the same layers (lowering + GEMM rows of Table 2, bsgemm-intl column) sum to 55.1 ms on the "
                    "paper's Cortex-A57 core; synthetic weights here"}
     # the dense (int8 MFMA) engine on the compute-bound configurations, beside the bit-serial
