@@ -267,6 +267,18 @@ def extras(bs, workloads, dev, timed):
     fused("W4A4_8192x8192x1_warm", 4, TC, 4, U, 8192, 1, 8192, 4, copies=1)
     for n in (64, 1024, 8192):
         fused("W4A4_8192x8192x%d" % n, 4, TC, 4, U, 8192, n, 8192, 4)
+    # compute-bound rate against precision (Sec. 4.1.1 of the paper lists W1A1, W1A2, W1A3, W2A2, W2A3): 4096^3,
+    # int32 output, unsigned activations, bipolar (1-bit) or two's-complement weights
+    sweep_p = {}
+    for (w_, a_) in [(1, 1), (1, 2), (1, 3), (2, 2), (2, 3), (3, 3), (4, 4)]:
+        Wq, Aq = planes(w_, 4096, 4096), planes(a_, 4096, 4096)
+        Cq = torch.empty((4096, 4096), dtype=torch.int32, device="cuda")
+        wf_ = BP if w_ == 1 else TC
+        ms, _ = timed(lambda: bs.bs_gemm(Wq, wf_, Aq, U, 4096, out=Cq), 10, 3)
+        gops = 2.0 * 4096 ** 3 / ms / 1e6
+        sweep_p["W%dA%d" % (w_, a_)] = {"us": round(ms * 1e3, 1), "GOPS": round(gops, 1), "GOPS_x_w_x_a": round(gops * w_ * a_, 1),
+                                        "frac_of_valu_popcount_peak": round(gops * w_ * a_ / 1e3 / BINARY_PEAK_TOPS, 4)}
+    out["precision_sweep_4096x4096x4096"] = sweep_p
     # a GEMV large enough that launch and first-byte latency stop mattering
     fused("W1A2_32768x32768x1_cold", 1, BP, 2, U, 32768, 1, 32768, 2, copies=3, reps=12)
     # the W1A2 layers of the paper's AlexNet (Table 2) as one packed chain, batch 1:
