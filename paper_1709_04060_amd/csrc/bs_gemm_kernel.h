@@ -19,7 +19,9 @@
 // touches fall in eight different bank groups.  A wavefront is an 8 x 8 grid of lanes,
 // each lane holding a TM x TN block of int32 accumulators; per 16-byte chunk it reads
 // TM weight rows and TN activation columns per plane from LDS and issues
-// v_and_b32 + v_bcnt_u32_b32 (whose add operand makes the accumulation free).
+// v_and_b32 + v_bcnt_u32_b32 (whose add operand makes the accumulation free), in the
+// AND / popcount / idle-slot rhythm that lets the two wavefronts of a SIMD interleave
+// (see mac_block).
 // Small output grids use 32 x 32 tiles whose four wavefronts split each stage's depth
 // among themselves (KS = 4) and add their partial sums in LDS, so that enough
 // wavefronts exist to fill 1024 SIMDs.
