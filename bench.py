@@ -330,6 +330,34 @@ def extras(bs, workloads, dev, timed):
         "us_per_layer_alone": per_layer,
         "context": "the same layers (lowering + GEMM rows of Table 2, bsgemm-intl column) sum to 55.1 ms on the "
                    "paper's Cortex-A57 core; synthetic weights here"}
+    # the same chain on a batch of images (columns = batch x pixels): throughput instead of latency
+    for Bn in (16, 64):
+        xb = torch.randint(0, 4, (Bn * H0 * W0, C0), dtype=torch.int8, device="cuda")
+        xbp = bs.bs_pack_planes(xb, 2, U)
+        bufs = {}
+
+        def frame_batch():
+            cur = xbp
+            for L, Wp, th in prepared:
+                key = (L["name"], Bn)
+                if L["kind"] == "conv":
+                    H, W, C, F, k, s, p = L["geom"]
+                    OHW = ((H + 2 * p - k) // s + 1) ** 2
+                    cur = bs.bs_conv_threshold_batch(cur, U, Bn, H, W, C, Wp, BP, k, k, s, p, th, 2, out=bufs.setdefault(
+                        key, torch.empty((2, Bn * OHW, bs.bs_words_per_row(F)), dtype=torch.int64, device="cuda")))
+                elif L["kind"] == "pool":
+                    H, W, C, k, s = L["geom"]
+                    OHW = ((H - k) // s + 1) ** 2
+                    cur = bs.bs_maxpool_packed_batch(cur, Bn, H, W, C, k, s, out=bufs.setdefault(
+                        key, torch.empty((2, Bn * OHW, bs.bs_words_per_row(C)), dtype=torch.int64, device="cuda")))
+                else:
+                    M, K = L["geom"]
+                    cur = bs.bs_gemm_threshold(Wp, BP, cur.reshape(2, Bn, -1), U, K, th, 2, out=bufs.setdefault(
+                        key, torch.empty((2, Bn, bs.bs_words_per_row(M)), dtype=torch.int64, device="cuda")))
+            return cur
+        msb = timed_graph([frame_batch], 10)
+        out["alexnet_W1A2_layers_conv2_to_fc7_chain_batch_%d" % Bn] = {
+            "us_per_batch": round(msb * 1e3, 2), "frames_per_s": round(Bn * 1e3 / msb, 1)}
     # the dense (int8 MFMA) engine on the compute-bound configurations, beside the bit-serial
     # numbers above: same logical product, operands unpacked to int8
     def dense(name, M, N, K, obits):

@@ -150,6 +150,10 @@ bs_status bs_gemm_threshold(const uint64_t *Wp, int wbits, bs_format wfmt,
  */
 bs_status bs_im2col_interleaved(const uint64_t *in, int abits, int H, int W, int C,
                                 int kh, int kw, int stride, int pad, uint64_t *out, void *stream);
+/* Batch of B images: in [abits][B][H][W][bs_words_per_row(C)], out [abits][B*OH*OW][bs_words_per_row(Kl)]
+ * (column = image * OH*OW + output pixel); everything else as bs_im2col_interleaved (B = 1). */
+bs_status bs_im2col_interleaved_batch(const uint64_t *in, int abits, int B, int H, int W, int C, int kh, int kw,
+                                      int stride, int pad, uint64_t *out, void *stream);
 
 /*
  * One quantized convolution layer on packed data, without materialising the lowered
@@ -171,6 +175,16 @@ bs_status bs_conv_threshold(const uint64_t *in, int abits, bs_format afmt, int H
                             int stride, int pad, const int32_t *thr, int obits, uint64_t *Yp, void *stream);
 
 /*
+ * The same layer for a batch of B images (N = batch x pixels, the columns of Sec. 3.2's lowered
+ * matrix for all images side by side): in device uint64_t [abits][B][H][W][bs_words_per_row(C)],
+ * Yp device uint64_t [obits][B][OH*OW][bs_words_per_row(F)]; everything else as bs_conv_threshold,
+ * which is the case B = 1.
+ */
+bs_status bs_conv_threshold_batch(const uint64_t *in, int abits, bs_format afmt, int B, int H, int W, int C,
+                                  const uint64_t *Fp, int wbits, bs_format wfmt, int F, int kh, int kw,
+                                  int stride, int pad, const int32_t *thr, int obits, uint64_t *Yp, void *stream);
+
+/*
  * Max pooling of a few-bit feature map held as packed HWC planes (unsigned codes).  Not a
  * step of the paper's hot path (pooling is one of its "other layers", Sec. 4.2); provided so
  * that the quantized layers of Table 2 chain without unpacking.  Exact because thresholding
@@ -181,6 +195,9 @@ bs_status bs_conv_threshold(const uint64_t *in, int abits, bs_format afmt, int H
  */
 bs_status bs_maxpool_packed(const uint64_t *in, int bits, int H, int W, int C, int k, int stride,
                             uint64_t *out, void *stream);
+/* Batch of B maps: in [bits][B][H][W][bs_words_per_row(C)], out [bits][B][OH][OW][bs_words_per_row(C)]. */
+bs_status bs_maxpool_packed_batch(const uint64_t *in, int bits, int B, int H, int W, int C, int k, int stride,
+                                  uint64_t *out, void *stream);
 
 /*
  * Dense engine.  The paper configures each quantized layer to run on either its

@@ -23,7 +23,8 @@ BS_UNSIGNED, BS_TWOS_COMPLEMENT, BS_BIPOLAR = 0, 1, 2
 BS_I8, BS_I32 = 0, 1
 
 EXPORTS = ("bs_words_per_row", "bs_lowered_depth", "bs_pack_planes", "bs_gemm", "bs_gemm_topbits", "bs_threshold_activate",
-           "bs_gemm_threshold", "bs_im2col_interleaved", "bs_conv_threshold", "bs_maxpool_packed",
+           "bs_gemm_threshold", "bs_im2col_interleaved", "bs_im2col_interleaved_batch", "bs_conv_threshold", "bs_conv_threshold_batch", "bs_maxpool_packed",
+           "bs_maxpool_packed_batch",
            "bs_unpack_planes", "bs_gemm_i8", "bs_gemm_i8_threshold", "bs_unpack_planes_fp4", "bs_gemm_fp4",
            "bs_gemm_fp4_threshold", "bs_streamline_collapse",
            "bs_streamline_thresholds", "bs_choose_engine", "bs_probe_popcount_rate", "bs_status_string", "bs_version")
@@ -60,6 +61,13 @@ def load_library() -> ctypes.CDLL:
     lib.bs_im2col_interleaved.restype = i32
     lib.bs_conv_threshold.argtypes = [vp, i32, i32, i32, i32, i32, vp, i32, i32, i32, i32, i32, i32, i32, vp, i32, vp, vp]
     lib.bs_conv_threshold.restype = i32
+    lib.bs_im2col_interleaved_batch.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.bs_im2col_interleaved_batch.restype = i32
+    lib.bs_conv_threshold_batch.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, i32, i32, i32, i32, i32, i32, i32, vp, i32,
+                                            vp, vp]
+    lib.bs_conv_threshold_batch.restype = i32
+    lib.bs_maxpool_packed_batch.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.bs_maxpool_packed_batch.restype = i32
     lib.bs_maxpool_packed.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp]; lib.bs_maxpool_packed.restype = i32
     lib.bs_unpack_planes.argtypes = [vp, i32, i32, i64, i64, vp, i64, vp]; lib.bs_unpack_planes.restype = i32
     lib.bs_gemm_i8.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i64, vp]; lib.bs_gemm_i8.restype = i32
@@ -185,6 +193,20 @@ def bs_im2col_interleaved(x: torch.Tensor, H: int, W: int, C: int, kh: int, kw: 
     return out
 
 
+def bs_im2col_interleaved_batch(x: torch.Tensor, B: int, H: int, W: int, C: int, kh: int, kw: int, stride: int, pad: int,
+                                out: torch.Tensor | None = None) -> torch.Tensor:
+    """Lower B packed HWC maps x [abits][B*H*W][S_C] to packed columns [abits][B*OH*OW][S_Kl]."""
+    abits = x.shape[0]
+    OH = (H + 2 * pad - kh) // stride + 1
+    OW = (W + 2 * pad - kw) // stride + 1
+    if out is None:
+        out = _planes(abits, B * OH * OW, bs_lowered_depth(C, kh, kw), x.device)
+    st = load_library().bs_im2col_interleaved_batch(_dev(x, "x"), abits, B, H, W, C, kh, kw, stride, pad,
+                                                    _dev(out, "out"), _stream())
+    _check(st, "bs_im2col_interleaved_batch")
+    return out
+
+
 def bs_conv_threshold(x: torch.Tensor, afmt: int, H: int, W: int, C: int, Fp: torch.Tensor, wfmt: int,
                       kh: int, kw: int, stride: int, pad: int, thr: torch.Tensor, obits: int,
                       out: torch.Tensor | None = None) -> torch.Tensor:
@@ -199,6 +221,34 @@ def bs_conv_threshold(x: torch.Tensor, afmt: int, H: int, W: int, C: int, Fp: to
     st = load_library().bs_conv_threshold(_dev(x, "x"), abits, afmt, H, W, C, _dev(Fp, "Fp"), wbits, wfmt, F,
                                           kh, kw, stride, pad, _dev(thr, "thr"), obits, _dev(out, "out"), _stream())
     _check(st, "bs_conv_threshold")
+    return out
+
+
+def bs_conv_threshold_batch(x: torch.Tensor, afmt: int, B: int, H: int, W: int, C: int, Fp: torch.Tensor, wfmt: int,
+                            kh: int, kw: int, stride: int, pad: int, thr: torch.Tensor, obits: int,
+                            out: torch.Tensor | None = None) -> torch.Tensor:
+    """bs_conv_threshold for B images: x [abits][B*H*W][S_C] -> [obits][B*OH*OW][S_F]."""
+    abits = x.shape[0]
+    wbits, F, _ = Fp.shape
+    OH = (H + 2 * pad - kh) // stride + 1
+    OW = (W + 2 * pad - kw) // stride + 1
+    if out is None:
+        out = _planes(obits, B * OH * OW, F, x.device)
+    st = load_library().bs_conv_threshold_batch(_dev(x, "x"), abits, afmt, B, H, W, C, _dev(Fp, "Fp"), wbits, wfmt, F,
+                                                kh, kw, stride, pad, _dev(thr, "thr"), obits, _dev(out, "out"), _stream())
+    _check(st, "bs_conv_threshold_batch")
+    return out
+
+
+def bs_maxpool_packed_batch(x: torch.Tensor, B: int, H: int, W: int, C: int, k: int, stride: int,
+                            out: torch.Tensor | None = None) -> torch.Tensor:
+    """Max pooling of B packed HWC maps x [bits][B*H*W][S_C] -> [bits][B*OH*OW][S_C]."""
+    bits = x.shape[0]
+    OH, OW = (H - k) // stride + 1, (W - k) // stride + 1
+    if out is None:
+        out = _planes(bits, B * OH * OW, C, x.device)
+    st = load_library().bs_maxpool_packed_batch(_dev(x, "x"), bits, B, H, W, C, k, stride, _dev(out, "out"), _stream())
+    _check(st, "bs_maxpool_packed_batch")
     return out
 
 

@@ -105,12 +105,13 @@ extern "C" bs_status bs_gemm_threshold(const uint64_t *Wp, int wbits, bs_format 
     return gemm_common(Wp, wbits, wfmt, Ap, abits, afmt, M, N, K, nullptr, 0, thr, obits, Yp, true, stream);
 }
 
-extern "C" bs_status bs_conv_threshold(const uint64_t *in, int abits, bs_format afmt, int H, int W, int C,
-                                       const uint64_t *Fp, int wbits, bs_format wfmt, int F, int kh, int kw,
-                                       int stride, int pad, const int32_t *thr, int obits, uint64_t *Yp, void *stream)
+extern "C" bs_status bs_conv_threshold_batch(const uint64_t *in, int abits, bs_format afmt, int B, int H, int W, int C,
+                                             const uint64_t *Fp, int wbits, bs_format wfmt, int F, int kh, int kw,
+                                             int stride, int pad, const int32_t *thr, int obits, uint64_t *Yp,
+                                             void *stream)
 {
-    if (!in || !Fp || !thr || !Yp || H <= 0 || W <= 0 || C <= 0 || F <= 0 || kh <= 0 || kw <= 0 || stride <= 0 ||
-        pad < 0 || obits < 1)
+    if (!in || !Fp || !thr || !Yp || B <= 0 || H <= 0 || W <= 0 || C <= 0 || F <= 0 || kh <= 0 || kw <= 0 ||
+        stride <= 0 || pad < 0 || obits < 1)
         return BS_ERR_INVALID_ARG;
     if (bs_status s = bs::check_bits_fmt(wbits, wfmt)) return s;
     if (bs_status s = bs::check_bits_fmt(abits, afmt)) return s;
@@ -123,12 +124,13 @@ extern "C" bs_status bs_conv_threshold(const uint64_t *in, int abits, bs_format 
     const int64_t Kl = bs_lowered_depth(C, kh, kw);
     const int64_t S = bs_words_per_row(Kl);
     const int OH = (H + 2 * pad - kh) / stride + 1, OW = (W + 2 * pad - kw) / stride + 1;
-    const int64_t N = (int64_t)OH * OW;
+    const int64_t N = (int64_t)B * OH * OW;
     if (2 * S > kConvMaxLut || kh > 127 || kw > 127) return BS_ERR_UNSUPPORTED;
     if ((Kl << (wbits + abits)) >= (int64_t(1) << 31)) return BS_ERR_OVERFLOW_RISK;
     const int64_t lim = int64_t(1) << 31;
     const int64_t pix = 2 * bs_words_per_row(C);
-    if (wbits * (int64_t)F * S * 2 >= lim || abits * (int64_t)H * W * pix >= lim || N >= lim) return BS_ERR_OVERFLOW_RISK;
+    if (wbits * (int64_t)F * S * 2 >= lim || abits * (int64_t)B * H * W * pix >= lim || N >= lim)
+        return BS_ERR_OVERFLOW_RISK;
 
     GemmParams g{};
     g.W = reinterpret_cast<const uint32_t *>(Fp);
@@ -140,9 +142,17 @@ extern "C" bs_status bs_conv_threshold(const uint64_t *in, int abits, bs_format 
     g.Y = reinterpret_cast<uint32_t *>(Yp);
     g.Yd = (int)(2 * bs_words_per_row(F));
     g.cH = H; g.cW = W; g.cCd = (C + 31) / 32; g.cPix = (int)pix; g.cKW = kw;
-    g.cStride = stride; g.cPad = pad; g.cOW = OW; g.cKused = (int)(Kl / 32);
+    g.cStride = stride; g.cPad = pad; g.cOW = OW; g.cOHW = OH * OW; g.cB = B; g.cKused = (int)(Kl / 32);
     const bool corr = (wfmt == BS_BIPOLAR);
     return dispatch_wb(g, wbits, abits, true, corr, true, false, static_cast<hipStream_t>(stream));
+}
+
+extern "C" bs_status bs_conv_threshold(const uint64_t *in, int abits, bs_format afmt, int H, int W, int C,
+                                       const uint64_t *Fp, int wbits, bs_format wfmt, int F, int kh, int kw,
+                                       int stride, int pad, const int32_t *thr, int obits, uint64_t *Yp, void *stream)
+{
+    return bs_conv_threshold_batch(in, abits, afmt, 1, H, W, C, Fp, wbits, wfmt, F, kh, kw, stride, pad, thr, obits, Yp,
+                                   stream);
 }
 
 extern "C" bs_status bs_gemm_topbits(const uint64_t *Wp, int wbits, bs_format wfmt, const uint64_t *Ap, int abits,

@@ -63,7 +63,9 @@ struct GemmParams {
     int cPix;           // 32-bit words between pixels
     int cKW;            // kernel width (taps per kernel row)
     int cStride, cPad;
-    int cOW;            // output width (columns n = oh * cOW + ow)
+    int cOW;            // output width
+    int cOHW;           // output pixels per image (columns n = (b * cOHW) + oh * cOW + ow)
+    int cB;             // images in the batch
     int cKused;         // dwords of a lowered column that carry data: kh * kw * cCd
     // single-column kernel: read the weights with the non-temporal hint (set for large weight sets)
     int stream_weights;
@@ -253,10 +255,11 @@ bs_gemm_kernel(const GemmParams p)
                 loff[s] = srow * KCH + (c ^ ((r / TN) & 7));
                 if (n0 + r < p.N) {
                     if constexpr (CONV) {
-                        const int oh = (n0 + r) / p.cOW, ow = (n0 + r) - oh * p.cOW;
+                        const int b = (n0 + r) / p.cOHW, opix = (n0 + r) - b * p.cOHW;
+                        const int oh = opix / p.cOW, ow = opix - oh * p.cOW;
                         pix_h[s] = oh * p.cStride - p.cPad;
                         pix_w[s] = ow * p.cStride - p.cPad;
-                        goff[s] = pl * p.cH * p.cW * p.cPix;  // plane base
+                        goff[s] = (pl * p.cB + b) * p.cH * p.cW * p.cPix;  // base of image b in plane pl
                     } else {
                         goff[s] = (pl * p.N + n0 + r) * p.Kd + c * 4;
                     }

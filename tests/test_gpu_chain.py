@@ -108,3 +108,35 @@ def test_alexnet_inner_chain(scale):
             ref = oracle.threshold(Cmat, L["thr"]).astype(np.int8)
         assert_equal(planes_to_numpy(cur), want, "chain after %s" % L["name"])
         assert len(np.unique(ref)) >= 3, "degenerate activations after %s" % L["name"]
+
+
+@pytest.mark.parametrize("B,H,W,C,F,k,s,p", [(3, 9, 9, 32, 70, 3, 1, 1), (5, 13, 13, 40, 33, 3, 2, 0), (2, 27, 27, 96, 256, 5, 1, 2),
+                                             (40, 8, 7, 130, 64, 1, 1, 0), (64, 13, 13, 64, 96, 3, 1, 1)])
+@pytest.mark.parametrize("w,wf,a,af,obits", [(1, BP, 2, U, 2), (2, TC, 2, U, 2), (4, TC, 3, TC, 4)])
+def test_conv_and_pool_on_a_batch(B, H, W, C, F, k, s, p, w, wf, a, af, obits):
+    """B images side by side in the column dimension: every image's output equals the oracle's direct convolution of
+    that image, and pooling the batch equals pooling each map.  (64, 13, 13) gives enough columns for 64 x 64 tiles."""
+    rng = np.random.default_rng(B * 1000 + H * W + C + F + w + a)
+    x = draw(rng, (B, H, W, C), a, af)
+    filt = draw(rng, (F, k, k, C), w, wf)
+    convs = [oracle.conv_direct(x[b], filt, s, p) for b in range(B)]
+    lo, hi = min(int(c.min()) for c in convs), max(int(c.max()) for c in convs)
+    T = (1 << obits) - 1
+    thr = np.sort(rng.integers(lo - 2, hi + 3, size=(F, T)), axis=1).astype(np.int32)
+    OH, OW, _ = convs[0].shape
+    want = np.concatenate([oracle.threshold_pack(c.reshape(OH * OW, F).T.copy(), thr, obits) for c in convs], axis=1)
+    Cp = 32 * ((C + 31) // 32)
+    xp = bs.bs_pack_planes(dev(x.reshape(B * H * W, C)), a, FMT[af])
+    Fp = bs.bs_pack_planes(dev(pad_last(filt, Cp).reshape(F, -1)), w, FMT[wf])
+    out = torch.full((obits, B * OH * OW, bs.bs_words_per_row(F)), -1, dtype=torch.int64, device="cuda")
+    bs.bs_conv_threshold_batch(xp, FMT[af], B, H, W, C, Fp, FMT[wf], k, k, s, p, dev(thr), obits, out=out)
+    assert_equal(planes_to_numpy(out), want, "conv_threshold_batch")
+    # the two-call route on the batch: lowered columns of all images side by side, then the plain GEMM
+    low = bs.bs_im2col_interleaved_batch(xp, B, H, W, C, k, k, s, p)
+    two = bs.bs_gemm_threshold(Fp, FMT[wf], low, FMT[af], bs.bs_lowered_depth(C, k, k), dev(thr), obits)
+    assert_equal(planes_to_numpy(two), want, "im2col_batch + gemm_threshold")
+    if min(OH, OW) >= 2:
+        Y = [oracle.threshold(c.reshape(OH * OW, F).T.copy(), thr).T.reshape(OH, OW, F) for c in convs]
+        wantp = np.concatenate([oracle.pack(oracle.maxpool(y, 2, 2).reshape(-1, F), obits, U) for y in Y], axis=1)
+        pooled = bs.bs_maxpool_packed_batch(out, B, OH, OW, F, 2, 2)
+        assert_equal(planes_to_numpy(pooled), wantp, "maxpool_packed_batch")
