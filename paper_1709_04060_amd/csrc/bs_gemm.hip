@@ -143,6 +143,7 @@ extern "C" bs_status bs_conv_threshold_batch(const uint64_t *in, int abits, bs_f
     g.Yd = (int)(2 * bs_words_per_row(F));
     g.cH = H; g.cW = W; g.cCd = (C + 31) / 32; g.cPix = (int)pix; g.cKW = kw;
     g.cStride = stride; g.cPad = pad; g.cOW = OW; g.cOHW = OH * OW; g.cB = B; g.cKused = (int)(Kl / 32);
+    g.cVec = (g.cCd % 4 == 0 && g.cPix % 4 == 0) ? 1 : 0;
     const bool corr = (wfmt == BS_BIPOLAR);
     return dispatch_wb(g, wbits, abits, true, corr, true, false, static_cast<hipStream_t>(stream));
 }

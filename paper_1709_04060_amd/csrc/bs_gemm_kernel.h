@@ -32,6 +32,7 @@
 // activation columns through its L2.
 #pragma once
 #include "bs_common.h"
+#include <type_traits>
 
 namespace bs {
 
@@ -67,6 +68,7 @@ struct GemmParams {
     int cOHW;           // output pixels per image (columns n = (b * cOHW) + oh * cOW + ow)
     int cB;             // images in the batch
     int cKused;         // dwords of a lowered column that carry data: kh * kw * cCd
+    int cVec;           // 1 if cCd and cPix are multiples of 4: a 16-byte chunk never straddles two taps
     // single-column kernel: read the weights with the non-temporal hint (set for large weight sets)
     int stream_weights;
 };
@@ -306,16 +308,25 @@ bs_gemm_kernel(const GemmParams p)
                 if (goff[s] >= 0 && k0 + c * 4 < p.Kd)
                     v = *reinterpret_cast<const uint4 *>(p.A + (size_t)(unsigned)goff[s] + k0);
             } else {
-                const int l[4] = {tap4[s].x, tap4[s].y, tap4[s].z, tap4[s].w};
-                uint32_t e[4];
+                if (p.cVec) {
+                    // the chunk lies inside one tap of one pixel: one test, one 16-byte load
+                    const int l0 = tap4[s].x;
+                    const int ih = pix_h[s] + (l0 >> 24), iw = pix_w[s] + ((l0 >> 16) & 0xFF);
+                    if (l0 >= 0 && ih >= 0 && ih < p.cH && iw >= 0 && iw < p.cW)
+                        v = *reinterpret_cast<const uint4 *>(p.A + (size_t)(unsigned)goff[s] +
+                                                             (size_t)(ih * p.cW + iw) * p.cPix + (l0 & 0xFFFF));
+                } else {
+                    const int l[4] = {tap4[s].x, tap4[s].y, tap4[s].z, tap4[s].w};
+                    uint32_t e[4];
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    e[t] = 0;
-                    const int ih = pix_h[s] + (l[t] >> 24), iw = pix_w[s] + ((l[t] >> 16) & 0xFF);
-                    if (l[t] >= 0 && ih >= 0 && ih < p.cH && iw >= 0 && iw < p.cW)
-                        e[t] = p.A[(size_t)(unsigned)goff[s] + (size_t)(ih * p.cW + iw) * p.cPix + (l[t] & 0xFFFF)];
+                    for (int t = 0; t < 4; ++t) {
+                        e[t] = 0;
+                        const int ih = pix_h[s] + (l[t] >> 24), iw = pix_w[s] + ((l[t] >> 16) & 0xFF);
+                        if (l[t] >= 0 && ih >= 0 && ih < p.cH && iw >= 0 && iw < p.cW)
+                            e[t] = p.A[(size_t)(unsigned)goff[s] + (size_t)(ih * p.cW + iw) * p.cPix + (l[t] & 0xFFFF)];
+                    }
+                    v = make_uint4(e[0], e[1], e[2], e[3]);
                 }
-                v = make_uint4(e[0], e[1], e[2], e[3]);
             }
             stage[s] = v;
         }
@@ -342,7 +353,13 @@ bs_gemm_kernel(const GemmParams p)
             thr_s[i] = (m0 + r < p.M) ? p.thr[(long long)(m0 + r) * p.T + (i - r * p.T)] : 0x7fffffff;
         }
     }
-    for (int k0 = 0; k0 < p.Kd; k0 += KT) {
+    // One stage: registers -> LDS, start the next stage's loads, then the products.
+    // FULL stages run the chunk loop unrolled; the last stage of a depth that is no
+    // multiple of the stage holds zero-filled chunks past the depth and runs, after
+    // the loop, a rolled copy that stops at the depth (nq chunks hold data).
+    auto run_stage = [&](const int k0, auto full_c) {
+        constexpr bool FULL = decltype(full_c)::value;
+        const int nq = FULL ? KCH : (p.Kd - k0 + 3) >> 2;
         __syncthreads();  // everyone is done reading the previous stage
 #pragma unroll
         for (int s = 0; s < CPT; ++s) {
@@ -350,13 +367,10 @@ bs_gemm_kernel(const GemmParams p)
             if (CORR) cnt[s] += popc4(stage[s]);
         }
         __syncthreads();
-        if (k0 + KT < p.Kd) fetch(k0 + KT);
+        if (FULL && k0 + KT < p.Kd) fetch(k0 + KT);
 
         if constexpr (PER_PAIR) {
-#pragma unroll
-            for (int qq = 0; qq < KCH / KS; ++qq) {
-                const int q = qq * KS + ks;
-                if (KT > kStageDwords && k0 + q * 4 >= p.Kd) continue;  // deep stages: skip chunks past the depth
+            auto chunk = [&](const int q) {
                 uint4 w[WB][TM], a[AB][TN];
 #pragma unroll
                 for (int i = 0; i < WB; ++i)
@@ -370,6 +384,13 @@ bs_gemm_kernel(const GemmParams p)
                 for (int i = 0; i < WB; ++i)
 #pragma unroll
                     for (int j = 0; j < AB; ++j) mac_block<XOR, IDLE, TM, TN>(w[i], a[j], acc[i * AB + j]);
+            };
+            if constexpr (FULL) {
+#pragma unroll
+                for (int qq = 0; qq < KCH / KS; ++qq) chunk(qq * KS + ks);
+            } else {
+#pragma unroll 1
+                for (int q = ks; q < nq; q += KS) chunk(q);
             }
         } else {
             // Many plane pairs: one pair at a time over the whole stage into a small
@@ -384,16 +405,20 @@ bs_gemm_kernel(const GemmParams p)
                     for (int r = 0; r < TM; ++r)
 #pragma unroll
                         for (int c = 0; c < TN; ++c) t[r][c] = 0;
-#pragma unroll
-                    for (int qq = 0; qq < KCH / KS; ++qq) {
-                        const int q = qq * KS + ks;
-                        if (KT > kStageDwords && k0 + q * 4 >= p.Kd) continue;
+                    auto chunk = [&](const int q) {
                         uint4 w[TM], a[TN];
 #pragma unroll
                         for (int r = 0; r < TM; ++r) w[r] = ldsW[(i * BM + r) * KCH + (q ^ ly)];
 #pragma unroll
                         for (int c = 0; c < TN; ++c) a[c] = ldsA[(j * BN + c) * KCH + (q ^ lx)];
                         mac_block<false, IDLE, TM, TN>(w, a, t);
+                    };
+                    if constexpr (FULL) {
+#pragma unroll
+                        for (int qq = 0; qq < KCH / KS; ++qq) chunk(qq * KS + ks);
+                    } else {
+#pragma unroll 1
+                        for (int q = ks; q < nq; q += KS) chunk(q);
                     }
                     const int cf = p.coef[i * 4 + j];
 #pragma unroll
@@ -403,7 +428,10 @@ bs_gemm_kernel(const GemmParams p)
                 }
             }
         }
-    }
+    };
+    const int Kfull = p.Kd - p.Kd % KT;
+    for (int k0 = 0; k0 < Kfull; k0 += KT) run_stage(k0, std::true_type{});
+    if (Kfull < p.Kd) run_stage(Kfull, std::false_type{});
 
     // ---- correction terms (bipolar operands): weighted row popcounts via LDS atomics ----
     if (CORR) {
