@@ -37,6 +37,7 @@
 namespace bs {
 
 constexpr int kStageDwords = 32;  // dwords of depth per packed row and stage
+constexpr long long kNarrowMaxTiles32 = 200;  // measured, W1A2..W4A4 at depth 2048: 32 x 8 tiles win up to 184 tiles of 32 x 32, tie at 256, lose from 512
 constexpr long long kIdleMinBlocks = 257;  // more workgroups than compute units (measured: 10.9 vs 12.5 us at 320, 10.7 vs 9.6 us at 256)
 
 struct GemmParams {
@@ -652,7 +653,10 @@ bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, bo
     // The inner loop's idle-slot rhythm pays when at least two wavefronts share a SIMD.  The small-grid
     // configuration (one wavefront per SIMD and workgroup) gets there only with more workgroups than
     // the chip has compute units.
-    if constexpr (KS > 1) {
+    if constexpr (KS > 1 && TN == 1) {
+        // narrow tiles exist for grids of a few workgroups per compute unit at most
+        return launch_variant<WB, AB, TM, TN, WM, WN, KS, KT, false>(g, grid, fuse, corr, conv, xr, st);
+    } else if constexpr (KS > 1) {
         if (blocks < kIdleMinBlocks) return launch_variant<WB, AB, TM, TN, WM, WN, KS, KT, false>(g, grid, fuse, corr, conv, xr, st);
     }
     return launch_variant<WB, AB, TM, TN, WM, WN, KS, KT, true>(g, grid, fuse, corr, conv, xr, st);
@@ -662,9 +666,13 @@ template <int WB, int AB>
 bs_status launch_planes(const GemmParams &g, bool fuse, bool corr, bool conv, bool xr, hipStream_t st)
 {
     // Large grids: 64 x 64 tiles, four wavefronts side by side.  Small grids: 32 x 32
-    // tiles whose four wavefronts split the depth, so that more wavefronts exist.
+    // tiles whose four wavefronts split the depth, so that more wavefronts exist.  Tiny
+    // grids (AlexNet's conv3..conv5 at batch 1: 72 tiles of 32 x 32 on 256 compute units):
+    // 32 rows x 8 columns, four times as many workgroups, each with a quarter of the products.
     const long long tiles64 = (long long)((g.M + 63) / 64) * ((g.N + 63) / 64);
+    const long long tiles32 = (long long)((g.M + 31) / 32) * ((g.N + 31) / 32);
     constexpr int KT_SMALL = kStageDwords;  // deeper stages were measured and bring nothing: the stage count is not what bounds small grids
+    if (tiles32 <= kNarrowMaxTiles32) return launch_cfg<WB, AB, 4, 1, 1, 1, 4, KT_SMALL>(g, fuse, corr, conv, xr, st);
     if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4, KT_SMALL>(g, fuse, corr, conv, xr, st);
     return launch_cfg<WB, AB, 4, 4, 2, 2, 1, kStageDwords>(g, fuse, corr, conv, xr, st);
 }

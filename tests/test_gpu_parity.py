@@ -217,7 +217,9 @@ def test_threshold_activate(M, N, obits):
     assert_equal(planes_to_numpy(out), oracle.threshold_pack(C, thr, obits), "threshold")
 
 
-@pytest.mark.parametrize("M,K,N", [(1, 64, 1), (64, 256, 64), (70, 1100, 45), (200, 700, 130), (260, 300, 3)])
+# tiny grids take 32 x 8 tiles, (530, 1100, 610) the 32 x 32 ones, (1500, 700, 1480) the 64 x 64 ones
+@pytest.mark.parametrize("M,K,N", [(1, 64, 1), (64, 256, 64), (70, 1100, 45), (200, 700, 130), (260, 300, 3), (530, 1100, 610),
+                                   (1500, 700, 1480)])
 @pytest.mark.parametrize("w,wf,a,af,obits", [(1, BP, 2, U, 2), (2, TC, 2, U, 2), (4, TC, 4, U, 4), (1, BP, 1, BP, 1),
                                              (2, U, 3, TC, 3)])
 def test_gemm_threshold_fused(M, K, N, w, wf, a, af, obits):
