@@ -358,6 +358,54 @@ def extras(bs, workloads, dev, timed):
         msb = timed_graph([frame_batch], 10)
         out["alexnet_W1A2_layers_conv2_to_fc7_chain_batch_%d" % Bn] = {
             "us_per_batch": round(msb * 1e3, 2), "frames_per_s": round(Bn * 1e3 / msb, 1)}
+        # the paper's per-layer choice of the execution method (Sec. 4.2), made by bs_choose_engine: layers it
+        # gives to the fp4 matrix-core engine run as lowering -> planes to E2M1 codes -> dense GEMM + thresholds
+        picks, wd = {}, {}
+        for L, Wp, th in prepared:
+            if L["kind"] == "pool":
+                continue
+            if L["kind"] == "conv":
+                H, W, C, F, k, s, p = L["geom"]
+                Mx, Nx, Kx = F, Bn * ((H + 2 * p - k) // s + 1) ** 2, bs.bs_lowered_depth(C, k, k)
+            else:
+                (Mx, Kx), Nx = L["geom"], Bn
+            picks[L["name"]] = bs.bs_choose_engine(1, BP, 2, U, Mx, Nx, Kx)
+            if picks[L["name"]] == bs.BS_ENGINE_DENSE_FP4:
+                wd[L["name"]] = bs.bs_unpack_planes_fp4(Wp, BP, Kx)
+        if any(v == bs.BS_ENGINE_DENSE_FP4 for v in picks.values()):
+            def frame_choice():
+                cur = xbp
+                for L, Wp, th in prepared:
+                    key = (L["name"], Bn)
+                    if L["kind"] == "pool":
+                        H, W, C, k, s = L["geom"]
+                        cur = bs.bs_maxpool_packed_batch(cur, Bn, H, W, C, k, s, out=bufs[key])
+                    elif picks[L["name"]] != bs.BS_ENGINE_DENSE_FP4:
+                        if L["kind"] == "conv":
+                            H, W, C, F, k, s, p = L["geom"]
+                            cur = bs.bs_conv_threshold_batch(cur, U, Bn, H, W, C, Wp, BP, k, k, s, p, th, 2, out=bufs[key])
+                        else:
+                            cur = bs.bs_gemm_threshold(Wp, BP, cur.reshape(2, Bn, -1), U, L["geom"][1], th, 2, out=bufs[key])
+                    else:
+                        if L["kind"] == "conv":
+                            H, W, C, F, k, s, p = L["geom"]
+                            Kx = bs.bs_lowered_depth(C, k, k)
+                            OHW = ((H + 2 * p - k) // s + 1) ** 2
+                            cols = bs.bs_im2col_interleaved_batch(cur, Bn, H, W, C, k, k, s, p, out=bufs.setdefault(
+                                key + ("low",), torch.empty((2, Bn * OHW, bs.bs_words_per_row(Kx)), dtype=torch.int64, device="cuda")))
+                        else:
+                            Kx, cols = L["geom"][1], cur.reshape(2, Bn, -1)
+                        codes = bs.bs_unpack_planes_fp4(cols, U, Kx, out=bufs.setdefault(
+                            key + ("fp4",), torch.empty((cols.shape[1], 16 * ((Kx + 31) // 32)), dtype=torch.uint8, device="cuda")))
+                        cur = bs.bs_gemm_fp4_threshold(wd[L["name"]], codes, Kx, th, 2, out=bufs[key])
+                return cur
+            want = frame_batch().clone()
+            same = bool((frame_choice() == want).all())
+            msc = timed_graph([frame_choice], 10)
+            names = {bs.BS_ENGINE_BITSERIAL: "bitserial", bs.BS_ENGINE_DENSE_I8: "dense_int8", bs.BS_ENGINE_DENSE_FP4: "dense_fp4"}
+            out["alexnet_W1A2_layers_conv2_to_fc7_chain_batch_%d" % Bn]["with_engine_choice"] = {
+                "us_per_batch": round(msc * 1e3, 2), "frames_per_s": round(Bn * 1e3 / msc, 1),
+                "engine": {k: names[v] for k, v in picks.items()}, "same_output_as_bitserial_chain": same}
     # the dense (int8 MFMA) engine on the compute-bound configurations, beside the bit-serial
     # numbers above: same logical product, operands unpacked to int8
     def dense(name, M, N, K, obits):

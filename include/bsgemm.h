@@ -281,10 +281,10 @@ bs_status bs_streamline_thresholds(const double *t, int T, const double *a, cons
  *                        (only when both operands have at most 2 bits or are 3-bit two's complement),
  * whichever is fastest under a time model fitted to measurements on MI355X (microseconds, p = wbits * abits,
  * k = K / 1024, activation unpack and the thresholding epilogue included):
- *   bit-serial  5.2 + 0.475 k p + 2MNK p / 1.23e9      (N > 16)
+ *   bit-serial  4.8 + 0.21 k p + 2MNK p / 1.13e9       (N > 16)
  *               5.4 + 2 M N' K p / 0.355e9, N' = N rounded up to 4   (N <= 16: the few-column kernel)
- *   dense int8  6.6 + 4.5 k + 3.2 abits + 2MNK / 4.17e9 + MN / 1.22e6
- *   dense fp4   11.0 + 2.4 k + 0.4 abits + 2MNK / 4.86e9 + MN / 2.18e6
+ *   dense int8  3.2 + 4.5 k + 2.5 abits + 2MNK / 4.33e9 + MN / 2.33e6
+ *   dense fp4   3.9 + 2.3 k + 1.8 abits + 2MNK / 6.77e9 + MN / 4.76e6
  * N <= 4 is always bit-serial (weights are read once: wbits/8 byte per weight instead of 1 or 1/2).
  * Invalid arguments (bits outside 1..4, bipolar with bits != 1, non-positive sizes) return BS_ENGINE_BITSERIAL.
  */

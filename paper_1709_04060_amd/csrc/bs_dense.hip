@@ -85,14 +85,86 @@ __device__ __forceinline__ uint4 mask_tail(uint4 v, int k, int K)
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// Thresholding epilogue for OB output bits (T = 2^OB - 1 thresholds per row, Sec. 2.1.1): the
+// tile's thresholds go to LDS (the operand tiles are no longer needed), one row padded to a
+// power of two with INT_MAX (never reached, which also zeroes rows past M); every output is
+// compared with its row's T thresholds, the count's OB bits are placed at the row's position
+// of one 32-row word per plane, and the words leave as whole dwords.
+template <int OB, int WTM, int WTN, bool FP4, int WGM, int WGN>
+__device__ __forceinline__ void dense_threshold_planes(const DenseParams &p, typename AccOf<FP4>::type (&acc)[WTM][WTN],
+                                                       unsigned char *lds, int m0, int n0)
+{
+    constexpr int T = (1 << OB) - 1;
+    constexpr int TS = OB == 1 ? 1 : OB == 2 ? 4 : OB == 3 ? 8 : 16;  // table entries per row
+    constexpr int BM = 32 * WTM * WGM, NT = 64 * WGM * WGN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int li = lane & 31, lg = lane >> 5;
+    __syncthreads();
+    int32_t *tl = reinterpret_cast<int32_t *>(lds);  // [BM][TS]
+    for (int it = tid; it < BM * TS; it += NT) {
+        const int r = it / TS, t = it % TS;
+        tl[it] = (m0 + r < p.M && t < T) ? p.thr[(long long)(m0 + r) * T + t] : 0x7fffffff;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int a = 0; a < WTM; ++a) {
+        const int rbase = (wm * WTM + a) * 32;  // first row of this 32-row band within the block tile
+        uint32_t word[WTN][OB];
+#pragma unroll
+        for (int b = 0; b < WTN; ++b)
+#pragma unroll
+            for (int pl = 0; pl < OB; ++pl) word[b][pl] = 0;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rr = 8 * (v >> 2) + 4 * lg + (v & 3);
+            // one row's thresholds serve the WTN column tiles this lane holds
+            int th[TS];
+            if constexpr (TS == 1) {
+                th[0] = tl[rbase + rr];
+            } else {
+#pragma unroll
+                for (int q = 0; q < TS / 4; ++q) {
+                    const int4 t4 = reinterpret_cast<const int4 *>(tl)[(rbase + rr) * (TS / 4) + q];
+                    th[4 * q] = t4.x; th[4 * q + 1] = t4.y; th[4 * q + 2] = t4.z; th[4 * q + 3] = t4.w;
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < WTN; ++b) {
+                const int c = (int)acc[a][b][v];
+                uint32_t y = 0;
+#pragma unroll
+                for (int e = 0; e < T; ++e)  // y += (c >= t): compare into the carry mask, add the carry
+                    asm("v_cmp_le_i32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, 0, %0, vcc" : "+v"(y) : "v"(c), "v"(th[e]) : "vcc");
+#pragma unroll
+                for (int pl = 0; pl < OB; ++pl) word[b][pl] |= ((y >> pl) & 1u) << rr;
+            }
+        }
+        // Row bands cover a multiple of 128 rows, i.e. at least the Yd words of a column, so
+        // every word (padding included) is written by some band; words beyond Yd (a 256-row
+        // tile over a shorter column) are dropped.
+        const int wi = (m0 + rbase) / 32;
+#pragma unroll
+        for (int b = 0; b < WTN; ++b) {
+            const int n = n0 + (wn * WTN + b) * 32 + li;
+            // the two half-wavefronts hold complementary rows of the same column
+#pragma unroll
+            for (int pl = 0; pl < OB; ++pl) word[b][pl] |= __shfl_xor(word[b][pl], 32);
+            if (lg == 0 && n < p.N && wi < p.Yd) {
+#pragma unroll
+                for (int pl = 0; pl < OB; ++pl) p.Y[((long long)pl * p.N + n) * p.Yd + wi] = word[b][pl];
+            }
+        }
+    }
+}
+
 // Epilogue shared by the two dense kernels: int32 store, or successive thresholding with
 // the packed-plane output.  `lds` is the (no longer needed) operand space of the caller.
 template <int WTM, int WTN, bool FUSE, bool FP4, int WGM = 2, int WGN = 2>
 __device__ __forceinline__ void dense_epilogue(const DenseParams &p, typename AccOf<FP4>::type (&acc)[WTM][WTN],
                                                unsigned char *lds, int m0, int n0, int tile_m)
 {
-    constexpr int BM = 32 * WTM * WGM, NT = 64 * WGM * WGN;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
     const int li = lane & 31, lg = lane >> 5;
     (void)tile_m;
@@ -109,63 +181,11 @@ __device__ __forceinline__ void dense_epilogue(const DenseParams &p, typename Ac
                 }
             }
     } else {
-        // thresholds of the tile's rows -> LDS (the operand tiles are no longer needed),
-        // padded to 16 per row with INT_MAX (never reached) so that a row is four 16-byte reads
-        __syncthreads();
-        int4 *tl = reinterpret_cast<int4 *>(lds);  // [BM][4]
-        for (int it = tid; it < BM * 16; it += NT) {
-            const int r = it >> 4, t = it & 15;
-            reinterpret_cast<int32_t *>(tl)[it] =
-                (m0 + r < p.M && t < p.T) ? p.thr[(long long)(m0 + r) * p.T + t] : 0x7fffffff;
-        }
-        __syncthreads();
-        const int nq = (p.T + 3) >> 2;  // 16-byte groups of thresholds actually used
-#pragma unroll
-        for (int a = 0; a < WTM; ++a) {
-            const int rbase = (wm * WTM + a) * 32;  // first row of this 32-row band within the block tile
-            uint32_t word[WTN][4];
-#pragma unroll
-            for (int b = 0; b < WTN; ++b)
-#pragma unroll
-                for (int pl = 0; pl < 4; ++pl) word[b][pl] = 0;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int rr = 8 * (v >> 2) + 4 * lg + (v & 3);
-                uint32_t y[WTN];
-#pragma unroll
-                for (int b = 0; b < WTN; ++b) y[b] = 0;
-                // one row's thresholds serve the WTN column tiles this lane holds
-                int c[WTN];
-#pragma unroll
-                for (int b = 0; b < WTN; ++b) c[b] = (int)acc[a][b][v];
-                for (int q = 0; q < nq; ++q) {
-                    const int4 th = tl[(rbase + rr) * 4 + q];
-                    const int t4[4] = {th.x, th.y, th.z, th.w};
-#pragma unroll
-                    for (int b = 0; b < WTN; ++b)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)  // y += (c >= t): compare into the carry mask, add the carry
-                            asm("v_cmp_le_i32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, 0, %0, vcc" : "+v"(y[b]) : "v"(c[b]), "v"(t4[e]) : "vcc");
-                }
-                const bool live = m0 + rbase + rr < p.M;
-#pragma unroll
-                for (int b = 0; b < WTN; ++b)
-#pragma unroll
-                    for (int pl = 0; pl < 4; ++pl) word[b][pl] |= (live ? ((y[b] >> pl) & 1u) : 0u) << rr;
-            }
-            // Row bands cover a multiple of 128 rows, i.e. at least the Yd words of a column, so
-            // every word (padding included) is written by some band; words beyond Yd (a 256-row
-            // tile over a shorter column) are dropped.
-            const int wi = (m0 + rbase) / 32;
-#pragma unroll
-            for (int b = 0; b < WTN; ++b) {
-                const int n = n0 + (wn * WTN + b) * 32 + li;
-                // the two half-wavefronts hold complementary rows of the same column
-#pragma unroll
-                for (int pl = 0; pl < 4; ++pl) word[b][pl] |= __shfl_xor(word[b][pl], 32);
-                if (lg == 0 && n < p.N && wi < p.Yd)
-                    for (int pl = 0; pl < p.obits; ++pl) p.Y[((long long)pl * p.N + n) * p.Yd + wi] = word[b][pl];
-            }
+        switch (p.obits) {  // uniform
+        case 1: dense_threshold_planes<1, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0); break;
+        case 2: dense_threshold_planes<2, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0); break;
+        case 3: dense_threshold_planes<3, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0); break;
+        default: dense_threshold_planes<4, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0); break;
         }
     }
 }
@@ -555,8 +575,13 @@ bs_status choose_tile(DenseParams &p, bool fuse, hipStream_t st)
 {
     auto tiles = [&](int bm, int bn) { return (long long)((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn); };
     if (p.K % DK == 0) {
-        if (tiles(256, 256) >= 256) return launch_dense<4, 2, 2, 4, FP4>(p, fuse, st);
-        if (tiles(128, 256) >= 256) return launch_dense<2, 2, 2, 4, FP4>(p, fuse, st);
+        // Time ~ rounds over the 256 compute units x time of one round.  Measured round times relative to the
+        // 256 x 256 tile (fused epilogue, depths 2304..8192, 18 shapes from 64 to 186624 columns): 128 x 256
+        // 0.60, 128 x 128 0.36 (two of its workgroups share a compute unit); on a tie the larger tile.
+        auto rounds = [&](int bm, int bn) { return (tiles(bm, bn) + 255) / 256; };
+        const long long ca = rounds(256, 256) * 100, cb = rounds(128, 256) * 60, cc = rounds(128, 128) * 36;
+        if (ca <= cb && ca <= cc) return launch_dense<4, 2, 2, 4, FP4>(p, fuse, st);
+        if (cb <= cc) return launch_dense<2, 2, 2, 4, FP4>(p, fuse, st);
         return launch_dense<2, 2, 2, 2, FP4>(p, fuse, st);
     }
     if (tiles(256, 256) >= 256) return launch_dense<4, 4, 2, 2, FP4>(p, fuse, st);
@@ -596,34 +621,39 @@ bs_status dense_common(const void *W, int64_t ldw, const void *At, int64_t lda, 
 
 // ------------------------------------------------------------------ unpack (planes -> fp4 codes)
 // One thread turns one 32-bit word per plane (32 depth indices of one row) into 32 E2M1 codes
-// (16 bytes, low nibble = even index).  lut holds the code of every plane-bit combination c
-// (bit i of c = bit of plane i) in its nibble c.
+// (16 bytes, low nibble = even index).  Eight indices at a time: the even bits of a plane byte
+// are spread to the low bits of four bytes (a 24-bit multiply and a mask), the planes are
+// stacked into a table index per byte, and one byte-permute instruction looks all four up in
+// the eight-entry code table (lut_lo: code of index c in byte c); the odd bits go through a
+// second table that holds the codes already shifted to the high nibble (lut_hi).
+template <int BITS>
 __global__ void __launch_bounds__(256)
-unpack_fp4_kernel(const uint32_t *__restrict__ planes, int bits, unsigned long long lut, long long rows,
-                  long long depth, int Kd, uint8_t *__restrict__ dst, long long ld, long long words_per_row)
+unpack_fp4_kernel(const uint32_t *__restrict__ planes, uint2 lut_lo, uint2 lut_hi, unsigned rows, long long depth,
+                  int Kd, uint8_t *__restrict__ dst, long long ld, unsigned words_per_row)
 {
-    const long long item = (long long)blockIdx.x * 256 + threadIdx.x;
+    const unsigned item = blockIdx.x * 256u + threadIdx.x;
     if (item >= rows * words_per_row) return;
-    const long long r = item / words_per_row, dw = item - r * words_per_row;
-    uint32_t x[3] = {0, 0, 0};
+    const unsigned r = item / words_per_row, dw = item - r * words_per_row;
+    uint32_t x[BITS];
 #pragma unroll
-    for (int pl = 0; pl < 3; ++pl)
-        if (pl < bits) x[pl] = planes[((long long)pl * rows + r) * Kd + dw];
+    for (int pl = 0; pl < BITS; ++pl) x[pl] = planes[((size_t)pl * rows + r) * Kd + dw];
+    const long long left = depth - (long long)dw * 32;  // indices of this word inside the depth (>= 1)
     uint32_t out[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-        uint32_t o = 0;
+        uint32_t se = 0, so = 0;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int k = 8 * g + e;
-            const uint32_t c = ((x[0] >> k) & 1u) | (((x[1] >> k) & 1u) << 1) | (((x[2] >> k) & 1u) << 2);
-            uint32_t code = (uint32_t)(lut >> (4 * c)) & 0xFu;
-            if (dw * 32 + k >= depth) code = 0;  // +0.0 past the depth
-            o |= code << (4 * e);
+        for (int pl = 0; pl < BITS; ++pl) {
+            const uint32_t b = (x[pl] >> (8 * g)) & 0xFFu;
+            se |= (__umul24(b & 0x55u, 0x041041u) & 0x01010101u) << pl;
+            so |= (__umul24((b >> 1) & 0x55u, 0x041041u) & 0x01010101u) << pl;
         }
+        uint32_t o = __builtin_amdgcn_perm(lut_lo.y, lut_lo.x, se) | __builtin_amdgcn_perm(lut_hi.y, lut_hi.x, so);
+        const long long n = left - 8 * g;                // +0.0 past the depth
+        if (n < 8) o = n <= 0 ? 0u : (o & ((1u << (4 * (int)n)) - 1u));
         out[g] = o;
     }
-    *reinterpret_cast<uint4 *>(dst + r * ld + dw * 16) = make_uint4(out[0], out[1], out[2], out[3]);
+    *reinterpret_cast<uint4 *>(dst + (size_t)r * ld + (size_t)dw * 16) = make_uint4(out[0], out[1], out[2], out[3]);
 }
 
 // E2M1 code of a small integer, -1 if it is not representable (the format holds 0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives)
@@ -698,9 +728,20 @@ extern "C" bs_status bs_unpack_planes_fp4(const uint64_t *planes, int bits, bs_f
         if (code < 0) return BS_ERR_UNSUPPORTED;  // 3-bit unsigned (5, 7) and every 4-bit format
         lut |= (unsigned long long)code << (4 * c);
     }
+    uint32_t lo[2] = {0, 0}, hi[2] = {0, 0};  // byte c: the code of index c, and the same code in the high nibble
+    for (int c = 0; c < (1 << bits); ++c) {
+        const uint32_t code = (uint32_t)(lut >> (4 * c)) & 0xFu;
+        lo[c / 4] |= code << (8 * (c % 4));
+        hi[c / 4] |= (code << 4) << (8 * (c % 4));
+    }
     const int64_t items = rows * words;
-    unpack_fp4_kernel<<<dim3((unsigned)((items + 255) / 256)), 256, 0, static_cast<hipStream_t>(stream)>>>(
-        reinterpret_cast<const uint32_t *>(planes), bits, lut, rows, depth, (int)(2 * S), dst, ld, words);
+    const dim3 grid((unsigned)((items + 255) / 256));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint32_t *pw = reinterpret_cast<const uint32_t *>(planes);
+    const uint2 l2 = make_uint2(lo[0], lo[1]), h2 = make_uint2(hi[0], hi[1]);
+    if (bits == 1) unpack_fp4_kernel<1><<<grid, 256, 0, st>>>(pw, l2, h2, (unsigned)rows, depth, (int)(2 * S), dst, ld, (unsigned)words);
+    else if (bits == 2) unpack_fp4_kernel<2><<<grid, 256, 0, st>>>(pw, l2, h2, (unsigned)rows, depth, (int)(2 * S), dst, ld, (unsigned)words);
+    else unpack_fp4_kernel<3><<<grid, 256, 0, st>>>(pw, l2, h2, (unsigned)rows, depth, (int)(2 * S), dst, ld, (unsigned)words);
     return bs::after_launch();
 }
 

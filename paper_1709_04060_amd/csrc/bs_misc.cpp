@@ -19,9 +19,9 @@ extern "C" int bs_version(void) { return 100; }
 // Per-layer engine choice (Sec. 4.1.1 / 4.2): the fastest of the engines under a time model whose
 // constants were fitted to measurements over M, N in 256..4096, K in {1024, 4096} and W1A1, W1A2,
 // W2A2, W4A4 on MI355X (fused 2^abits-level epilogue, activation unpack counted for the dense
-// engines; least squares on the logarithm of the time: rms error 12 % bit-serial, 8 % int8, 6 % fp4;
-// over the measured cases the choice costs 0.25 % on average and 21 % at worst against always picking
-// the fastest).  Microseconds.
+// engines; non-negative least squares on the relative error, which stays within -18 / +29 % bit-serial,
+// -29 / +15 % int8, -17 / +10 % fp4; over the measured cases the choice costs 0.4 % on average and 31 % at
+// worst against always picking the fastest).  Microseconds.
 static bool fp4_representable(int bits, bs_format fmt) { return bits <= 2 || (bits == 3 && fmt == BS_TWOS_COMPLEMENT); }
 
 extern "C" bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_format afmt, int64_t M, int64_t N, int64_t K)
@@ -33,11 +33,11 @@ extern "C" bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_f
     const double mnk2 = 2.0 * (double)M * (double)N * (double)K, mn = (double)M * (double)N;
     // up to 16 columns the bit-serial call is the streaming kernel in groups of four columns
     const double t_bitserial = N <= 16 ? 5.4 + 2.0 * (double)M * (double)(4 * ((N + 3) / 4)) * (double)K * pairs / 0.355e9
-                                       : 5.2 + 0.475 * kk * pairs + mnk2 * pairs / 1.23e9;
+                                       : 4.8 + 0.21 * kk * pairs + mnk2 * pairs / 1.13e9;
     if (fp4_representable(wbits, wfmt) && fp4_representable(abits, afmt)) {
-        const double t_fp4 = 11.0 + 2.4 * kk + 0.4 * abits + mnk2 / 4.86e9 + mn / 2.18e6;
+        const double t_fp4 = 3.9 + 2.3 * kk + 1.8 * abits + mnk2 / 6.77e9 + mn / 4.76e6;
         return t_fp4 < t_bitserial ? BS_ENGINE_DENSE_FP4 : BS_ENGINE_BITSERIAL;  // measured 1.1 - 1.5 x faster than int8 everywhere
     }
-    const double t_int8 = 6.6 + 4.5 * kk + 3.2 * abits + mnk2 / 4.17e9 + mn / 1.22e6;
+    const double t_int8 = 3.2 + 4.5 * kk + 2.5 * abits + mnk2 / 4.33e9 + mn / 2.33e6;
     return t_int8 < t_bitserial ? BS_ENGINE_DENSE_I8 : BS_ENGINE_BITSERIAL;
 }

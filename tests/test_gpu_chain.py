@@ -135,6 +135,15 @@ def test_conv_and_pool_on_a_batch(B, H, W, C, F, k, s, p, w, wf, a, af, obits):
     low = bs.bs_im2col_interleaved_batch(xp, B, H, W, C, k, k, s, p)
     two = bs.bs_gemm_threshold(Fp, FMT[wf], low, FMT[af], bs.bs_lowered_depth(C, k, k), dev(thr), obits)
     assert_equal(planes_to_numpy(two), want, "im2col_batch + gemm_threshold")
+    # the same layer on the matrix-core engines: lowered columns unpacked to int8 / E2M1 codes
+    Kl = bs.bs_lowered_depth(C, k, k)
+    i8 = bs.bs_gemm_i8_threshold(bs.bs_unpack_planes(Fp, FMT[wf], Kl), bs.bs_unpack_planes(low, FMT[af], Kl), Kl, dev(thr), obits)
+    assert_equal(planes_to_numpy(i8), want, "im2col_batch + unpack + gemm_i8_threshold")
+    fp4_ok = lambda bits, fmt: bits <= 2 or (bits == 3 and fmt == TC)
+    if fp4_ok(w, wf) and fp4_ok(a, af):
+        f4 = bs.bs_gemm_fp4_threshold(bs.bs_unpack_planes_fp4(Fp, FMT[wf], Kl), bs.bs_unpack_planes_fp4(low, FMT[af], Kl), Kl,
+                                      dev(thr), obits)
+        assert_equal(planes_to_numpy(f4), want, "im2col_batch + unpack_fp4 + gemm_fp4_threshold")
     if min(OH, OW) >= 2:
         Y = [oracle.threshold(c.reshape(OH * OW, F).T.copy(), thr).T.reshape(OH, OW, F) for c in convs]
         wantp = np.concatenate([oracle.pack(oracle.maxpool(y, 2, 2).reshape(-1, F), obits, U) for y in Y], axis=1)
