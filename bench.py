@@ -388,15 +388,22 @@ def extras(bs, workloads, dev, timed):
                             cur = bs.bs_gemm_threshold(Wp, BP, cur.reshape(2, Bn, -1), U, L["geom"][1], th, 2, out=bufs[key])
                     else:
                         if L["kind"] == "conv":
+                            # unpack first, lower second: the small feature map becomes E2M1 codes (16 bytes per 32
+                            # channels), and that map is lowered like a one-plane map of 4 C bit-channels, so the
+                            # large lowered matrix is written once, already as codes (channels are multiples of 32)
                             H, W, C, F, k, s, p = L["geom"]
                             Kx = bs.bs_lowered_depth(C, k, k)
                             OHW = ((H + 2 * p - k) // s + 1) ** 2
-                            cols = bs.bs_im2col_interleaved_batch(cur, Bn, H, W, C, k, k, s, p, out=bufs.setdefault(
-                                key + ("low",), torch.empty((2, Bn * OHW, bs.bs_words_per_row(Kx)), dtype=torch.int64, device="cuda")))
+                            cmap = bs.bs_unpack_planes_fp4(cur, U, C, out=bufs.setdefault(
+                                key + ("map",), torch.empty((Bn * H * W, C // 2), dtype=torch.uint8, device="cuda")))
+                            codes = bs.bs_im2col_interleaved_batch(
+                                cmap.view(torch.int64).reshape(1, Bn * H * W, -1), Bn, H, W, 4 * C, k, k, s, p, out=bufs.setdefault(
+                                    key + ("fp4",), torch.empty((1, Bn * OHW, bs.bs_words_per_row(4 * Kx)), dtype=torch.int64, device="cuda"))
+                            ).view(torch.uint8).reshape(Bn * OHW, -1)
                         else:
                             Kx, cols = L["geom"][1], cur.reshape(2, Bn, -1)
-                        codes = bs.bs_unpack_planes_fp4(cols, U, Kx, out=bufs.setdefault(
-                            key + ("fp4",), torch.empty((cols.shape[1], 16 * ((Kx + 31) // 32)), dtype=torch.uint8, device="cuda")))
+                            codes = bs.bs_unpack_planes_fp4(cols, U, Kx, out=bufs.setdefault(
+                                key + ("fp4",), torch.empty((Bn, 16 * ((Kx + 31) // 32)), dtype=torch.uint8, device="cuda")))
                         cur = bs.bs_gemm_fp4_threshold(wd[L["name"]], codes, Kx, th, 2, out=bufs[key])
                 return cur
             want = frame_batch().clone()

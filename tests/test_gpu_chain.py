@@ -144,6 +144,15 @@ def test_conv_and_pool_on_a_batch(B, H, W, C, F, k, s, p, w, wf, a, af, obits):
         f4 = bs.bs_gemm_fp4_threshold(bs.bs_unpack_planes_fp4(Fp, FMT[wf], Kl), bs.bs_unpack_planes_fp4(low, FMT[af], Kl), Kl,
                                       dev(thr), obits)
         assert_equal(planes_to_numpy(f4), want, "im2col_batch + unpack_fp4 + gemm_fp4_threshold")
+        if C % 32 == 0:
+            # unpack first, lower second: the map of E2M1 codes is itself a one-plane map of 4 C bit-channels
+            # (16 bytes per 32 channels), which the lowering kernel copies like any other
+            codes = bs.bs_unpack_planes_fp4(xp, FMT[af], C)                       # [B H W][C / 2 bytes]
+            cmap = codes.view(torch.int64).reshape(1, B * H * W, -1)
+            lowc = bs.bs_im2col_interleaved_batch(cmap, B, H, W, 4 * C, k, k, s, p)  # [1][B OH OW][4 Kl bits]
+            f5 = bs.bs_gemm_fp4_threshold(bs.bs_unpack_planes_fp4(Fp, FMT[wf], Kl), lowc.view(torch.uint8).reshape(B * OH * OW, -1),
+                                          Kl, dev(thr), obits)
+            assert_equal(planes_to_numpy(f5), want, "unpack_fp4 + im2col_batch on codes + gemm_fp4_threshold")
     if min(OH, OW) >= 2:
         Y = [oracle.threshold(c.reshape(OH * OW, F).T.copy(), thr).T.reshape(OH, OW, F) for c in convs]
         wantp = np.concatenate([oracle.pack(oracle.maxpool(y, 2, 2).reshape(-1, F), obits, U) for y in Y], axis=1)
