@@ -82,7 +82,7 @@ def test_gemm_i8_threshold(M, K, N, obits):
 
 
 def test_dense_engine_large_tiles_and_packed_route():
-    """2048^3 takes the 256 x 256 tile configuration; operands come from packed planes through
+    """2048^3 (128 x 128 tiles, two workgroups per compute unit); operands come from packed planes through
     bs_unpack_planes, so the dense engine is checked as a drop-in for bs_gemm_threshold."""
     rng = np.random.default_rng(2048)
     n = 2048
@@ -103,11 +103,14 @@ def test_dense_engine_large_tiles_and_packed_route():
     assert_equal(planes_to_numpy(y_bits), planes_to_numpy(y_dense), "engines agree")
 
 
-def test_dense_engines_middle_tile():
-    """4096 x 2304 outputs: too few 256 x 256 tiles for every compute unit, enough 128 x 256 ones (eight wavefronts);
+@pytest.mark.parametrize("M,N", [(4096 - 3, 2304 - 5), (2048 - 3, 4096 - 5)])
+def test_dense_engines_large_tiles(M, N):
+    """The tile is chosen by rounds over the 256 compute units x relative round time (256 x 256: 1, 128 x 256: 0.6,
+    128 x 128: 0.36).  4093 x 2299 outputs: 144 / 288 / 576 tiles -> 1 / 2 / 3 rounds -> the 256 x 256 tile;
+    2045 x 4091: 128 / 256 / 512 tiles -> 1 / 1 / 2 rounds -> the 128 x 256 tile (smaller products take 128 x 128).
     int8 and fp4, int32 output and fused thresholds, ragged last tiles."""
-    rng = np.random.default_rng(77)
-    M, K, N = 4096 - 3, 128, 2304 - 5
+    rng = np.random.default_rng(77 + M)
+    K = 128
     W, A = draw(rng, (M, K), 2, TC), draw(rng, (K, N), 2, U)
     want = oracle.gemm(W, A)
     thr = workloads.thresholds(rng, M, 2, float(want.mean()), float(want.std()))
@@ -115,8 +118,8 @@ def test_dense_engines_middle_tile():
     Wp = bs.bs_pack_planes(dev(W), 2, bs.BS_TWOS_COMPLEMENT)
     Ap = bs.bs_pack_planes(dev(A), 2, bs.BS_UNSIGNED, depth_is_strided=True)
     W8, A8 = bs.bs_unpack_planes(Wp, bs.BS_TWOS_COMPLEMENT, K), bs.bs_unpack_planes(Ap, bs.BS_UNSIGNED, K)
-    assert_equal(bs.bs_gemm_i8(W8, A8, K).cpu().numpy(), want, "int8, 128 x 256 tiles")
-    assert_equal(planes_to_numpy(bs.bs_gemm_i8_threshold(W8, A8, K, dev(thr), 2)), wantp, "int8 fused, 128 x 256 tiles")
+    assert_equal(bs.bs_gemm_i8(W8, A8, K).cpu().numpy(), want, "int8")
+    assert_equal(planes_to_numpy(bs.bs_gemm_i8_threshold(W8, A8, K, dev(thr), 2)), wantp, "int8 fused")
     W4, A4 = bs.bs_unpack_planes_fp4(Wp, bs.BS_TWOS_COMPLEMENT, K), bs.bs_unpack_planes_fp4(Ap, bs.BS_UNSIGNED, K)
-    assert_equal(bs.bs_gemm_fp4(W4, A4, K).cpu().numpy(), want, "fp4, 128 x 256 tiles")
-    assert_equal(planes_to_numpy(bs.bs_gemm_fp4_threshold(W4, A4, K, dev(thr), 2)), wantp, "fp4 fused, 128 x 256 tiles")
+    assert_equal(bs.bs_gemm_fp4(W4, A4, K).cpu().numpy(), want, "fp4")
+    assert_equal(planes_to_numpy(bs.bs_gemm_fp4_threshold(W4, A4, K, dev(thr), 2)), wantp, "fp4 fused")

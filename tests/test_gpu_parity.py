@@ -255,3 +255,19 @@ def test_im2col_interleaved(H, W, C, k, s, p, abits):
     xin = oracle.pack(x.reshape(H * W, C), abits, U)          # packed HWC planes
     out = bs.bs_im2col_interleaved(planes_to_dev(xin), H, W, C, k, k, s, p)
     assert_equal(planes_to_numpy(out), want, "interleaved lowering")
+
+
+def test_im2col_more_maps_than_grid_rows():
+    """70000 one-plane images exceed the 65535 rows of the launch grid's second dimension, so workgroups walk
+    several maps.  With a 1 x 1 kernel lowering is the identity on every image (checked on all of them), and a
+    3 x 3 kernel is checked against the oracle on the first, one past the grid limit and the last image."""
+    rng = np.random.default_rng(70000)
+    B, H, W, C = 70000, 2, 2, 32
+    x = rng.integers(0, 2, size=(B, H, W, C)).astype(np.int8)
+    xp = bs.bs_pack_planes(dev(x.reshape(B * H * W, C)), 1, bs.BS_UNSIGNED)
+    same = bs.bs_im2col_interleaved_batch(xp, B, H, W, C, 1, 1, 1, 0)
+    assert torch.equal(same, xp), "1 x 1 lowering of a batch is the identity"
+    low = planes_to_numpy(bs.bs_im2col_interleaved_batch(xp, B, H, W, C, 3, 3, 1, 1))   # [1][B * 4][words of 288 bits]
+    for b in (0, 65535, 65536, B - 1):
+        want = oracle.pack(oracle.im2col_plain(x[b], 3, 3, 1, 1).T.copy(), 1, U)
+        assert_equal(low[:, 4 * b: 4 * b + 4], want, "image %d" % b)
