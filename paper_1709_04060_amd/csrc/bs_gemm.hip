@@ -86,7 +86,7 @@ bs_status gemm_common(const uint64_t *Wp, int wbits, bs_format wfmt, const uint6
     const bool corr = !xr && ((wfmt == BS_BIPOLAR) || (afmt == BS_BIPOLAR));
     g.stream_weights = (long long)wbits * M * S * 8 >= kStreamWeightBytes;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (gemv_applicable(g, abits, afmt == BS_BIPOLAR, wfmt == BS_BIPOLAR)) return launch_gemv(g, wbits, abits, fuse, xr, st);
+    if (gemv_applicable(g, wbits, abits, afmt == BS_BIPOLAR, wfmt == BS_BIPOLAR)) return launch_gemv(g, wbits, abits, fuse, xr, st);
     return dispatch_wb(g, wbits, abits, fuse, corr, false, xr, st);
 }
 

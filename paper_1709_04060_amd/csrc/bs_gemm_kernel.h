@@ -82,11 +82,12 @@ constexpr int kConvMaxLut = 2048;  // lowered dwords the implicit-lowering kerne
 // GEMV path (bs_gemv.hip): a workgroup handles at most kGemvMaxCols columns, activation planes in LDS; up to
 // kGemvMaxGroupedCols columns run as groups of four side by side (each group streams the weights again, from
 // L2 as the groups run together): 32 x 32 tiles would leave 3/4 or more of their columns empty there
-// (W4A4 8192 x 8192: 89 us tiled for 5..32 columns, 36 / 53 / 67 us grouped for 8 / 12 / 16).
+// (W4A4 8192 x 8192: 89 us tiled for 5..32 columns, 36 / 53 / 67 us grouped for 8 / 12 / 16).  Between 5 and
+// kGemvMaxGroupedCols columns the faster of the two kernels is taken under a time model (gemv_applicable).
 constexpr int kGemvMaxCols = 4;
 constexpr int kGemvMaxGroupedCols = 16;
 constexpr size_t kGemvMaxLds = 64 * 1024;
-bool gemv_applicable(const GemmParams &g, int abits, bool a_bipolar, bool w_bipolar);
+bool gemv_applicable(const GemmParams &g, int wbits, int abits, bool a_bipolar, bool w_bipolar);
 bs_status launch_gemv(const GemmParams &g, int wbits, int abits, bool fuse, bool xr, hipStream_t st);
 
 // acc + popcount(x) in ONE instruction: v_bcnt_u32_b32 adds its second operand for
@@ -672,7 +673,8 @@ bs_status launch_planes(const GemmParams &g, bool fuse, bool corr, bool conv, bo
     const long long tiles64 = (long long)((g.M + 63) / 64) * ((g.N + 63) / 64);
     const long long tiles32 = (long long)((g.M + 31) / 32) * ((g.N + 31) / 32);
     constexpr int KT_SMALL = kStageDwords;  // deeper stages were measured and bring nothing: the stage count is not what bounds small grids
-    if (tiles32 <= kNarrowMaxTiles32) return launch_cfg<WB, AB, 4, 1, 1, 1, 4, KT_SMALL>(g, fuse, corr, conv, xr, st);
+    // (also whenever at most 16 columns exist: wider tiles would be half empty or more)
+    if (tiles32 <= kNarrowMaxTiles32 || g.N <= 16) return launch_cfg<WB, AB, 4, 1, 1, 1, 4, KT_SMALL>(g, fuse, corr, conv, xr, st);
     if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4, KT_SMALL>(g, fuse, corr, conv, xr, st);
     return launch_cfg<WB, AB, 4, 4, 2, 2, 1, kStageDwords>(g, fuse, corr, conv, xr, st);
 }

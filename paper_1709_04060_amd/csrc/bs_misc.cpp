@@ -31,9 +31,17 @@ extern "C" bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_f
     if (N <= 4) return BS_ENGINE_BITSERIAL;  // weights streamed once: wbits/8 byte per weight beats a byte or half a byte
     const double pairs = (double)wbits * abits, kk = (double)K / 1024.0;
     const double mnk2 = 2.0 * (double)M * (double)N * (double)K, mn = (double)M * (double)N;
-    // up to 16 columns the bit-serial call is the streaming kernel in groups of four columns
-    const double t_bitserial = N <= 16 ? 5.4 + 2.0 * (double)M * (double)(4 * ((N + 3) / 4)) * (double)K * pairs / 0.355e9
-                                       : 4.8 + 0.21 * kk * pairs + mnk2 * pairs / 1.13e9;
+    // 5..16 columns: the bit-serial call takes the faster of the streaming kernel in groups of four columns and
+    // the tiled kernel with 32 x 8 tiles (the same two models decide inside bs_gemm)
+    double t_bitserial = 4.8 + 0.21 * kk * pairs + mnk2 * pairs / 1.13e9;
+    if (N <= 16) {
+        const double groups = (double)((N + 3) / 4) * (double)M / 4096.0;
+        const double t_stream = 3.88 + groups * (0.69 + 0.2 * pairs + 0.031 * pairs * kk);
+        const double blocks = (double)((M + 31) / 32) * (double)((N + 7) / 8);
+        const double rounds = 1.0 + (blocks > 256.0 ? (blocks - 256.0) / 900.0 : 0.0);
+        const double t_tiled = 3.64 + rounds * pairs * (0.253 * kk + 0.21);
+        t_bitserial = t_stream < t_tiled ? t_stream : t_tiled;
+    }
     if (fp4_representable(wbits, wfmt) && fp4_representable(abits, afmt)) {
         const double t_fp4 = 3.9 + 2.3 * kk + 1.8 * abits + mnk2 / 6.77e9 + mn / 4.76e6;
         return t_fp4 < t_bitserial ? BS_ENGINE_DENSE_FP4 : BS_ENGINE_BITSERIAL;  // measured 1.1 - 1.5 x faster than int8 everywhere

@@ -120,7 +120,8 @@ def test_gemm_shapes(M, K, N, w, wf, a, af):
 @pytest.mark.parametrize("w,wf,a,af,obits", [(1, BP, 2, U, 2), (4, TC, 4, U, 4), (2, U, 3, TC, 1), (3, TC, 1, U, 3),
                                              (1, U, 1, BP, 2)])
 def test_few_column_path(N, M, K, w, wf, a, af, obits):
-    """N <= 16 takes the streaming (GEMV) kernel, in groups of four columns; N = 17 and bipolar activations the tiled one."""
+    """N <= 4 takes the streaming (GEMV) kernel, 5..16 columns too at these row counts (groups of four columns);
+    N = 17 and bipolar activations the tiled one."""
     rng = np.random.default_rng(N * 100 + M + K + w)
     W, A = draw(rng, (M, K), w, wf), draw(rng, (K, N), a, af)
     want = oracle.gemm(W, A)
@@ -131,6 +132,25 @@ def test_few_column_path(N, M, K, w, wf, a, af, obits):
     out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
     bs.bs_gemm_threshold(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits, out=out)
     assert_equal(planes_to_numpy(out), oracle.threshold_pack(want, thr, obits), "gemv fused")
+
+
+@pytest.mark.parametrize("N", [5, 8, 12, 16])
+@pytest.mark.parametrize("w,wf,a,af,obits", [(1, BP, 2, U, 2), (4, TC, 4, U, 4)])
+def test_few_columns_many_rows(N, w, wf, a, af, obits):
+    """5..16 columns and many short rows: the time model hands these to the tiled kernel (32 x 8 tiles) instead of
+    the grouped streaming kernel; 4096 x 256 for W4A4 and W1A2 lies on that side for every N here, 4096 x 9216 W4A4
+    at N = 5 on the other."""
+    rng = np.random.default_rng(N * 7 + w)
+    for (M, K) in [(4096, 256), (4096 + 33, 9216 if (w == 4 and N == 5) else 300)]:
+        W, A = draw(rng, (M, K), w, wf), draw(rng, (K, N), a, af)
+        want = oracle.gemm(W, A)
+        assert_equal(run_gemm(W, A, w, wf, a, af), want, "int32 %dx%dx%d" % (M, K, N))
+        thr = make_thr(rng, want, obits)
+        Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
+        Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
+        out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
+        bs.bs_gemm_threshold(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits, out=out)
+        assert_equal(planes_to_numpy(out), oracle.threshold_pack(want, thr, obits), "fused %dx%dx%d" % (M, K, N))
 
 
 @pytest.mark.parametrize("M,K,N", [(1, 1, 1), (64, 64, 64), (65, 129, 63), (200, 3000, 130), (4, 5000, 2), (300, 100, 4),
