@@ -582,7 +582,9 @@ bs_status choose_tile(DenseParams &p, bool fuse, hipStream_t st)
         const long long ca = rounds(256, 256) * 100, cb = rounds(128, 256) * 60, cc = rounds(128, 128) * 36;
         if (ca <= cb && ca <= cc) return launch_dense<4, 2, 2, 4, FP4>(p, fuse, st);
         if (cb <= cc) return launch_dense<2, 2, 2, 4, FP4>(p, fuse, st);
-        return launch_dense<2, 2, 2, 2, FP4>(p, fuse, st);
+        // 128 x 128 on eight wavefronts of 32 x 64 as well: 10 % faster than on four of 64 x 64 (fp4, fused,
+        // 384 x 2304 x 10816: 12.5 vs 14.0 us; 2048^3: 9.1 vs 10.6 us)
+        return launch_dense<1, 2, 4, 2, FP4>(p, fuse, st);
     }
     if (tiles(256, 256) >= 256) return launch_dense<4, 4, 2, 2, FP4>(p, fuse, st);
     return launch_dense<2, 2, 2, 2, FP4>(p, fuse, st);
