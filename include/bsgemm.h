@@ -285,8 +285,8 @@ bs_status bs_streamline_thresholds(const double *t, int T, const double *a, cons
  *               min(3.88 + G (0.69 + 0.2 p + 0.031 p k), 3.64 + R p (0.253 k + 0.21))   (5 <= N <= 16), with
  *               G = ceil(N / 4) M / 4096 (streaming kernel, groups of four columns), R = 1 + max(0, B - 256) / 900,
  *               B = ceil(M / 32) ceil(N / 8) (tiled kernel, 32 x 8 tiles); bs_gemm itself picks between these two
- *   dense int8  3.2 + 4.5 k + 2.5 abits + 2MNK / 4.33e9 + MN / 2.33e6
- *   dense fp4   3.9 + 2.3 k + 1.8 abits + 2MNK / 6.77e9 + MN / 4.76e6
+ *   dense int8  3.2 + 4.3 k + 1.8 abits + 2MNK / 4.07e9 + MN / 2.18e6
+ *   dense fp4   4.2 + 2.2 k + 1.1 abits + 2MNK / 6.63e9 + MN / 3.92e6
  * N <= 4 is always bit-serial (weights are read once: wbits/8 byte per weight instead of 1 or 1/2).
  * Invalid arguments (bits outside 1..4, bipolar with bits != 1, non-positive sizes) return BS_ENGINE_BITSERIAL.
  */

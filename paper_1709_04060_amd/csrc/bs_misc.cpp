@@ -20,7 +20,7 @@ extern "C" int bs_version(void) { return 100; }
 // constants were fitted to measurements over M, N in 256..4096, K in {1024, 4096} and W1A1, W1A2,
 // W2A2, W4A4 on MI355X (fused 2^abits-level epilogue, activation unpack counted for the dense
 // engines; non-negative least squares on the relative error, which stays within -18 / +29 % bit-serial,
-// -29 / +15 % int8, -17 / +10 % fp4; over the measured cases the choice costs 0.4 % on average and 31 % at
+// -33 / +12 % int8, -17 / +11 % fp4; over the measured cases the choice costs 0.4 % on average and 17 % at
 // worst against always picking the fastest).  Microseconds.
 static bool fp4_representable(int bits, bs_format fmt) { return bits <= 2 || (bits == 3 && fmt == BS_TWOS_COMPLEMENT); }
 
@@ -43,9 +43,9 @@ extern "C" bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_f
         t_bitserial = t_stream < t_tiled ? t_stream : t_tiled;
     }
     if (fp4_representable(wbits, wfmt) && fp4_representable(abits, afmt)) {
-        const double t_fp4 = 3.9 + 2.3 * kk + 1.8 * abits + mnk2 / 6.77e9 + mn / 4.76e6;
+        const double t_fp4 = 4.2 + 2.2 * kk + 1.1 * abits + mnk2 / 6.63e9 + mn / 3.92e6;
         return t_fp4 < t_bitserial ? BS_ENGINE_DENSE_FP4 : BS_ENGINE_BITSERIAL;  // measured 1.1 - 1.5 x faster than int8 everywhere
     }
-    const double t_int8 = 3.2 + 4.5 * kk + 2.5 * abits + mnk2 / 4.33e9 + mn / 2.33e6;
+    const double t_int8 = 3.2 + 4.3 * kk + 1.8 * abits + mnk2 / 4.07e9 + mn / 2.18e6;
     return t_int8 < t_bitserial ? BS_ENGINE_DENSE_I8 : BS_ENGINE_BITSERIAL;
 }
