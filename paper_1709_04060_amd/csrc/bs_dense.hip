@@ -367,8 +367,9 @@ dense_gemm_kernel(const DenseParams p)
 // their use.  Such a load writes the 64 lanes' 16 bytes to consecutive LDS addresses, so
 // a row is 64 unpadded bytes; bank conflicts of the fragment reads are avoided by an XOR
 // swizzle applied on the GLOBAL side (lane l of a load fetches chunk (l % 4) ^ f(row) of
-// its row, f(row) = (row / 2) % 4) and undone by the reader.  Needs a depth that is a
-// multiple of 64 (no tail to mask); other depths use the register-staged kernel above.
+// its row, f(row) = (row / 2) % 4) and undone by the reader.  Needs a depth of whole 16-byte
+// chunks (a last stage of fewer than four chunks is completed with zeros written by the lanes
+// that have nothing to load); other depths use the register-staged kernel above.
 typedef __attribute__((address_space(3))) void lds_void;
 
 template <int WTM, int WTN, bool FUSE, bool FP4, int WGM = 2, int WGN = 2>
@@ -391,10 +392,12 @@ dense_gemm_lds_kernel(const DenseParams p)
 
     // ---- loader: instruction j of this wavefront covers stacked rows (wave * LPW + j) * 16 .. + 15 ----
     const int8_t *gsrc[LPW];
+    int gchunk[LPW];  // byte offset of this lane's chunk within a stage's 64 depth bytes
 #pragma unroll
     for (int j = 0; j < LPW; ++j) {
         const int row = (wave * LPW + j) * 16 + (lane >> 2);
         const int c = (lane & 3) ^ ((row >> 1) & 3);
+        gchunk[j] = c * 16;
         if (row < BM) {
             const int m = m0 + row < p.M ? m0 + row : p.M - 1;
             gsrc[j] = p.W + (long long)m * p.ldw + c * 16;
@@ -408,6 +411,19 @@ dense_gemm_lds_kernel(const DenseParams p)
         for (int j = 0; j < LPW; ++j)
             __builtin_amdgcn_global_load_lds((const void *)(gsrc[j] + k0), (lds_void *)(lds + buf * TILE + (wave * LPW + j) * 16 * DK),
                                              16, 0, 0);
+    };
+    // The last stage of a depth that is a multiple of 16 but not of 64 bytes: lanes whose chunk lies past the
+    // depth write zeros instead of loading.  The first chunk of every row is inside the depth, so each of
+    // the LPW load instructions still has active lanes and the load counter advances as for a full stage.
+    auto issue_tail = [&](int buf, int k0) {
+#pragma unroll
+        for (int j = 0; j < LPW; ++j) {
+            unsigned char *dst = lds + buf * TILE + (wave * LPW + j) * 16 * DK;
+            if (k0 + gchunk[j] < p.K)
+                __builtin_amdgcn_global_load_lds((const void *)(gsrc[j] + k0), (lds_void *)dst, 16, 0, 0);
+            else
+                *reinterpret_cast<uint4 *>(dst + lane * 16) = make_uint4(0, 0, 0, 0);
+        }
     };
 
     typename AccOf<FP4>::type acc[WTM][WTN];
@@ -439,14 +455,17 @@ dense_gemm_lds_kernel(const DenseParams p)
                 acc[a][b] = mma<FP4>(fa[set][a], fb[set][b], acc[a][b]);
     };
 
-    const int nst = p.K / DK;
-    // One stage.  MORE: stage i + 2 exists and is requested now (branch-free main loop, so that
-    // the loads can be spread between the MFMAs); the last two stages run without requests.
-    auto step = [&](auto more_t, int i, int cur) {
-        constexpr bool MORE = decltype(more_t)::value;
+    const int nfull = p.K / DK, nst = (p.K + DK - 1) / DK;  // whole stages, and stages with the partial last one
+    // One stage.  MODE 1: stage i + 2 exists and is requested now (branch-free main loop, so that
+    // the loads can be spread between the MFMAs); MODE 2: the same for the partial last stage;
+    // MODE 0: the last two stages run without requests.
+    auto step = [&](auto mode_t, int i, int cur) {
+        constexpr int MODE = decltype(mode_t)::value;
+        constexpr bool MORE = MODE != 0;
         const int nxt = cur == NBUF - 1 ? 0 : cur + 1, last = cur == 0 ? NBUF - 1 : cur - 1;
         // buffer `last` held stage i - 1: nobody reads it after the previous iteration's barrier
-        if constexpr (MORE) issue(last, (i + NBUF - 1) * DK);
+        if constexpr (MODE == 1) issue(last, (i + NBUF - 1) * DK);
+        if constexpr (MODE == 2) issue_tail(last, (i + NBUF - 1) * DK);
         load_frags(1, cur, 1);
         mfmas(0);
         if constexpr (MORE) {
@@ -478,17 +497,24 @@ dense_gemm_lds_kernel(const DenseParams p)
 
     // prologue: stages 0 .. NBUF - 2 requested, stage 0 awaited
 #pragma unroll
-    for (int st = 0; st < NBUF - 1; ++st)
-        if (st < nst) issue(st, st * DK);
-    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    for (int st = 0; st < NBUF - 1; ++st) {
+        if (st < nfull) issue(st, st * DK);
+        else if (st < nst) issue_tail(st, st * DK);
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     load_frags(0, 0, 0);
     int cur = 0, i = 0;
-    for (; i + NBUF - 1 < nst; ++i) {
-        step(std::true_type{}, i, cur);
+    for (; i + NBUF - 1 < nfull; ++i) {
+        step(std::integral_constant<int, 1>{}, i, cur);
         cur = cur == NBUF - 1 ? 0 : cur + 1;
     }
+    if (i + NBUF - 1 < nst) {  // the partial last stage is requested here (at most once)
+        step(std::integral_constant<int, 2>{}, i, cur);
+        cur = cur == NBUF - 1 ? 0 : cur + 1;
+        ++i;
+    }
     for (; i < nst; ++i) {
-        step(std::false_type{}, i, cur);
+        step(std::integral_constant<int, 0>{}, i, cur);
         cur = cur == NBUF - 1 ? 0 : cur + 1;
     }
 
@@ -551,7 +577,7 @@ bs_status launch_dense(DenseParams &p, bool fuse, hipStream_t st)
     if (blocks >= (1LL << 31)) return BS_ERR_UNSUPPORTED;
     // four wavefronts of 128 x 128 exist in the register-staged kernel only (the direct-to-LDS kernel runs that tile on eight)
     constexpr bool DIRECT = !(WTM == 4 && WTN == 4);
-    if (p.K % DK == 0) {  // no depth tail: operands can go straight from memory to LDS
+    if (p.K % 16 == 0) {  // whole 16-byte chunks: operands can go straight from memory to LDS
         if constexpr (DIRECT) {
             if (fuse) dense_gemm_lds_kernel<WTM, WTN, true, FP4, WGM, WGN><<<dim3((unsigned)blocks), NT, 0, st>>>(p);
             else dense_gemm_lds_kernel<WTM, WTN, false, FP4, WGM, WGN><<<dim3((unsigned)blocks), NT, 0, st>>>(p);
@@ -574,7 +600,7 @@ template <bool FP4>
 bs_status choose_tile(DenseParams &p, bool fuse, hipStream_t st)
 {
     auto tiles = [&](int bm, int bn) { return (long long)((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn); };
-    if (p.K % DK == 0) {
+    if (p.K % 16 == 0) {
         // Time ~ rounds over the 256 compute units x time of one round.  Measured round times relative to the
         // 256 x 256 tile (fused epilogue, depths 2304..8192, 18 shapes from 64 to 186624 columns): 128 x 256
         // 0.60, 128 x 128 0.36 (two of its workgroups share a compute unit); on a tie the larger tile.

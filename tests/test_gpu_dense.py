@@ -123,3 +123,35 @@ def test_dense_engines_large_tiles(M, N):
     W4, A4 = bs.bs_unpack_planes_fp4(Wp, bs.BS_TWOS_COMPLEMENT, K), bs.bs_unpack_planes_fp4(Ap, bs.BS_UNSIGNED, K)
     assert_equal(bs.bs_gemm_fp4(W4, A4, K).cpu().numpy(), want, "fp4")
     assert_equal(planes_to_numpy(bs.bs_gemm_fp4_threshold(W4, A4, K, dev(thr), 2)), wantp, "fp4 fused")
+
+
+@pytest.mark.parametrize("M,N", [(70, 45), (300, 520), (4096 - 3, 2304 - 5), (2048 - 3, 4096 - 5)])
+@pytest.mark.parametrize("kbytes", [16, 48, 80, 144, 1200])
+def test_dense_partial_last_stage(M, N, kbytes):
+    """Depths of whole 16-byte chunks that are no multiple of the 64-byte stage (int8: K = kbytes, fp4: K = 2 kbytes;
+    1200 bytes is conv2's lowered depth in E2M1 codes): the direct-to-LDS kernels complete the last stage with
+    zeros.  Rows are followed in memory by a guard value that must not leak in; all three tile sizes."""
+    if kbytes == 1200 and M > 2048:
+        pytest.skip("covered at the smaller sizes; keeps the oracle products short")
+    rng = np.random.default_rng(M + N + kbytes)
+    # int8 engine, operands with a leading dimension larger than the depth and guard bytes behind every row
+    K = kbytes
+    W, A = draw(rng, (M, K), 4, TC), draw(rng, (K, N), 4, U)
+    want = oracle.gemm(W, A)
+    Wg = np.full((M, K + 64), 99, dtype=np.int8); Wg[:, :K] = W
+    Ag = np.full((N, K + 64), 99, dtype=np.int8); Ag[:, :K] = A.T
+    Wd, Ad = dev(Wg)[:, :K], dev(Ag)[:, :K]                     # strided views: ld = K + 64
+    assert_equal(bs.bs_gemm_i8(Wd, Ad, K).cpu().numpy(), want, "int8 %d bytes" % kbytes)
+    thr = workloads.thresholds(rng, M, 4, float(want.mean()), float(want.std()) + 1.0)
+    assert_equal(planes_to_numpy(bs.bs_gemm_i8_threshold(Wd, Ad, K, dev(thr), 4)), oracle.threshold_pack(want, thr, 4),
+                 "int8 fused %d bytes" % kbytes)
+    # fp4 engine from packed planes (the unpacker's rows are exactly K / 2 bytes)
+    K = 2 * kbytes
+    W, A = draw(rng, (M, K), 2, TC), draw(rng, (K, N), 2, U)
+    want = oracle.gemm(W, A)
+    W4 = bs.bs_unpack_planes_fp4(bs.bs_pack_planes(dev(W), 2, bs.BS_TWOS_COMPLEMENT), bs.BS_TWOS_COMPLEMENT, K)
+    A4 = bs.bs_unpack_planes_fp4(bs.bs_pack_planes(dev(A), 2, bs.BS_UNSIGNED, depth_is_strided=True), bs.BS_UNSIGNED, K)
+    assert_equal(bs.bs_gemm_fp4(W4, A4, K).cpu().numpy(), want, "fp4 %d bytes" % kbytes)
+    thr = workloads.thresholds(rng, M, 2, float(want.mean()), float(want.std()) + 1.0)
+    assert_equal(planes_to_numpy(bs.bs_gemm_fp4_threshold(W4, A4, K, dev(thr), 2)), oracle.threshold_pack(want, thr, 2),
+                 "fp4 fused %d bytes" % kbytes)
