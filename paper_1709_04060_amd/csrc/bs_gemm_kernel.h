@@ -38,6 +38,7 @@ namespace bs {
 
 constexpr int kStageDwords = 32;  // dwords of depth per packed row and stage
 constexpr long long kNarrowMaxTiles32 = 200;  // measured, W1A2..W4A4 at depth 2048: 32 x 8 tiles win up to 184 tiles of 32 x 32, tie at 256, lose from 512
+constexpr long long kHalfWidthMaxTiles32 = 384;  // 32 x 16 tiles between the tiny grids and this many 32 x 32 tiles
 constexpr long long kIdleMinBlocks = 257;  // more workgroups than compute units (measured: 10.9 vs 12.5 us at 320, 10.7 vs 9.6 us at 256)
 
 struct GemmParams {
@@ -657,7 +658,7 @@ bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, bo
     if constexpr (KS > 1 && TN == 1) {
         // narrow tiles exist for grids of a few workgroups per compute unit at most
         return launch_variant<WB, AB, TM, TN, WM, WN, KS, KT, false>(g, grid, fuse, corr, conv, xr, st);
-    } else if constexpr (KS > 1) {
+    } else if constexpr (KS > 1 && TN == 4) {
         if (blocks < kIdleMinBlocks) return launch_variant<WB, AB, TM, TN, WM, WN, KS, KT, false>(g, grid, fuse, corr, conv, xr, st);
     }
     return launch_variant<WB, AB, TM, TN, WM, WN, KS, KT, true>(g, grid, fuse, corr, conv, xr, st);
@@ -675,6 +676,9 @@ bs_status launch_planes(const GemmParams &g, bool fuse, bool corr, bool conv, bo
     constexpr int KT_SMALL = kStageDwords;  // deeper stages were measured and bring nothing: the stage count is not what bounds small grids
     // (also whenever at most 16 columns exist: wider tiles would be half empty or more)
     if (tiles32 <= kNarrowMaxTiles32 || g.N <= 16) return launch_cfg<WB, AB, 4, 1, 1, 1, 4, KT_SMALL>(g, fuse, corr, conv, xr, st);
+    // just above the tiny grids 32 x 16 tiles still pay: twice the workgroups, so that two wavefronts share a SIMD
+    // (4096 x 9216 x 64 W1A2: 18.7 -> 15.5 us; W4A4 4096 x 4096 x 64: 49.9 -> 41.5 us; a tie from 512 tiles on)
+    if (tiles32 <= kHalfWidthMaxTiles32) return launch_cfg<WB, AB, 4, 2, 1, 1, 4, KT_SMALL>(g, fuse, corr, conv, xr, st);
     if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4, KT_SMALL>(g, fuse, corr, conv, xr, st);
     return launch_cfg<WB, AB, 4, 4, 2, 2, 1, kStageDwords>(g, fuse, corr, conv, xr, st);
 }

@@ -96,11 +96,11 @@ def test_gemm_all_precisions_and_formats(w, wf, a, af):
     assert_equal(run_gemm(W, A, w, wf, a, af), oracle.gemm(W, A), "gemm W%dA%d" % (w, a))
 
 
-@pytest.mark.parametrize("M,K,N", [(530, 1100, 610), (1500, 1100, 1480)])
+@pytest.mark.parametrize("M,K,N", [(530, 1100, 610), (700, 1100, 900), (1500, 1100, 1480)])
 @pytest.mark.parametrize("w,wf,a,af", ALL_WA + BIP)
 def test_gemm_all_precisions_on_larger_grids(w, wf, a, af, M, K, N):
-    """The launch configurations that small shapes do not reach: 340 workgroups of 32 x 32 (depth split over
-    the wavefronts, more workgroups than compute units) and 576 tiles of 64 x 64; ragged in every dimension."""
+    """The launch configurations that small shapes do not reach: 340 tiles of 32 x 32 run as 32 x 16 tiles, 638 as
+    32 x 32 tiles (both with the depth split over the wavefronts), and 576 tiles of 64 x 64; ragged in every dimension."""
     rng = np.random.default_rng(w * 64 + a * 16 + wf * 4 + af + M)
     W, A = draw(rng, (M, K), w, wf), draw(rng, (K, N), a, af)
     assert_equal(run_gemm(W, A, w, wf, a, af), oracle.gemm(W, A), "gemm W%dA%d %dx%dx%d" % (w, a, M, K, N))
@@ -237,9 +237,9 @@ def test_threshold_activate(M, N, obits):
     assert_equal(planes_to_numpy(out), oracle.threshold_pack(C, thr, obits), "threshold")
 
 
-# tiny grids take 32 x 8 tiles, (530, 1100, 610) the 32 x 32 ones, (1500, 700, 1480) the 64 x 64 ones
+# tiny grids take 32 x 8 tiles, (530, 1100, 610) 32 x 16, (700, 600, 900) 32 x 32, (1500, 700, 1480) 64 x 64 ones
 @pytest.mark.parametrize("M,K,N", [(1, 64, 1), (64, 256, 64), (70, 1100, 45), (200, 700, 130), (260, 300, 3), (530, 1100, 610),
-                                   (1500, 700, 1480)])
+                                   (700, 600, 900), (1500, 700, 1480)])
 @pytest.mark.parametrize("w,wf,a,af,obits", [(1, BP, 2, U, 2), (2, TC, 2, U, 2), (4, TC, 4, U, 4), (1, BP, 1, BP, 1),
                                              (2, U, 3, TC, 3)])
 def test_gemm_threshold_fused(M, K, N, w, wf, a, af, obits):
