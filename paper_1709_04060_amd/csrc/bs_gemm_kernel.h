@@ -41,6 +41,29 @@ constexpr long long kNarrowMaxTiles32 = 200;  // measured, W1A2..W4A4 at depth 2
 constexpr long long kHalfWidthMaxTiles32 = 384;  // 32 x 16 tiles between the tiny grids and this many 32 x 32 tiles
 constexpr long long kIdleMinBlocks = 257;  // more workgroups than compute units (measured: 10.9 vs 12.5 us at 320, 10.7 vs 9.6 us at 256)
 
+// Division of a 32-bit index by a launch constant as a multiply-high and two shifts (the set-up of
+// a workgroup is a single wavefront's serial code, where a plain division costs about forty
+// instructions and there are up to nine of them).  Exact for every 32-bit numerator.
+struct FastDiv {
+    uint32_t mul;
+    int sh1, sh2;
+};
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    int l = 0;
+    while ((1ull << l) < d) ++l;  // ceil(log2 d)
+    FastDiv f;
+    f.mul = (uint32_t)((((1ull << l) - d) << 32) / d + 1);
+    f.sh1 = l < 1 ? l : 1;
+    f.sh2 = l > 1 ? l - 1 : 0;
+    return f;
+}
+__device__ __forceinline__ int fdiv(int n, const FastDiv &f)
+{
+    const uint32_t t = __umulhi(f.mul, (uint32_t)n);
+    return (int)((t + (((uint32_t)n - t) >> f.sh1)) >> f.sh2);
+}
+
 struct GemmParams {
     const uint32_t *W;  // dword view of Wp
     const uint32_t *A;  // dword view of Ap
@@ -73,7 +96,17 @@ struct GemmParams {
     int cVec;           // 1 if cCd and cPix are multiples of 4: a 16-byte chunk never straddles two taps
     // single-column kernel: read the weights with the non-temporal hint (set for large weight sets)
     int stream_weights;
+    // divisors of the workgroups' set-up code (filled by finish_params)
+    FastDiv dGx, dHx, dRx, dT, dOHW, dOW, dCd, dKW;
 };
+
+// to be called once the fields above are final, before the launch
+inline void finish_params(GemmParams &g)
+{
+    auto fd = [](int d) { return make_fastdiv(d > 0 ? (uint32_t)d : 1u); };
+    g.dGx = fd(g.gx); g.dHx = fd(g.hx); g.dRx = fd(g.rx); g.dT = fd(g.T);
+    g.dOHW = fd(g.cOHW); g.dOW = fd(g.cOW); g.dCd = fd(g.cCd); g.dKW = fd(g.cKW);
+}
 
 // weight bytes from which the few-column kernel streams past the caches
 constexpr long long kStreamWeightBytes = 64ll << 20;
@@ -179,13 +212,13 @@ __device__ __forceinline__ int popc4(const uint4 &a)
 __device__ __forceinline__ bool tile_of_block(const GemmParams &p, int bid, int &tm, int &tn)
 {
     if (p.rx == 0) {
-        tm = bid / p.gx;
+        tm = fdiv(bid, p.dGx);
         tn = bid - tm * p.gx;
         return true;
     }
     const int xcd = bid & 7, local = bid >> 3;
-    const int ry = xcd / p.rx, rx = xcd - ry * p.rx;
-    const int ly = local / p.hx, lx = local - ly * p.hx;
+    const int ry = fdiv(xcd, p.dRx), rx = xcd - ry * p.rx;
+    const int ly = fdiv(local, p.dHx), lx = local - ly * p.hx;
     tm = ry * p.hy + ly;
     tn = rx * p.hx + lx;
     return ly < p.hy && tm < p.gy && tn < p.gx;
@@ -260,8 +293,8 @@ bs_gemm_kernel(const GemmParams p)
                 loff[s] = srow * KCH + (c ^ ((r / TN) & 7));
                 if (n0 + r < p.N) {
                     if constexpr (CONV) {
-                        const int b = (n0 + r) / p.cOHW, opix = (n0 + r) - b * p.cOHW;
-                        const int oh = opix / p.cOW, ow = opix - oh * p.cOW;
+                        const int b = fdiv(n0 + r, p.dOHW), opix = (n0 + r) - b * p.cOHW;
+                        const int oh = fdiv(opix, p.dOW), ow = opix - oh * p.cOW;
                         pix_h[s] = oh * p.cStride - p.cPad;
                         pix_w[s] = ow * p.cStride - p.cPad;
                         goff[s] = (pl * p.cB + b) * p.cH * p.cW * p.cPix;  // base of image b in plane pl
@@ -279,8 +312,8 @@ bs_gemm_kernel(const GemmParams p)
     }
     if constexpr (CONV) {
         for (int q = tid; q < p.Kd; q += NT) {
-            const int tap = q / p.cCd, cd = q - tap * p.cCd;
-            const int fr = tap / p.cKW, fs = tap - fr * p.cKW;
+            const int tap = fdiv(q, p.dCd), cd = q - tap * p.cCd;
+            const int fr = fdiv(tap, p.dKW), fs = tap - fr * p.cKW;
             lut[q] = q < p.cKused ? ((fr << 24) | (fs << 16) | cd) : -1;
         }
         __syncthreads();
@@ -352,7 +385,7 @@ bs_gemm_kernel(const GemmParams p)
     if constexpr (FUSE) {
         // ride on the first stage's memory latency instead of paying a round trip in the epilogue
         for (int i = tid; i < BM * p.T; i += NT) {
-            const int r = i / p.T;
+            const int r = fdiv(i, p.dT);
             thr_s[i] = (m0 + r < p.M) ? p.thr[(long long)(m0 + r) * p.T + (i - r * p.T)] : 0x7fffffff;
         }
     }
@@ -528,11 +561,18 @@ bs_gemm_kernel(const GemmParams p)
             }
         }
     } else {
-        // Successive thresholding: count the thresholds reached, stage the few-bit
-        // results as bytes in LDS ([column][row]), then pack along the rows.
-        static_assert(BM % 32 == 0, "packed output is written in 32-bit words");
-        uint8_t *ytile = reinterpret_cast<uint8_t *>(lds) + (KS > 1 ? BM * BN * 4 : 0);
-        if (writer) {
+        // Successive thresholding: count the thresholds reached.  The eight lanes that share a
+        // column index hold four consecutive rows each, 32 rows in all: every lane places its
+        // results' bits at its rows' positions of one word per plane, three lane exchanges OR the
+        // eight partial words together, and the first of the eight lanes stores them (no staging
+        // through LDS, no barrier: on the tiny layers that took a quarter of the kernel).
+        static_assert(BM % 32 == 0 && TM == 4, "a wavefront's eight row groups of four rows make one 32-bit word");
+        if (writer) {  // uniform per wavefront
+            uint32_t word[TN][4];
+#pragma unroll
+            for (int c = 0; c < TN; ++c)
+#pragma unroll
+                for (int pl = 0; pl < 4; ++pl) word[c][pl] = 0;
 #pragma unroll
             for (int r = 0; r < TM; ++r) {
                 const int m = m0 + wrow0 + r;
@@ -547,34 +587,30 @@ bs_gemm_kernel(const GemmParams p)
                         for (int c = 0; c < TN; ++c) y[c] += (val[r][c] >= tv) ? 1 : 0;
                     }
 #pragma unroll
-                for (int c = 0; c < TN; ++c) ytile[(acol0 + c) * BM + wrow0 + r] = (uint8_t)y[c];
-            }
-        }
-        __syncthreads();
-        constexpr int WPC = BM / 32;  // output dwords per column and plane in this tile
-        const bool last_m_block = (tile_m == p.gy - 1);
-        for (int it = tid; it < BN * WPC; it += NT) {
-            const int col = it / WPC, wi = it % WPC;
-            const int n = n0 + col;
-            if (n >= p.N) continue;
-            const uint32_t *yb = reinterpret_cast<const uint32_t *>(ytile + col * BM + wi * 32);
-            uint32_t bitsw[4] = {0, 0, 0, 0};
+                for (int c = 0; c < TN; ++c)
 #pragma unroll
-            for (int d = 0; d < 8; ++d) {
-                const uint32_t x = yb[d];
+                    for (int pl = 0; pl < 4; ++pl) word[c][pl] |= (((uint32_t)y[c] >> pl) & 1u) << (4 * ly + r);
+            }
+            const bool last_m_block = (tile_m == p.gy - 1);
+            const int wi = m0 / 32 + wm;  // this wavefront's word of the output column
+#pragma unroll
+            for (int c = 0; c < TN; ++c) {
+                const int n = n0 + acol0 + c;
 #pragma unroll
                 for (int pl = 0; pl < 4; ++pl) {
-                    // bits pl of the four bytes of x -> a 4-bit group
-                    const uint32_t nib = ((((x >> pl) & 0x01010101u) * 0x01020408u) >> 24) & 0xFu;
-                    bitsw[pl] |= nib << (4 * d);
+                    if (pl >= p.obits) break;  // uniform
+                    uint32_t v = word[c][pl];
+                    v |= __shfl_xor(v, 8);
+                    v |= __shfl_xor(v, 16);
+                    v |= __shfl_xor(v, 32);
+                    if (ly == 0 && n < p.N) {
+                        uint32_t *dst = p.Y + ((long long)pl * p.N + n) * p.Yd;
+                        dst[wi] = v;
+                        // the last row block also clears the padding words of the column
+                        if (last_m_block && wm == WM - 1)
+                            for (int z = wi + 1; z < p.Yd; ++z) dst[z] = 0;
+                    }
                 }
-            }
-            for (int pl = 0; pl < p.obits; ++pl) {
-                uint32_t *dst = p.Y + ((long long)pl * p.N + n) * p.Yd;
-                dst[m0 / 32 + wi] = bitsw[pl];
-                // the last row block also clears the padding words of the column
-                if (last_m_block && wi == WPC - 1)
-                    for (int z = m0 / 32 + WPC; z < p.Yd; ++z) dst[z] = 0;
             }
         }
     }
@@ -651,6 +687,7 @@ bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, bo
     GemmParams g = g_in;
     const long long blocks = plan_tile_order(g, BM, BN, WB, AB);
     if (blocks >= (1LL << 31)) return BS_ERR_UNSUPPORTED;
+    finish_params(g);
     dim3 grid((unsigned)blocks);
     // The inner loop's idle-slot rhythm pays when at least two wavefronts share a SIMD.  The small-grid
     // configuration (one wavefront per SIMD and workgroup) gets there only with more workgroups than
