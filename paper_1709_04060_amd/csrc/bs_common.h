@@ -12,6 +12,22 @@ constexpr int kMaxBits = 4;      // the few-bit range of the paper (w, a <= 4)
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+// A kernel's parameter block arrives through scalar loads, and the compiler requests each
+// field where it is first needed: for a 350-byte block that is up to nine load-and-wait
+// rounds on the serial path of every workgroup.  Touching every 64-byte line of the block in
+// one burst at the kernel's entry lets the later field loads hit the scalar cache (measured on
+// the small latency-bound layers: 0.1 to 0.3 us per launch).
+template <int BYTES>
+__device__ __forceinline__ void prefetch_kernel_arguments()
+{
+    typedef const uint32_t __attribute__((address_space(4))) *karg_ptr;
+    karg_ptr ka = (karg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+    uint32_t sink = ka[(BYTES - 4) / 4];
+#pragma unroll
+    for (int o = 0; o + 4 <= BYTES; o += 64) sink ^= ka[o / 4];
+    asm volatile("" ::"s"(sink));  // keeps the loads; nothing is done with the value
+}
+
 inline bs_status after_launch() { return hipGetLastError() == hipSuccess ? BS_OK : BS_ERR_LAUNCH; }
 
 inline bs_status check_bits_fmt(int bits, bs_format fmt)

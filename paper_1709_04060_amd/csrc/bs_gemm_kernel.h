@@ -259,6 +259,7 @@ bs_gemm_kernel(const GemmParams p)
     __shared__ __attribute__((aligned(16))) int lut[CONV ? kConvMaxLut + 4 : 4];
     __shared__ int thr_s[FUSE ? BM * 15 : 1];    // thresholds of the tile's rows, fetched while the first stage is in flight
 
+    prefetch_kernel_arguments<(int)sizeof(GemmParams)>();
     int tile_m, tile_n;
     if (!tile_of_block(p, blockIdx.x, tile_m, tile_n)) return;  // uniform for the workgroup
 

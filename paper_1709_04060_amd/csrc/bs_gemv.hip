@@ -27,6 +27,7 @@ constexpr int UNROLL = 4;           // chunks per lane and plane fetched in one 
 template <int WB, int AB, int NC, bool FUSE, bool XOR = false, bool NT = false>
 __global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams p)
 {
+    bs::prefetch_kernel_arguments<(int)sizeof(GemmParams)>();
     extern __shared__ uint4 ldsA[];  // [AB][NC][nch]
     __shared__ int colsum_s[NC];
     __shared__ int yrow[ROWS_PER_BLOCK][NC];
