@@ -574,23 +574,31 @@ bs_gemm_kernel(const GemmParams p)
             for (int c = 0; c < TN; ++c)
 #pragma unroll
                 for (int pl = 0; pl < 4; ++pl) word[c][pl] = 0;
+            // the threshold count known at compile time, so that a row's thresholds are read from LDS in one
+            // go instead of one wait per threshold (rows past M hold INT_MAX thresholds: count 0)
+            auto count_rows = [&](auto t_c) {
+                constexpr int T = decltype(t_c)::value;
 #pragma unroll
-            for (int r = 0; r < TM; ++r) {
-                const int m = m0 + wrow0 + r;
-                const int *th = thr_s + (wrow0 + r) * p.T;
-                int y[TN];
+                for (int r = 0; r < TM; ++r) {
+                    const int *th = thr_s + (wrow0 + r) * T;
+                    int tv[T];
 #pragma unroll
-                for (int c = 0; c < TN; ++c) y[c] = 0;
-                if (m < p.M)
-                    for (int t = 0; t < p.T; ++t) {
-                        const int tv = th[t];
+                    for (int t = 0; t < T; ++t) tv[t] = th[t];
 #pragma unroll
-                        for (int c = 0; c < TN; ++c) y[c] += (val[r][c] >= tv) ? 1 : 0;
+                    for (int c = 0; c < TN; ++c) {
+                        uint32_t y = 0;
+#pragma unroll
+                        for (int t = 0; t < T; ++t) y += (val[r][c] >= tv[t]) ? 1u : 0u;
+#pragma unroll
+                        for (int pl = 0; pl < 4; ++pl) word[c][pl] |= ((y >> pl) & 1u) << (4 * ly + r);
                     }
-#pragma unroll
-                for (int c = 0; c < TN; ++c)
-#pragma unroll
-                    for (int pl = 0; pl < 4; ++pl) word[c][pl] |= (((uint32_t)y[c] >> pl) & 1u) << (4 * ly + r);
+                }
+            };
+            switch (p.obits) {  // uniform
+            case 1: count_rows(std::integral_constant<int, 1>{}); break;
+            case 2: count_rows(std::integral_constant<int, 3>{}); break;
+            case 3: count_rows(std::integral_constant<int, 7>{}); break;
+            default: count_rows(std::integral_constant<int, 15>{}); break;
             }
             const bool last_m_block = (tile_m == p.gy - 1);
             const int wi = m0 / 32 + wm;  // this wavefront's word of the output column
