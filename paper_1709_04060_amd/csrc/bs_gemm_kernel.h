@@ -307,25 +307,14 @@ bs_gemm_kernel(const GemmParams p)
             }
         }
     }
-    if (CORR) {
-        for (int i = tid; i < BM; i += NT) corr_row[i] = 0;
-        for (int i = tid; i < BN; i += NT) corr_col[i] = 0;
-    }
-    if constexpr (CONV) {
-        for (int q = tid; q < p.Kd; q += NT) {
-            const int tap = fdiv(q, p.dCd), cd = q - tap * p.cCd;
-            const int fr = fdiv(tap, p.dKW), fs = tap - fr * p.cKW;
-            lut[q] = q < p.cKused ? ((fr << 24) | (fs << 16) | cd) : -1;
-        }
-        __syncthreads();
-    }
-
     uint4 stage[CPT];
-    auto fetch = [&](int k0) {
+    // DO_W / DO_A: the weight slots, the activation slots or (in the depth loop) both
+    auto fetch_part = [&](int k0, auto w_c, auto a_c) {
+        constexpr bool DO_W = decltype(w_c)::value, DO_A = decltype(a_c)::value;
         // CONV: the table entries of all activation chunks first (one 16-byte LDS read each),
         // so that a single wait precedes the gathers instead of one per word
         int4 tap4[CONV ? CPT : 1];
-        if constexpr (CONV) {
+        if constexpr (CONV && DO_A) {
 #pragma unroll
             for (int s = 0; s < CPT; ++s) {
                 const int c = (tid + s * NT) % KCH;
@@ -337,6 +326,7 @@ bs_gemm_kernel(const GemmParams p)
 #pragma unroll
         for (int s = 0; s < CPT; ++s) {
             const int c = (tid + s * NT) % KCH;
+            if ((s * NT < WROWS * KCH) ? !DO_W : !DO_A) continue;  // resolved at compile time
             uint4 v = make_uint4(0, 0, 0, 0);
             if (s * NT < WROWS * KCH) {
                 if (goff[s] >= 0 && k0 + c * 4 < p.Kd)
@@ -368,6 +358,7 @@ bs_gemm_kernel(const GemmParams p)
             stage[s] = v;
         }
     };
+    auto fetch = [&](int k0) { fetch_part(k0, std::true_type{}, std::true_type{}); };
 
     int acc[NACC][TM][TN];
 #pragma unroll
@@ -382,7 +373,25 @@ bs_gemm_kernel(const GemmParams p)
     const uint4 *ldsW = lds + wrow0 * KCH;
     const uint4 *ldsA = lds + (WROWS + acol0) * KCH;
 
-    fetch(0);
+    // The weights of the first stage are requested before the correction counters are cleared and the lowering
+    // table is built, so that this set-up runs under their memory latency; the gathers need the table.
+    fetch_part(0, std::true_type{}, std::false_type{});
+    if (CORR) {
+        for (int i = tid; i < BM; i += NT) corr_row[i] = 0;
+        for (int i = tid; i < BN; i += NT) corr_col[i] = 0;
+    }
+    if constexpr (CONV) {
+        for (int q = tid; q < p.Kd; q += NT) {
+            const int tap = fdiv(q, p.dCd), cd = q - tap * p.cCd;
+            const int fr = fdiv(tap, p.dKW), fs = tap - fr * p.cKW;
+            lut[q] = q < p.cKused ? ((fr << 24) | (fs << 16) | cd) : -1;
+        }
+        // a barrier that waits for the table's LDS writes only: __syncthreads() would also wait for the weight
+        // loads just requested
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    }
+
+    fetch_part(0, std::false_type{}, std::true_type{});
     if constexpr (FUSE) {
         // ride on the first stage's memory latency instead of paying a round trip in the epilogue
         for (int i = tid; i < BM * p.T; i += NT) {
