@@ -711,7 +711,9 @@ bs_status launch_cfg(const GemmParams &g_in, bool fuse, bool corr, bool conv, bo
     // configuration (one wavefront per SIMD and workgroup) gets there only with more workgroups than
     // the chip has compute units.
     if constexpr (KS > 1 && TN == 1) {
-        // narrow tiles exist for grids of a few workgroups per compute unit at most
+        // narrow tiles: the rhythm pays from two workgroups per compute unit on (measured at 516..1024 workgroups:
+        // 0..4 % for W1A2, 4..7 % for W2A2 and W4A4)
+        if (blocks >= 2 * kIdleMinBlocks) return launch_variant<WB, AB, TM, TN, WM, WN, KS, KT, true>(g, grid, fuse, corr, conv, xr, st);
         return launch_variant<WB, AB, TM, TN, WM, WN, KS, KT, false>(g, grid, fuse, corr, conv, xr, st);
     } else if constexpr (KS > 1 && TN == 4) {
         if (blocks < kIdleMinBlocks) return launch_variant<WB, AB, TM, TN, WM, WN, KS, KT, false>(g, grid, fuse, corr, conv, xr, st);
