@@ -232,8 +232,8 @@ __device__ __forceinline__ bool tile_of_block(const GemmParams &p, int bid, int 
 // loader gathers each lowered column's words from the image (Sec. 3.2's lowering folded
 // into the operand fetch, so the lowered matrix never exists in memory).
 // XOR: both operands bipolar (W1A1): popcount(XOR) instead of popcount(AND), no correction terms.
-// KT: dwords of depth per packed row and stage (a multiple of 32; both configurations use
-// 32: deeper stages were measured on the small, latency-bound grids and bring nothing).
+// KT: dwords of depth per packed row and stage (a multiple of 32; 32 everywhere except the
+// 32 x 32 tiles of more than four plane pairs, which take 64: see launch_planes).
 template <int WB, int AB, int TM, int TN, int WM, int WN, int KS, int KT, bool FUSE, bool CORR, bool CONV = false,
           bool XOR = false, bool IDLE = true>
 __global__ void __launch_bounds__(WM * WN * KS * 64)
@@ -736,7 +736,11 @@ bs_status launch_planes(const GemmParams &g, bool fuse, bool corr, bool conv, bo
     // just above the tiny grids 32 x 16 tiles still pay: twice the workgroups, so that two wavefronts share a SIMD
     // (4096 x 9216 x 64 W1A2: 18.7 -> 15.5 us; W4A4 4096 x 4096 x 64: 49.9 -> 41.5 us; a tie from 512 tiles on)
     if (tiles32 <= kHalfWidthMaxTiles32) return launch_cfg<WB, AB, 4, 2, 1, 1, 4, KT_SMALL>(g, fuse, corr, conv, xr, st);
-    if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4, KT_SMALL>(g, fuse, corr, conv, xr, st);
+    // 32 x 32 tiles: with more than four plane pairs (the pair-at-a-time loop) a stage of twice the depth halves
+    // the barriers per product (W4A4 8192 x 8192 x 64: 137 -> 122 us; neutral at 1024 tiles); with one or two pairs
+    // it measured 5..12 % slower, with four the same
+    constexpr int KT_MID = (WB * AB > 4) ? 2 * kStageDwords : kStageDwords;
+    if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4, KT_MID>(g, fuse, corr, conv, xr, st);
     return launch_cfg<WB, AB, 4, 4, 2, 2, 1, kStageDwords>(g, fuse, corr, conv, xr, st);
 }
 
