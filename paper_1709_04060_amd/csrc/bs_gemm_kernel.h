@@ -730,17 +730,23 @@ bs_status launch_planes(const GemmParams &g, bool fuse, bool corr, bool conv, bo
     // 32 rows x 8 columns, four times as many workgroups, each with a quarter of the products.
     const long long tiles64 = (long long)((g.M + 63) / 64) * ((g.N + 63) / 64);
     const long long tiles32 = (long long)((g.M + 31) / 32) * ((g.N + 31) / 32);
-    constexpr int KT_SMALL = kStageDwords;  // deeper stages were measured and bring nothing: the stage count is not what bounds small grids
-    // (also whenever at most 16 columns exist: wider tiles would be half empty or more)
-    if (tiles32 <= kNarrowMaxTiles32 || g.N <= 16) return launch_cfg<WB, AB, 4, 1, 1, 1, 4, KT_SMALL>(g, fuse, corr, conv, xr, st);
+    constexpr int KT_SMALL = kStageDwords;
+    // With more than four plane pairs (the pair-at-a-time loop) a stage of twice the depth halves the barriers per
+    // product: 3..13 % on deep products, neutral on short ones (W4A4 256 x 4096 x 256: 22.8 -> 20.2 us; 32 x 32 tiles,
+    // 8192 x 8192 x 64: 137 -> 122 us), except where the larger LDS tile limits the resident workgroups (narrow tiles
+    // from about 800 workgroups on: 16384 x 4096 x 16 took 45.8 instead of 39.4 us).  One or two pairs measured
+    // 5..12 % slower with it, four the same.
+    constexpr int KT_DEEP = (WB * AB > 4) ? 2 * kStageDwords : kStageDwords;
+    // narrow tiles also whenever at most 16 columns exist: wider tiles would be half empty or more
+    if (tiles32 <= kNarrowMaxTiles32 || g.N <= 16) {
+        const long long narrow_blocks = (long long)((g.M + 31) / 32) * ((g.N + 7) / 8);
+        if (narrow_blocks <= 768) return launch_cfg<WB, AB, 4, 1, 1, 1, 4, KT_DEEP>(g, fuse, corr, conv, xr, st);
+        return launch_cfg<WB, AB, 4, 1, 1, 1, 4, KT_SMALL>(g, fuse, corr, conv, xr, st);
+    }
     // just above the tiny grids 32 x 16 tiles still pay: twice the workgroups, so that two wavefronts share a SIMD
     // (4096 x 9216 x 64 W1A2: 18.7 -> 15.5 us; W4A4 4096 x 4096 x 64: 49.9 -> 41.5 us; a tie from 512 tiles on)
-    if (tiles32 <= kHalfWidthMaxTiles32) return launch_cfg<WB, AB, 4, 2, 1, 1, 4, KT_SMALL>(g, fuse, corr, conv, xr, st);
-    // 32 x 32 tiles: with more than four plane pairs (the pair-at-a-time loop) a stage of twice the depth halves
-    // the barriers per product (W4A4 8192 x 8192 x 64: 137 -> 122 us; neutral at 1024 tiles); with one or two pairs
-    // it measured 5..12 % slower, with four the same
-    constexpr int KT_MID = (WB * AB > 4) ? 2 * kStageDwords : kStageDwords;
-    if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4, KT_MID>(g, fuse, corr, conv, xr, st);
+    if (tiles32 <= kHalfWidthMaxTiles32) return launch_cfg<WB, AB, 4, 2, 1, 1, 4, KT_DEEP>(g, fuse, corr, conv, xr, st);
+    if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4, KT_DEEP>(g, fuse, corr, conv, xr, st);
     return launch_cfg<WB, AB, 4, 4, 2, 2, 1, kStageDwords>(g, fuse, corr, conv, xr, st);
 }
 
