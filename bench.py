@@ -30,7 +30,7 @@ BINARY_PEAK_TOPS = CUS * SIMDS_PER_CU * LANES * 32 * 2 / CLOCKS_PER_PRODUCT * CL
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per bs_gemm launch on the W2A2 4096^3 workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE scaled by a 256 MiB copy (profiles/pmc_fetch_write_w2a2_4096.md): 24.5 MiB + 64 MiB
-GEMM_TRAFFIC_BYTES = 92_947_776
+GEMM_TRAFFIC_BYTES = 92_971_495
 
 
 def main() -> int:
