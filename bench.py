@@ -141,7 +141,7 @@ def main() -> int:
     result = {
         "metric": "bit-serial GEMM GOPS (2*M*N*K/T), W2A2", "value": round(gops, 1), "unit": "GOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32 popcount (u32 bitwise)",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32", "dtype_note": "32-bit AND + popcount on bit planes, int32 accumulation",
         "data": "synthetic",
         "config": {"workload": "W2A2 4096x4096x4096: pack int8 activations (K x N) to bit planes + bit-serial "
                                "GEMM to int32; weights pre-packed", "M": M, "N": N, "K": K, "wbits": w, "abits": a},
