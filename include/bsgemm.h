@@ -151,7 +151,11 @@ bs_status bs_gemm_threshold(const uint64_t *Wp, int wbits, bs_format wfmt,
 bs_status bs_im2col_interleaved(const uint64_t *in, int abits, int H, int W, int C,
                                 int kh, int kw, int stride, int pad, uint64_t *out, void *stream);
 /* Batch of B images: in [abits][B][H][W][bs_words_per_row(C)], out [abits][B*OH*OW][bs_words_per_row(Kl)]
- * (column = image * OH*OW + output pixel); everything else as bs_im2col_interleaved (B = 1). */
+ * (column = image * OH*OW + output pixel); everything else as bs_im2col_interleaved (B = 1).
+ * The copy moves whole 32-bit words and does not look inside them, so any map whose pixels are runs of 32-bit
+ * words can be lowered with it: a feature map already unpacked to E2M1 codes by bs_unpack_planes_fp4 (16 bytes
+ * per 32 channels, C a multiple of 32) is a one-plane map of 4 C bit-channels, and its lowering is the
+ * [B*OH*OW][Kl / 2 bytes] code matrix that bs_gemm_fp4* takes (call with abits = 1 and 4 C for C). */
 bs_status bs_im2col_interleaved_batch(const uint64_t *in, int abits, int B, int H, int W, int C, int kh, int kw,
                                       int stride, int pad, uint64_t *out, void *stream);
 
