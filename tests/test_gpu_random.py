@@ -117,3 +117,48 @@ def test_random_convolution_and_pooling(seed):
         Y = oracle.threshold(Cmat, thr).T.reshape(OH, OW, F)
         pooled = bs.bs_maxpool_packed(out, OH, OW, F, pk, ps)
         assert_equal(planes_to_numpy(pooled), oracle.pack(oracle.maxpool(Y, pk, ps).reshape(-1, F), obits, U), "bs_maxpool_packed " + what)
+
+
+@pytest.mark.parametrize("seed", range(300, 364))
+def test_random_large_shapes(seed):
+    """Shapes beyond the sweep above, so that every tile configuration and both few-column kernels are drawn: mid-sized
+    squares (32 x 16, 32 x 32 and 64 x 64 tiles), many rows with 1..40 columns, few rows with many columns.  Bit-serial
+    and both matrix-core engines, int32 product and fused thresholds."""
+    rng = np.random.default_rng([20240612, seed])
+    (w, wf), (a, af) = draw_operand(rng), draw_operand(rng)
+    regime = seed % 4
+    if regime == 0:
+        M, N = int(rng.integers(300, 1600)), int(rng.integers(300, 1600))
+    elif regime == 1:
+        M, N = int(rng.integers(1000, 20000)), int(rng.integers(1, 40))
+    elif regime == 2:
+        M, N = int(rng.integers(1, 400)), int(rng.integers(500, 8000))
+    else:
+        M, N = int(rng.integers(200, 1200)), int(rng.integers(200, 1200))
+    K = int(rng.choice([32, 64, 96, 1024, 2048, 2400])) if rng.random() < 0.5 else int(rng.integers(1, 2500))
+    K = max(1, min(K, int(2.5e9 / (M * N))))          # keeps the oracle's product to a few seconds
+    obits = int(rng.integers(1, 5))
+    W, A = draw(rng, (M, K), w, wf), draw(rng, (K, N), a, af)
+    C = oracle.gemm(W, A)
+    T = (1 << obits) - 1
+    thr = np.sort(rng.integers(int(C.min()) - 2, int(C.max()) + 3, size=(M, T)), axis=1).astype(np.int32)
+    want = oracle.threshold_pack(C, thr, obits)
+    what = "seed %d W%d(%d)A%d(%d) %dx%dx%d o=%d" % (seed, w, wf, a, af, M, K, N, obits)
+    Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
+    Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
+    assert_equal(bs.bs_gemm(Wp, FMT[wf], Ap, FMT[af], K).cpu().numpy(), C, "bs_gemm " + what)
+    out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
+    bs.bs_gemm_threshold(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits, out=out)
+    assert_equal(planes_to_numpy(out), want, "bs_gemm_threshold " + what)
+    W8, A8 = bs.bs_unpack_planes(Wp, FMT[wf], K), bs.bs_unpack_planes(Ap, FMT[af], K)
+    assert_equal(bs.bs_gemm_i8(W8, A8, K).cpu().numpy(), C, "bs_gemm_i8 " + what)
+    out.fill_(-1)
+    bs.bs_gemm_i8_threshold(W8, A8, K, dev(thr), obits, out=out)
+    assert_equal(planes_to_numpy(out), want, "bs_gemm_i8_threshold " + what)
+    rep = lambda b, f: b <= 2 or (b == 3 and f == TC)
+    if rep(w, wf) and rep(a, af):
+        W4, A4 = bs.bs_unpack_planes_fp4(Wp, FMT[wf], K), bs.bs_unpack_planes_fp4(Ap, FMT[af], K)
+        assert_equal(bs.bs_gemm_fp4(W4, A4, K).cpu().numpy(), C, "bs_gemm_fp4 " + what)
+        out.fill_(-1)
+        bs.bs_gemm_fp4_threshold(W4, A4, K, dev(thr), obits, out=out)
+        assert_equal(planes_to_numpy(out), want, "bs_gemm_fp4_threshold " + what)
