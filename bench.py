@@ -29,8 +29,15 @@ CLOCKS_PER_PRODUCT = 6
 BINARY_PEAK_TOPS = CUS * SIMDS_PER_CU * LANES * 32 * 2 / CLOCKS_PER_PRODUCT * CLOCK_HZ / 1e12   # 1677.7
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per bs_gemm launch on the W2A2 4096^3 workload, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE scaled by a 256 MiB copy (profiles/pmc_fetch_write_w2a2_4096.md): 24.5 MiB + 64 MiB
+# WRITE_SIZE scaled by a 256 MiB copy (profiles/pmc_fetch_write_w2a2_4096.md): 24.5 MiB + 64 MiB.  A counter run
+# cannot be made from inside this script; the figure is the one of the committed profile and is labelled as such.
 GEMM_TRAFFIC_BYTES = 92_989_771
+GEMM_TRAFFIC_SOURCE = "profiles/pmc_fetch_write_w2a2_4096.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE of an earlier run of this command; not re-measured in this run)"
+# untimed GEMM launches before the warm-up steps (see main)
+CLOCK_WARMUP_LAUNCHES = 100
+# the inner loop's AND / popcount / idle-slot rhythm is worth 4..16 % and rests on how the compiler spaces dependent
+# instructions; below this fraction of the in-run probe rate the line says so ("rhythm_ok": false)
+RHYTHM_MIN_FRACTION_OF_PROBE = 0.80
 
 
 def main() -> int:
@@ -43,6 +50,11 @@ def main() -> int:
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line, run the W1A1 size sweep of Sec. 4.1.2 (every dimension "
                          "from 2^6 to 2^12) and print one JSON line per (M, K, N)")
+    ap.add_argument("--only", choices=["gemv", "dense", "planes"], default=None,
+                    help="run one kernel family only, with plain launches and a short JSON line: the few-column "
+                         "(batch-1) kernels, the matrix-core kernels on unpacked operands, or the matrix-core "
+                         "kernels on packed planes; meant to be run under rocprofv3")
+    ap.add_argument("--case", default=None, help="with --only: run this one case (see the names in the printed line)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run plain 256 MiB device copies, so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
                          "readings can be scaled by what the same counter reports for a copy of known size")
@@ -81,6 +93,9 @@ def main() -> int:
 
     if args.sweep:
         return sweep(bs, torch)
+    if args.only:
+        print(json.dumps(only(args.only, args.case, bs, torch, timed)))
+        return 0
 
     if args.calibration_copy:
         src = torch.full((256 << 20,), 3, dtype=torch.uint8, device="cuda")
@@ -99,15 +114,17 @@ def main() -> int:
     Ap = torch.empty((a, N, bs.bs_words_per_row(K)), dtype=torch.int64, device="cuda")
     C = torch.empty((M, N), dtype=torch.int32, device="cuda")
 
+    BSER = bs.BS_ENGINE_BITSERIAL   # the headline is the AND-popcount kernel (Alg. 1, 2), whatever bs_gemm itself would pick
+
     def step():
         bs.bs_pack_planes(Ad, a, bs.BS_UNSIGNED, depth_is_strided=True, out=Ap)
-        bs.bs_gemm(Wp, bs.BS_TWOS_COMPLEMENT, Ap, bs.BS_UNSIGNED, K, out=C)
+        bs.bs_gemm(Wp, bs.BS_TWOS_COMPLEMENT, Ap, bs.BS_UNSIGNED, K, out=C, engine=BSER)
 
     # The device leaves its idle clocks only after tens of milliseconds of work (measured: 0.451 ms per step over 20
     # steps after a 3-step warm-up, 0.410 ms over 200): set-up ends with 100 untimed GEMM launches (about 40 ms), so
     # that the W warm-up steps and the K timed steps run at the clocks of a busy device whatever W and K are.
-    for _ in range(100):
-        bs.bs_gemm(Wp, bs.BS_TWOS_COMPLEMENT, Ap, bs.BS_UNSIGNED, K, out=C)
+    for _ in range(CLOCK_WARMUP_LAUNCHES):
+        bs.bs_gemm(Wp, bs.BS_TWOS_COMPLEMENT, Ap, bs.BS_UNSIGNED, K, out=C, engine=BSER)
     torch.cuda.synchronize()
     ev_ms, wall_ms = timed(step, args.steps, args.warmup)
     ms_per_step = max(ev_ms, wall_ms)
@@ -121,12 +138,12 @@ def main() -> int:
     for i in range(args.steps):
         bs.bs_pack_planes(Ad, a, bs.BS_UNSIGNED, depth_is_strided=True, out=Ap)
         ev_a[i].record()
-        bs.bs_gemm(Wp, bs.BS_TWOS_COMPLEMENT, Ap, bs.BS_UNSIGNED, K, out=C)
+        bs.bs_gemm(Wp, bs.BS_TWOS_COMPLEMENT, Ap, bs.BS_UNSIGNED, K, out=C, engine=BSER)
         ev_b[i].record()
     torch.cuda.synchronize()
     gemm_ms = sum(x.elapsed_time(y) for x, y in zip(ev_a, ev_b)) / args.steps
     # and alone, back to back (no packing kernel in between: warmer caches, steadier clock)
-    gemm_alone_ms, _ = timed(lambda: bs.bs_gemm(Wp, bs.BS_TWOS_COMPLEMENT, Ap, bs.BS_UNSIGNED, K, out=C), args.steps, 2)
+    gemm_alone_ms, _ = timed(lambda: bs.bs_gemm(Wp, bs.BS_TWOS_COMPLEMENT, Ap, bs.BS_UNSIGNED, K, out=C, engine=BSER), args.steps, 2)
     pack_ms, _ = timed(lambda: bs.bs_pack_planes(Ad, a, bs.BS_UNSIGNED, depth_is_strided=True, out=Ap), args.steps, 2)
     binary_tops = w * a * 2.0 * M * N * K / (gemm_ms * 1e-3) / 1e12
 
@@ -140,17 +157,21 @@ def main() -> int:
 
     result = {
         "metric": "bit-serial GEMM GOPS (2*M*N*K/T), W2A2", "value": round(gops, 1), "unit": "GOPS",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "clock_warmup_launches": CLOCK_WARMUP_LAUNCHES,
+        "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32", "dtype_note": "32-bit AND + popcount on bit planes, int32 accumulation",
         "data": "synthetic",
         "config": {"workload": "W2A2 4096x4096x4096: pack int8 activations (K x N) to bit planes + bit-serial "
-                               "GEMM to int32; weights pre-packed", "M": M, "N": N, "K": K, "wbits": w, "abits": a},
+                               "GEMM (AND-popcount engine) to int32; weights pre-packed", "M": M, "N": N, "K": K,
+                   "wbits": w, "abits": a, "engine": "bit-serial (bs_gemm_on); bs_gemm itself picks the fp4 matrix-core "
+                                                      "kernel for this shape, see other_configs.engines_on_packed_planes"},
         "roofline": {"bound": "alu", "kernel": "bs_gemm_kernel<2,2,...>", "achieved": round(binary_tops, 1),
                      "peak": round(BINARY_PEAK_TOPS, 1), "unit": "binary TOP/s", "frac": round(binary_tops / BINARY_PEAK_TOPS, 4),
                      "measured_peak": round(measured_peak_tops, 1),
                      "frac_of_measured_peak": round(binary_tops / measured_peak_tops, 4),
+                     "rhythm_ok": bool(binary_tops >= RHYTHM_MIN_FRACTION_OF_PROBE * measured_peak_tops),
                      "kernel_ms": round(gemm_ms, 4), "kernel_ms_back_to_back": round(gemm_alone_ms, 4),
-                     "traffic": GEMM_TRAFFIC_BYTES,
+                     "traffic": GEMM_TRAFFIC_BYTES, "traffic_source": GEMM_TRAFFIC_SOURCE,
                      "algorithmic_bytes": 2 * (w * M * K // 8) // 1 + 4 * M * N},
         "breakdown_ms": {"pack_activations": round(pack_ms, 4), "bs_gemm": round(gemm_ms, 4)},
     }
@@ -173,6 +194,8 @@ def main() -> int:
         dt = (time.perf_counter() - t0) / reps
         result["cpu_baseline"] = {"value": round(2.0 * M * N * K / dt / 1e9, 1), "unit": "GOPS",
                                   "cores": oracle.num_threads(), "kind": "oracle",
+                                  "compile_flags": "gcc " + " ".join(oracle.COMPILE_FLAGS) + " (built where there is no GPU, "
+                                                   "hence no -march=native: the host's widest vectors are not used)",
                                   "sample": "the full 4096^3 integer product (no packing), mean of %d runs, %.2f s each"
                                             % (reps, dt)}
         # the oracle on the small configurations, once each (milliseconds), beside the GPU times below
@@ -188,6 +211,11 @@ def main() -> int:
             "conv2_W1A2_direct_convolution_and_thresholds": once(lambda: oracle.threshold(
                 oracle.conv_direct(c4["x"], c4["filt"], c4["stride"], c4["pad"]).reshape(-1, c4["filt"].shape[0]).T.copy(),
                 c4["thr"]))}
+        for n5 in (1, 64, 1024, 8192):   # W4A4 8192 x 8192 x N: integer product + 15 thresholds per row
+            c5 = workloads.cfg5_w4a4(n5)
+            result["cpu_baseline"]["other_configs_ms"]["W4A4_8192x8192x%d_product_and_thresholds" % n5] = once(
+                lambda: oracle.threshold(oracle.gemm(c5["W"], c5["A"]), c5["thr"]))
+            del c5
 
     # ------------------------------------------------------------- other configurations, per kernel
     if not args.no_extras:
@@ -217,6 +245,98 @@ def sweep(bs, torch):
                 best[K] = (min(lo, gops), max(hi, gops))
     print(json.dumps({"sweep_summary_GOPS_min_max_by_depth": {str(k): [round(v[0], 1), round(v[1], 1)] for k, v in best.items()}}))
     return 0
+
+
+def only(which, case, bs, torch, timed):
+    """One kernel family with plain launches (a counter run of rocprofv3 sees one dispatch per launch and the kernel
+    names stay apart when a single case is selected with --case).  Times are HIP-event averages over the launches."""
+    BP, U, TC = bs.BS_BIPOLAR, bs.BS_UNSIGNED, bs.BS_TWOS_COMPLEMENT
+    BSER = bs.BS_ENGINE_BITSERIAL
+    res = {"only": which, "cases": {}}
+
+    def planes(bits, rows, K):
+        return torch.randint(-2 ** 62, 2 ** 62, (bits, rows, bs.bs_words_per_row(K)), dtype=torch.int64, device="cuda")
+
+    def thr_for(Mrows, obits):
+        T = (1 << obits) - 1
+        return torch.sort(torch.randint(-1000, 1000, (Mrows, T), dtype=torch.int32, device="cuda"), dim=1)[0].contiguous()
+
+    def run(name, fns, rounds):
+        if case and case != name:
+            return
+        for f in fns[:2]:
+            f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(rounds):
+            for f in fns:
+                f()
+        e1.record()
+        torch.cuda.synchronize()
+        res["cases"][name] = {"us_per_launch": round(e0.elapsed_time(e1) * 1e3 / (rounds * len(fns)), 2),
+                              "launches": rounds * len(fns)}
+
+    if which == "gemv":
+        # (name, w, wfmt, a, M, K, obits, weight buffers cycled): cold = more bytes than the 256 MiB last-level cache
+        for (name, w, wf, a, M, K, ob, copies) in [
+                ("fc6_W1A2_4096x9216x1_cold", 1, BP, 2, 4096, 9216, 2, 96), ("fc6_W1A2_4096x9216x1_warm", 1, BP, 2, 4096, 9216, 2, 1),
+                ("fc7_W1A2_4096x4096x1_cold", 1, BP, 2, 4096, 4096, 2, 192), ("fc7_W1A2_4096x4096x1_warm", 1, BP, 2, 4096, 4096, 2, 1),
+                ("W4A4_8192x8192x1_cold", 4, TC, 4, 8192, 8192, 4, 12), ("W4A4_8192x8192x1_warm", 4, TC, 4, 8192, 8192, 4, 1),
+                ("W1A2_32768x32768x1_cold", 1, BP, 2, 32768, 32768, 2, 3)]:
+            if case and not case.startswith(name):
+                continue
+            Wps = [planes(w, M, K) for _ in range(copies)]
+            Ap, th = planes(a, 1, K), thr_for(M, ob)
+            Y = torch.empty((ob, 1, bs.bs_words_per_row(M)), dtype=torch.int64, device="cuda")
+            sink = torch.zeros(1024, dtype=torch.int32, device="cuda")
+            rounds = 100 if copies == 1 else 3
+            run(name, [(lambda Wp=Wp: bs.bs_gemm_threshold(Wp, wf, Ap, U, K, th, ob, out=Y, engine=BSER)) for Wp in Wps], rounds)
+            run(name + "_stream_read_probe", [(lambda Wp=Wp: bs.bs_probe_stream_read(Wp, sink)) for Wp in Wps], rounds)
+            run(name + "_stream_read_probe_nontemporal", [(lambda Wp=Wp: bs.bs_probe_stream_read(Wp, sink, non_temporal=True)) for Wp in Wps], rounds)
+            del Wps
+    elif which == "dense":
+        for (name, fp4, M, N, K, ob) in [("dense_int8_4096", False, 4096, 4096, 4096, 0), ("dense_int8_8192_fused4", False, 8192, 8192, 8192, 4),
+                                         ("dense_fp4_4096", True, 4096, 4096, 4096, 0), ("dense_fp4_8192_fused2", True, 8192, 8192, 8192, 2)]:
+            if case and case != name:
+                continue
+            if fp4:
+                Wd = torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device="cuda") & 0x55
+                Ad = torch.randint(0, 256, (N, K // 2), dtype=torch.uint8, device="cuda") & 0x55
+            else:
+                Wd = torch.randint(-8, 8, (M, K), dtype=torch.int8, device="cuda")
+                Ad = torch.randint(0, 16, (N, K), dtype=torch.int8, device="cuda")
+            if ob:
+                th = thr_for(M, ob)
+                Y = torch.empty((ob, N, bs.bs_words_per_row(M)), dtype=torch.int64, device="cuda")
+                f = (lambda: bs.bs_gemm_fp4_threshold(Wd, Ad, K, th, ob, out=Y)) if fp4 else (lambda: bs.bs_gemm_i8_threshold(Wd, Ad, K, th, ob, out=Y))
+            else:
+                C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+                f = (lambda: bs.bs_gemm_fp4(Wd, Ad, K, out=C)) if fp4 else (lambda: bs.bs_gemm_i8(Wd, Ad, K, out=C))
+            for _ in range(30):
+                f()                        # clocks
+            run(name, [f], 20)
+    else:
+        for (name, e, w, a, M, N, K, ob) in [("planes_fp4_W2A2_4096", bs.BS_ENGINE_DENSE_FP4, 2, 2, 4096, 4096, 4096, 0),
+                                             ("planes_fp4_W1A2_4096_fused2", bs.BS_ENGINE_DENSE_FP4, 1, 2, 4096, 4096, 4096, 2),
+                                             ("planes_int8_W4A4_8192_fused4", bs.BS_ENGINE_DENSE_I8, 4, 4, 8192, 8192, 8192, 4),
+                                             ("planes_int8_W2A2_4096", bs.BS_ENGINE_DENSE_I8, 2, 2, 4096, 4096, 4096, 0),
+                                             ("bitserial_W2A2_4096", BSER, 2, 2, 4096, 4096, 4096, 0)]:
+            if case and case != name:
+                continue
+            wf = BP if w == 1 else TC
+            Wq, Aq = planes(w, M, K), planes(a, N, K)
+            if ob:
+                th = thr_for(M, ob)
+                Y = torch.empty((ob, N, bs.bs_words_per_row(M)), dtype=torch.int64, device="cuda")
+                f = lambda: bs.bs_gemm_threshold(Wq, wf, Aq, U, K, th, ob, out=Y, engine=e)
+            else:
+                C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+                f = lambda: bs.bs_gemm(Wq, wf, Aq, U, K, out=C, engine=e)
+            for _ in range(30):
+                f()
+            run(name, [f], 20)
+    return res
 
 
 def timed_graph(fn_list, reps):
@@ -264,13 +384,16 @@ def extras(bs, workloads, dev, timed):
         T = (1 << obits) - 1
         return torch.sort(torch.randint(-1000, 1000, (Mrows, T), dtype=torch.int32, device="cuda"), dim=1)[0].contiguous()
 
-    def fused(name, w, wf, a, af, M, N, K, obits, copies=1, reps=None):
+    BSER = bs.BS_ENGINE_BITSERIAL
+
+    def fused(name, w, wf, a, af, M, N, K, obits, copies=1, reps=None, stream_probe=False):
         # `copies` distinct weight buffers are cycled through so that the weights of a small
-        # layer do not simply sit in the last-level cache (256 MB) from the previous launch
+        # layer do not simply sit in the last-level cache (256 MB) from the previous launch.
+        # These rows time the AND-popcount kernels (engine named explicitly).
         Wps = [planes(w, M, K) for _ in range(copies)]
         Ap, th = planes(a, N, K), thr_for(M, obits)
         Y = torch.empty((obits, N, bs.bs_words_per_row(M)), dtype=torch.int64, device="cuda")
-        fns = [(lambda Wp=Wp: bs.bs_gemm_threshold(Wp, wf, Ap, af, K, th, obits, out=Y)) for Wp in Wps]
+        fns = [(lambda Wp=Wp: bs.bs_gemm_threshold(Wp, wf, Ap, af, K, th, obits, out=Y, engine=BSER)) for Wp in Wps]
         work = 2.0 * M * N * K
         if work > 1e12:                       # long kernels: plain back-to-back launches
             ms, _ = timed(fns[0], 10, 2)
@@ -280,15 +403,24 @@ def extras(bs, workloads, dev, timed):
         out[name] = {"us": round(ms * 1e3, 2), "GOPS": round(work / ms / 1e6, 1),
                      "frac_of_valu_popcount_peak": round(w * a * work / (ms * 1e-3) / 1e12 / BINARY_PEAK_TOPS, 4),
                      "GBps": round(byts / ms / 1e6, 1), "frac_of_hbm_peak": round(byts / ms / 1e6 / HBM_PEAK_GBS, 4),
-                     "weight_buffers_cycled": copies}
+                     "weight_buffers_cycled": copies, "weight_bytes_cycled": copies * Wps[0].numel() * 8}
+        if stream_probe:
+            # the measured floor: a plain streaming read of the same weight buffers, cycled the same way (the
+            # shortest time in which a kernel of this library brings that many bytes in from where they lie)
+            sink = torch.zeros(1024, dtype=torch.int32, device="cuda")
+            for nt in (False, True):
+                pf = [(lambda Wp=Wp: bs.bs_probe_stream_read(Wp, sink, non_temporal=nt)) for Wp in Wps]
+                pms = timed_graph(pf, reps or max(2 * copies, 20))
+                out[name]["stream_read_of_the_weights_us" + ("_nontemporal" if nt else "")] = round(pms * 1e3, 2)
 
     BP, U, TC = bs.BS_BIPOLAR, bs.BS_UNSIGNED, bs.BS_TWOS_COMPLEMENT
-    fused("fc6_W1A2_4096x9216x1_cold", 1, BP, 2, U, 4096, 1, 9216, 2, copies=64)
-    fused("fc7_W1A2_4096x4096x1_cold", 1, BP, 2, U, 4096, 1, 4096, 2, copies=128)
+    # "cold": more weight bytes cycled than the 256 MiB last-level cache holds (432, 384 and 384 MiB)
+    fused("fc6_W1A2_4096x9216x1_cold", 1, BP, 2, U, 4096, 1, 9216, 2, copies=96, stream_probe=True)
+    fused("fc7_W1A2_4096x4096x1_cold", 1, BP, 2, U, 4096, 1, 4096, 2, copies=192, stream_probe=True)
     fused("fc6_W1A2_4096x9216x1_warm", 1, BP, 2, U, 4096, 1, 9216, 2, copies=1)
     fused("conv2_W1A2_256x2400x729", 1, BP, 2, U, 256, 729, 2400, 2)
-    fused("W4A4_8192x8192x1_cold", 4, TC, 4, U, 8192, 1, 8192, 4, copies=10)
-    fused("W4A4_8192x8192x1_warm", 4, TC, 4, U, 8192, 1, 8192, 4, copies=1)
+    fused("W4A4_8192x8192x1_cold", 4, TC, 4, U, 8192, 1, 8192, 4, copies=12, stream_probe=True)
+    fused("W4A4_8192x8192x1_warm", 4, TC, 4, U, 8192, 1, 8192, 4, copies=1, stream_probe=True)
     for n in (64, 1024, 8192):
         fused("W4A4_8192x8192x%d" % n, 4, TC, 4, U, 8192, n, 8192, 4)
     # compute-bound rate against precision (Sec. 4.1.1 of the paper lists W1A1, W1A2, W1A3, W2A2, W2A3): 4096^3,
@@ -298,13 +430,61 @@ def extras(bs, workloads, dev, timed):
         Wq, Aq = planes(w_, 4096, 4096), planes(a_, 4096, 4096)
         Cq = torch.empty((4096, 4096), dtype=torch.int32, device="cuda")
         wf_ = BP if w_ == 1 else TC
-        ms, _ = timed(lambda: bs.bs_gemm(Wq, wf_, Aq, U, 4096, out=Cq), 10, 3)
+        ms, _ = timed(lambda: bs.bs_gemm(Wq, wf_, Aq, U, 4096, out=Cq, engine=BSER), 10, 3)
         gops = 2.0 * 4096 ** 3 / ms / 1e6
         sweep_p["W%dA%d" % (w_, a_)] = {"us": round(ms * 1e3, 1), "GOPS": round(gops, 1), "GOPS_x_w_x_a": round(gops * w_ * a_, 1),
                                         "frac_of_valu_popcount_peak": round(gops * w_ * a_ / 1e3 / BINARY_PEAK_TOPS, 4)}
     out["precision_sweep_4096x4096x4096"] = sweep_p
     # a GEMV large enough that launch and first-byte latency stop mattering
-    fused("W1A2_32768x32768x1_cold", 1, BP, 2, U, 32768, 1, 32768, 2, copies=3, reps=12)
+    fused("W1A2_32768x32768x1_cold", 1, BP, 2, U, 32768, 1, 32768, 2, copies=3, reps=12, stream_probe=True)
+    # The per-layer choice of Sec. 4.1.1 / 4.2 as the library makes it on PACKED PLANES: the same call on the
+    # AND-popcount kernels, on the two matrix-core kernels that expand plane bits in their loader, and as bs_gemm /
+    # bs_gemm_threshold pick by themselves; beside them the matrix-core kernels on operands unpacked beforehand
+    # (bs_gemm_fp4 / bs_gemm_i8: the caller's buffers, unpack time not counted).
+    eng = {}
+    names = {bs.BS_ENGINE_BITSERIAL: "bitserial", bs.BS_ENGINE_DENSE_I8: "dense_int8", bs.BS_ENGINE_DENSE_FP4: "dense_fp4",
+             bs.BS_ENGINE_AUTO: "auto"}
+    for (w_, a_, M_, N_, K_, ob_) in [(2, 2, 4096, 4096, 4096, 0), (2, 2, 4096, 4096, 4096, 2), (1, 2, 4096, 4096, 4096, 2),
+                                       (1, 1, 4096, 4096, 4096, 0), (4, 4, 8192, 8192, 8192, 4), (4, 4, 8192, 1024, 8192, 4),
+                                       (4, 4, 8192, 64, 8192, 4), (1, 2, 384, 10816, 2304, 2), (2, 2, 1024, 1024, 4096, 2)]:
+        wf_ = BP if w_ == 1 else TC
+        af_ = BP if (w_ == 1 and a_ == 1) else U
+        Wq, Aq = planes(w_, M_, K_), planes(a_, N_, K_)
+        if ob_:
+            th_ = thr_for(M_, ob_)
+            Yq = torch.empty((ob_, N_, bs.bs_words_per_row(M_)), dtype=torch.int64, device="cuda")
+            call = lambda e: bs.bs_gemm_threshold(Wq, wf_, Aq, af_, K_, th_, ob_, out=Yq, engine=e)
+        else:
+            Cq = torch.empty((M_, N_), dtype=torch.int32, device="cuda")
+            call = lambda e: bs.bs_gemm(Wq, wf_, Aq, af_, K_, out=Cq, engine=e)
+        row = {}
+        engines = [bs.BS_ENGINE_BITSERIAL, bs.BS_ENGINE_DENSE_I8] + ([bs.BS_ENGINE_DENSE_FP4] if max(w_, a_) <= 2 else []) \
+            + [bs.BS_ENGINE_AUTO]
+        for e in engines:
+            if 2.0 * M_ * N_ * K_ * (w_ * a_ if e == bs.BS_ENGINE_BITSERIAL else 1) > 2e12:
+                ms_e, _ = timed(lambda: call(e), 5, 2)
+            else:
+                ms_e = timed_graph([lambda: call(e)], 10)
+            row[names[e] + "_us"] = round(ms_e * 1e3, 2)
+        row["auto_picks"] = names[bs.bs_choose_engine(w_, wf_, a_, af_, M_, N_, K_)]
+        # reference: the same product from operands unpacked beforehand into the caller's buffers
+        if max(w_, a_) <= 2:
+            W4q, A4q = bs.bs_unpack_planes_fp4(Wq, wf_, K_), bs.bs_unpack_planes_fp4(Aq, af_, K_)
+            ref = (lambda: bs.bs_gemm_fp4_threshold(W4q, A4q, K_, th_, ob_, out=Yq)) if ob_ else (lambda: bs.bs_gemm_fp4(W4q, A4q, K_, out=Cq))
+            row["dense_fp4_on_unpacked_operands_us"] = round(timed_graph([ref], 10) * 1e3, 2)
+            del W4q, A4q
+        else:
+            W8q, A8q = bs.bs_unpack_planes(Wq, wf_, K_), bs.bs_unpack_planes(Aq, af_, K_)
+            ref = (lambda: bs.bs_gemm_i8_threshold(W8q, A8q, K_, th_, ob_, out=Yq)) if ob_ else (lambda: bs.bs_gemm_i8(W8q, A8q, K_, out=Cq))
+            row["dense_int8_on_unpacked_operands_us"] = round((timed(ref, 5, 2)[0] if 2.0 * M_ * N_ * K_ > 2e12 else timed_graph([ref], 10)) * 1e3, 2)
+            del W8q, A8q
+        best = min((v, k) for k, v in row.items() if k.endswith("_us") and "unpacked" not in k and not k.startswith("auto"))
+        row["fastest_on_planes"] = best[1][:-3]
+        flops = 2.0 * M_ * N_ * K_
+        row["auto_GOPS"] = round(flops / row["auto_us"] / 1e3, 1)
+        eng["W%dA%d_%dx%dx%d_%s" % (w_, a_, M_, K_, N_, ("fused_%dbit_out" % ob_) if ob_ else "int32_out")] = row
+        del Wq, Aq
+    out["engines_on_packed_planes"] = eng
     # the W1A2 layers of the paper's AlexNet (Table 2) as one packed chain, batch 1:
     # conv2 (fused lowering + GEMM + thresholds) -> pool -> conv3 -> conv4 -> conv5 -> pool -> fc6 -> fc7
     xin, layers = workloads.alexnet_inner()

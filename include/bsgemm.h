@@ -92,12 +92,32 @@ bs_status bs_pack_planes(const void *src, bs_dtype dtype, int64_t rows, int64_t 
  *   Ap  device, planes [abits][N][S]
  *   C   device int32 [M][ldc], ldc >= N, OVERWRITTEN (not accumulated into)
  * Errors: INVALID_ARG; UNSUPPORTED (bits > 4); ALIGNMENT (planes 16 B, C 4 B);
- * OVERFLOW_RISK if K * 2^(wbits+abits) >= 2^31 (bounds every partial sum) or an operand
- * exceeds 2^31 32-bit words; LAUNCH.
+ * OVERFLOW_RISK if K * max|w| * max|a| >= 2^31 (max|v| of a format: unsigned 2^bits - 1, two's
+ * complement 2^(bits-1), bipolar 1: no result can then leave the int32 range; partial sums are
+ * taken modulo 2^32, which does not change an in-range result) or an operand exceeds 2^31 32-bit
+ * words; LAUNCH.
+ *
+ * Engine (Sec. 4.1.1, 4.2: each layer runs on the faster of a bit-serial and a byte-wise engine).
+ * bs_gemm, bs_gemm_threshold and the bs_conv_threshold calls take PACKED PLANES and choose per
+ * call, with bs_choose_engine's time model, between the AND-popcount kernels (Alg. 1, 2) and a
+ * matrix-core kernel whose loader expands the plane bits to int8 or 4-bit floating-point codes
+ * on the way to on-chip memory (nothing unpacked is ever written to device memory, no extra
+ * buffer or launch).  All engines return identical results.  bs_gemm_on / bs_gemm_threshold_on
+ * take the engine as an argument: BS_ENGINE_BITSERIAL is Alg. 2 as printed, whatever the shape.
  */
 bs_status bs_gemm(const uint64_t *Wp, int wbits, bs_format wfmt,
                   const uint64_t *Ap, int abits, bs_format afmt,
                   int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc, void *stream);
+
+typedef enum { BS_ENGINE_BITSERIAL = 0, BS_ENGINE_DENSE_I8 = 1, BS_ENGINE_DENSE_FP4 = 2, BS_ENGINE_AUTO = 3 } bs_engine;
+
+/* bs_gemm on a named engine.  BS_ENGINE_AUTO is bs_gemm.  BS_ENGINE_DENSE_FP4 needs operands whose
+ * values are all numbers of the E2M1 format (at most 2 bits, or 3-bit two's complement) and
+ * K * max|w| * max|a| < 2^24; a dense engine that cannot take the call returns BS_ERR_UNSUPPORTED
+ * (nothing is launched).  Other arguments and errors as bs_gemm. */
+bs_status bs_gemm_on(bs_engine engine, const uint64_t *Wp, int wbits, bs_format wfmt,
+                     const uint64_t *Ap, int abits, bs_format afmt,
+                     int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc, void *stream);
 
 /*
  * Approximate product from the higher-order bits only (the approximate-computing use the
@@ -132,6 +152,11 @@ bs_status bs_gemm_threshold(const uint64_t *Wp, int wbits, bs_format wfmt,
                             const uint64_t *Ap, int abits, bs_format afmt,
                             int64_t M, int64_t N, int64_t K,
                             const int32_t *thr, int obits, uint64_t *Yp, void *stream);
+/* bs_gemm_threshold on a named engine (see bs_gemm_on). */
+bs_status bs_gemm_threshold_on(bs_engine engine, const uint64_t *Wp, int wbits, bs_format wfmt,
+                               const uint64_t *Ap, int abits, bs_format afmt,
+                               int64_t M, int64_t N, int64_t K,
+                               const int32_t *thr, int obits, uint64_t *Yp, void *stream);
 
 /*
  * Channel-interleaved lowering on packed data (Sec. 3.2): one im2col per
@@ -294,11 +319,11 @@ bs_status bs_streamline_thresholds(const double *t, int T, const double *a, cons
  * N <= 4 is always bit-serial (weights are read once: wbits/8 byte per weight instead of 1 or 1/2).
  * Invalid arguments (bits outside 1..4, bipolar with bits != 1, non-positive sizes) return BS_ENGINE_BITSERIAL.
  */
-typedef enum { BS_ENGINE_BITSERIAL = 0, BS_ENGINE_DENSE_I8 = 1, BS_ENGINE_DENSE_FP4 = 2 } bs_engine;
 bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_format afmt, int64_t M, int64_t N, int64_t K);
 
 /*
- * Diagnostic: rate probe for the instruction pair of Alg. 1's inner loop (AND, popcount-accumulate).
+ * Diagnostic, not part of the versioned interface (bs_version does not cover it; it may change or go
+ * without notice): rate probe for the instruction pair of Alg. 1's inner loop (AND, popcount-accumulate).
  * Launches `workgroups` workgroups of 256 lanes; every lane executes passes * 16 AND and passes * 16
  * popcount-add instructions on registers (no memory traffic, one idle issue slot per pair as in the
  * GEMM's inner loop) and the workgroup stores one word to sink [workgroups] (device memory,
@@ -307,6 +332,17 @@ bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_format afmt,
  * measured ceiling that goes beside the theoretical VALU popcount peak.  Asynchronous on `stream`.
  */
 bs_status bs_probe_popcount_rate(uint32_t *sink, int workgroups, int passes, void *stream);
+
+/*
+ * Diagnostic, not part of the versioned interface: streaming read of `bytes` bytes (a multiple of 16) from src
+ * (device, 16-byte aligned) with 16-byte loads, four in flight per lane, `workgroups` workgroups of 256 lanes each
+ * walking 16 KiB slices round-robin; every workgroup XORs what it read into sink [workgroups] (device, caller-owned,
+ * not cleared).  non_temporal != 0 reads with the non-temporal hint.  Timed by the caller on a buffer that is not in
+ * any cache, it gives the shortest time in which a kernel of this library can bring that many bytes from memory:
+ * the measured floor that goes beside the HBM peak for the few-column (batch-1) layers of Table 2.
+ */
+bs_status bs_probe_stream_read(const void *src, int64_t bytes, uint32_t *sink, int workgroups, int non_temporal,
+                               void *stream);
 
 const char *bs_status_string(bs_status s);
 int bs_version(void);

@@ -19,176 +19,11 @@
 // so the contraction is over matching depth indices whatever order the instruction uses
 // internally.  Accumulator register v of lane l is C[8 (v / 4) + 4 (l / 32) + v % 4][l % 32]
 // of its 32 x 32 tile.
-#include <type_traits>
-
-#include "bs_common.h"
+#include "bs_dense_common.h"
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-typedef float v16f __attribute__((ext_vector_type(16)));
-
-// Operand kinds.  I8: one int8 per depth index, v_mfma_i32_32x32x32_i8 (32 depth indices per
-// instruction).  FP4: two 4-bit E2M1 floating-point codes per byte (low nibble = even depth index),
-// v_mfma_f32_32x32x64_f8f6f4 with both formats set to fp4 (64 depth indices per instruction, the same
-// 16 operand bytes per lane, twice the int8 rate); every value of a <= 2-bit operand (and of a 3-bit
-// two's-complement one) is an E2M1 number, products and sums stay integers below 2^24, so the fp32
-// accumulators are exact and convert to int32 without rounding.  Lane l supplies the 16 bytes
-// [16 (l / 32), 16 (l / 32) + 16) of row l % 32 of the instruction's depth step in both kinds, and
-// the accumulator layout is the same.
-template <bool FP4> struct AccOf { using type = v16i; };
-template <> struct AccOf<true> { using type = v16f; };
-
-template <bool FP4>
-__device__ __forceinline__ typename AccOf<FP4>::type mma(v4i a, v4i b, typename AccOf<FP4>::type c)
-{
-    if constexpr (FP4) {
-        const v8i a8 = {a.x, a.y, a.z, a.w, 0, 0, 0, 0}, b8 = {b.x, b.y, b.z, b.w, 0, 0, 0, 0};
-        // format selectors 4 = fp4 for both operands; zero scale operands select the unscaled instruction
-        return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0, 0, 0);
-    } else {
-        return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
-    }
-}
-
-constexpr int DK = 64;        // depth bytes per row and stage
-constexpr int DROW = 80;      // LDS row stride in bytes (64 + 16 pad)
-constexpr int DCH = DK / 16;  // 16-byte chunks per row and stage
-
-struct DenseParams {
-    const int8_t *W;   // [M][ldw]
-    const int8_t *A;   // [N][lda]  (activations, depth-contiguous)
-    long long ldw, lda;
-    int M, N, K;       // K: depth in operand BYTES (int8: depth indices; fp4: half as many)
-    int32_t *C;
-    long long ldc;
-    const int32_t *thr;
-    int T, obits;
-    uint32_t *Y;
-    int Yd;
-    int gx, gy;        // tiles along N and M
-};
-
-// zero the bytes of a 16-byte chunk that lie at or beyond depth index K
-__device__ __forceinline__ uint4 mask_tail(uint4 v, int k, int K)
-{
-    if (k + 16 <= K) return v;
-    uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-        const int left = K - (k + 4 * d);  // valid bytes in this dword
-        if (left <= 0) w[d] = 0;
-        else if (left < 4) w[d] &= (1u << (8 * left)) - 1u;
-    }
-    return make_uint4(w[0], w[1], w[2], w[3]);
-}
-
-// Thresholding epilogue for OB output bits (T = 2^OB - 1 thresholds per row, Sec. 2.1.1): the
-// tile's thresholds go to LDS (the operand tiles are no longer needed), one row padded to a
-// power of two with INT_MAX (never reached, which also zeroes rows past M); every output is
-// compared with its row's T thresholds, the count's OB bits are placed at the row's position
-// of one 32-row word per plane, and the words leave as whole dwords.
-template <int OB, int WTM, int WTN, bool FP4, int WGM, int WGN>
-__device__ __forceinline__ void dense_threshold_planes(const DenseParams &p, typename AccOf<FP4>::type (&acc)[WTM][WTN],
-                                                       unsigned char *lds, int m0, int n0)
-{
-    constexpr int T = (1 << OB) - 1;
-    constexpr int TS = OB == 1 ? 1 : OB == 2 ? 4 : OB == 3 ? 8 : 16;  // table entries per row
-    constexpr int BM = 32 * WTM * WGM, NT = 64 * WGM * WGN;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WGN, wn = wave % WGN;
-    const int li = lane & 31, lg = lane >> 5;
-    __syncthreads();
-    int32_t *tl = reinterpret_cast<int32_t *>(lds);  // [BM][TS]
-    for (int it = tid; it < BM * TS; it += NT) {
-        const int r = it / TS, t = it % TS;
-        tl[it] = (m0 + r < p.M && t < T) ? p.thr[(long long)(m0 + r) * T + t] : 0x7fffffff;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int a = 0; a < WTM; ++a) {
-        const int rbase = (wm * WTM + a) * 32;  // first row of this 32-row band within the block tile
-        uint32_t word[WTN][OB];
-#pragma unroll
-        for (int b = 0; b < WTN; ++b)
-#pragma unroll
-            for (int pl = 0; pl < OB; ++pl) word[b][pl] = 0;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int rr = 8 * (v >> 2) + 4 * lg + (v & 3);
-            // one row's thresholds serve the WTN column tiles this lane holds
-            int th[TS];
-            if constexpr (TS == 1) {
-                th[0] = tl[rbase + rr];
-            } else {
-#pragma unroll
-                for (int q = 0; q < TS / 4; ++q) {
-                    const int4 t4 = reinterpret_cast<const int4 *>(tl)[(rbase + rr) * (TS / 4) + q];
-                    th[4 * q] = t4.x; th[4 * q + 1] = t4.y; th[4 * q + 2] = t4.z; th[4 * q + 3] = t4.w;
-                }
-            }
-#pragma unroll
-            for (int b = 0; b < WTN; ++b) {
-                const int c = (int)acc[a][b][v];
-                uint32_t y = 0;
-#pragma unroll
-                for (int e = 0; e < T; ++e)  // y += (c >= t): compare into the carry mask, add the carry
-                    asm("v_cmp_le_i32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, 0, %0, vcc" : "+v"(y) : "v"(c), "v"(th[e]) : "vcc");
-#pragma unroll
-                for (int pl = 0; pl < OB; ++pl) word[b][pl] |= ((y >> pl) & 1u) << rr;
-            }
-        }
-        // Row bands cover a multiple of 128 rows, i.e. at least the Yd words of a column, so
-        // every word (padding included) is written by some band; words beyond Yd (a 256-row
-        // tile over a shorter column) are dropped.
-        const int wi = (m0 + rbase) / 32;
-#pragma unroll
-        for (int b = 0; b < WTN; ++b) {
-            const int n = n0 + (wn * WTN + b) * 32 + li;
-            // the two half-wavefronts hold complementary rows of the same column
-#pragma unroll
-            for (int pl = 0; pl < OB; ++pl) word[b][pl] |= __shfl_xor(word[b][pl], 32);
-            if (lg == 0 && n < p.N && wi < p.Yd) {
-#pragma unroll
-                for (int pl = 0; pl < OB; ++pl) p.Y[((long long)pl * p.N + n) * p.Yd + wi] = word[b][pl];
-            }
-        }
-    }
-}
-
-// Epilogue shared by the two dense kernels: int32 store, or successive thresholding with
-// the packed-plane output.  `lds` is the (no longer needed) operand space of the caller.
-template <int WTM, int WTN, bool FUSE, bool FP4, int WGM = 2, int WGN = 2>
-__device__ __forceinline__ void dense_epilogue(const DenseParams &p, typename AccOf<FP4>::type (&acc)[WTM][WTN],
-                                               unsigned char *lds, int m0, int n0, int tile_m)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave / WGN, wn = wave % WGN;
-    const int li = lane & 31, lg = lane >> 5;
-    (void)tile_m;
-    if constexpr (!FUSE) {
-#pragma unroll
-        for (int a = 0; a < WTM; ++a)
-#pragma unroll
-            for (int b = 0; b < WTN; ++b) {
-                const int n = n0 + (wn * WTN + b) * 32 + li;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = m0 + (wm * WTM + a) * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-                    if (m < p.M && n < p.N) p.C[(long long)m * p.ldc + n] = (int)acc[a][b][v];
-                }
-            }
-    } else {
-        switch (p.obits) {  // uniform
-        case 1: dense_threshold_planes<1, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0); break;
-        case 2: dense_threshold_planes<2, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0); break;
-        case 3: dense_threshold_planes<3, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0); break;
-        default: dense_threshold_planes<4, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0); break;
-        }
-    }
-}
+using namespace bs::dense;
 
 template <int WTM, int WTN, bool FUSE, bool FP4>
 __global__ void __launch_bounds__(256)

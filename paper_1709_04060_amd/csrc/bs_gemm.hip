@@ -37,10 +37,23 @@ bs_status dispatch_wb(const GemmParams &g, int wbits, int abits, bool fuse, bool
     }
 }
 
-bs_status gemm_common(const uint64_t *Wp, int wbits, bs_format wfmt, const uint64_t *Ap, int abits, bs_format afmt,
-                      int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc,
+// |result| <= K * max|w| * max|a| must fit int32 (sums inside the kernels are taken modulo 2^32, which leaves an
+// in-range result unchanged).  The approximate mode sums a subset of the plane pairs, bounded by the unsigned ranges.
+bool result_may_overflow(int64_t K, int wbits, bs_format wfmt, int abits, bs_format afmt, bool subset_of_pairs)
+{
+    const int64_t mw = subset_of_pairs ? (int64_t(1) << wbits) - 1 : bs::max_abs(wbits, wfmt);
+    const int64_t ma = subset_of_pairs ? (int64_t(1) << abits) - 1 : bs::max_abs(abits, afmt);
+    const int64_t lim = int64_t(1) << 31;
+    return K >= lim || K * mw * ma >= lim;
+}
+
+bs_status gemm_common(bs_engine engine, const uint64_t *Wp, int wbits, bs_format wfmt, const uint64_t *Ap, int abits,
+                      bs_format afmt, int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc,
                       const int32_t *thr, int obits, uint64_t *Yp, bool fuse, void *stream, int min_shift = 0)
 {
+    if (engine != BS_ENGINE_BITSERIAL && engine != BS_ENGINE_DENSE_I8 && engine != BS_ENGINE_DENSE_FP4 &&
+        engine != BS_ENGINE_AUTO)
+        return BS_ERR_INVALID_ARG;
     if (!Wp || !Ap || M <= 0 || N <= 0 || K <= 0) return BS_ERR_INVALID_ARG;
     if (bs_status s = bs::check_bits_fmt(wbits, wfmt)) return s;
     if (bs_status s = bs::check_bits_fmt(abits, afmt)) return s;
@@ -54,8 +67,7 @@ bs_status gemm_common(const uint64_t *Wp, int wbits, bs_format wfmt, const uint6
         if (!C || ldc < N) return BS_ERR_INVALID_ARG;
         if (!bs::aligned(C, 4)) return BS_ERR_ALIGNMENT;
     }
-    // Conservative: bounds every partial sum of plane-pair terms, not only the result.
-    if ((K << (wbits + abits)) >= (int64_t(1) << 31)) return BS_ERR_OVERFLOW_RISK;
+    if (result_may_overflow(K, wbits, wfmt, abits, afmt, min_shift > 0)) return BS_ERR_OVERFLOW_RISK;
     const int64_t S = bs_words_per_row(K);
     const int64_t lim = int64_t(1) << 31;
     if (wbits * M * S * 2 >= lim || abits * N * S * 2 >= lim || M >= lim || N >= lim) return BS_ERR_OVERFLOW_RISK;
@@ -86,6 +98,18 @@ bs_status gemm_common(const uint64_t *Wp, int wbits, bs_format wfmt, const uint6
     const bool corr = !xr && ((wfmt == BS_BIPOLAR) || (afmt == BS_BIPOLAR));
     g.stream_weights = (long long)wbits * M * S * 8 >= kStreamWeightBytes;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    // Engine (Sec. 4.1.1, 4.2): the approximate mode exists bit-serially only; otherwise the caller's engine, or the
+    // one the time model expects to be fastest for this shape.
+    if (min_shift == 0 && engine != BS_ENGINE_BITSERIAL) {
+        const bs_engine e = engine == BS_ENGINE_AUTO ? bs_choose_engine(wbits, wfmt, abits, afmt, M, N, K) : engine;
+        if (e != BS_ENGINE_BITSERIAL) {
+            PlanesGemm q{};
+            q.W = g.W; q.A = g.A; q.wbits = wbits; q.abits = abits; q.wfmt = wfmt; q.afmt = afmt;
+            q.M = g.M; q.N = g.N; q.K = K; q.Kd = g.Kd;
+            q.C = C; q.ldc = ldc; q.thr = thr; q.obits = obits; q.Y = g.Y; q.Yd = g.Yd;
+            return launch_planes_mfma(q, e == BS_ENGINE_DENSE_FP4, fuse, st);
+        }
+    }
     if (gemv_applicable(g, wbits, abits, afmt == BS_BIPOLAR, wfmt == BS_BIPOLAR)) return launch_gemv(g, wbits, abits, fuse, xr, st);
     return dispatch_wb(g, wbits, abits, fuse, corr, false, xr, st);
 }
@@ -95,14 +119,28 @@ bs_status gemm_common(const uint64_t *Wp, int wbits, bs_format wfmt, const uint6
 extern "C" bs_status bs_gemm(const uint64_t *Wp, int wbits, bs_format wfmt, const uint64_t *Ap, int abits,
                              bs_format afmt, int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc, void *stream)
 {
-    return gemm_common(Wp, wbits, wfmt, Ap, abits, afmt, M, N, K, C, ldc, nullptr, 0, nullptr, false, stream);
+    return gemm_common(BS_ENGINE_AUTO, Wp, wbits, wfmt, Ap, abits, afmt, M, N, K, C, ldc, nullptr, 0, nullptr, false, stream);
+}
+
+extern "C" bs_status bs_gemm_on(bs_engine engine, const uint64_t *Wp, int wbits, bs_format wfmt, const uint64_t *Ap,
+                                int abits, bs_format afmt, int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc,
+                                void *stream)
+{
+    return gemm_common(engine, Wp, wbits, wfmt, Ap, abits, afmt, M, N, K, C, ldc, nullptr, 0, nullptr, false, stream);
+}
+
+extern "C" bs_status bs_gemm_threshold_on(bs_engine engine, const uint64_t *Wp, int wbits, bs_format wfmt,
+                                          const uint64_t *Ap, int abits, bs_format afmt, int64_t M, int64_t N, int64_t K,
+                                          const int32_t *thr, int obits, uint64_t *Yp, void *stream)
+{
+    return gemm_common(engine, Wp, wbits, wfmt, Ap, abits, afmt, M, N, K, nullptr, 0, thr, obits, Yp, true, stream);
 }
 
 extern "C" bs_status bs_gemm_threshold(const uint64_t *Wp, int wbits, bs_format wfmt, const uint64_t *Ap, int abits,
                                        bs_format afmt, int64_t M, int64_t N, int64_t K, const int32_t *thr,
                                        int obits, uint64_t *Yp, void *stream)
 {
-    return gemm_common(Wp, wbits, wfmt, Ap, abits, afmt, M, N, K, nullptr, 0, thr, obits, Yp, true, stream);
+    return gemm_common(BS_ENGINE_AUTO, Wp, wbits, wfmt, Ap, abits, afmt, M, N, K, nullptr, 0, thr, obits, Yp, true, stream);
 }
 
 extern "C" bs_status bs_conv_threshold_batch(const uint64_t *in, int abits, bs_format afmt, int B, int H, int W, int C,
@@ -126,7 +164,7 @@ extern "C" bs_status bs_conv_threshold_batch(const uint64_t *in, int abits, bs_f
     const int OH = (H + 2 * pad - kh) / stride + 1, OW = (W + 2 * pad - kw) / stride + 1;
     const int64_t N = (int64_t)B * OH * OW;
     if (2 * S > kConvMaxLut || kh > 127 || kw > 127) return BS_ERR_UNSUPPORTED;
-    if ((Kl << (wbits + abits)) >= (int64_t(1) << 31)) return BS_ERR_OVERFLOW_RISK;
+    if (result_may_overflow(Kl, wbits, wfmt, abits, afmt, false)) return BS_ERR_OVERFLOW_RISK;
     const int64_t lim = int64_t(1) << 31;
     const int64_t pix = 2 * bs_words_per_row(C);
     if (wbits * (int64_t)F * S * 2 >= lim || abits * (int64_t)B * H * W * pix >= lim || N >= lim)
@@ -161,5 +199,6 @@ extern "C" bs_status bs_gemm_topbits(const uint64_t *Wp, int wbits, bs_format wf
                                      int64_t ldc, void *stream)
 {
     if (min_shift < 0 || min_shift > wbits + abits - 2) return BS_ERR_INVALID_ARG;
-    return gemm_common(Wp, wbits, wfmt, Ap, abits, afmt, M, N, K, C, ldc, nullptr, 0, nullptr, false, stream, min_shift);
+    return gemm_common(BS_ENGINE_BITSERIAL, Wp, wbits, wfmt, Ap, abits, afmt, M, N, K, C, ldc, nullptr, 0, nullptr, false, stream,
+                       min_shift);
 }

@@ -124,6 +124,25 @@ constexpr size_t kGemvMaxLds = 64 * 1024;
 bool gemv_applicable(const GemmParams &g, int wbits, int abits, bool a_bipolar, bool w_bipolar);
 bs_status launch_gemv(const GemmParams &g, int wbits, int abits, bool fuse, bool xr, hipStream_t st);
 
+// Matrix-core engine on packed planes (bs_planes_mfma.hip): the same product from the same operands, plane bits
+// expanded to int8 or 4-bit floating-point codes inside the kernel's loader.
+struct PlanesGemm {
+    const uint32_t *W, *A;  // dword views of the packed operands
+    int wbits, abits;
+    bs_format wfmt, afmt;
+    int M, N;
+    int64_t K;
+    int Kd;                 // dwords per packed row
+    int32_t *C;
+    long long ldc;
+    const int32_t *thr;
+    int obits;
+    uint32_t *Y;
+    int Yd;
+};
+bool planes_mfma_supported(int wbits, bs_format wfmt, int abits, bs_format afmt, int64_t K, bool fp4);
+bs_status launch_planes_mfma(const PlanesGemm &q, bool fp4, bool fuse, hipStream_t st);
+
 // acc + popcount(x) in ONE instruction: v_bcnt_u32_b32 adds its second operand for
 // free.  Written as inline assembly because the optimiser otherwise re-associates a sum
 // of popcounts into a tree and pays separate adds for it (25 % more VALU work in the
@@ -201,6 +220,11 @@ __device__ __forceinline__ void mac_block(const uint4 (&w)[TM], const uint4 (&a)
         }
     }
 }
+
+// Sums of plane-pair terms are taken modulo 2^32: a partial sum may leave the int32 range although the result
+// (bounded by K max|w| max|a| < 2^31, checked on the host) does not, and unsigned arithmetic makes that well defined.
+__device__ __forceinline__ int wrap_add(int a, int b) { return (int)((unsigned)a + (unsigned)b); }
+__device__ __forceinline__ int wrap_mul(int a, int b) { return (int)((unsigned)a * (unsigned)b); }
 
 __device__ __forceinline__ int popc4(const uint4 &a)
 {
@@ -470,7 +494,7 @@ bs_gemm_kernel(const GemmParams p)
 #pragma unroll
                     for (int r = 0; r < TM; ++r)
 #pragma unroll
-                        for (int c = 0; c < TN; ++c) acc[0][r][c] += __mul24(t[r][c], cf);
+                        for (int c = 0; c < TN; ++c) acc[0][r][c] = wrap_add(acc[0][r][c], __mul24(t[r][c], cf));
                 }
             }
         }
@@ -505,7 +529,7 @@ bs_gemm_kernel(const GemmParams p)
 #pragma unroll
                 for (int i = 0; i < WB; ++i)
 #pragma unroll
-                    for (int j = 0; j < AB; ++j) v += p.coef[i * 4 + j] * acc[i * AB + j][r][c];
+                    for (int j = 0; j < AB; ++j) v = wrap_add(v, wrap_mul(p.coef[i * 4 + j], acc[i * AB + j][r][c]));
             } else {
                 v = acc[0][r][c];
             }
@@ -540,13 +564,13 @@ bs_gemm_kernel(const GemmParams p)
 #pragma unroll
         for (int r = 0; r < TM; ++r)
 #pragma unroll
-            for (int c = 0; c < TN; ++c) val[r][c] += corr_row[wrow0 + r] + corr_col[acol0 + c] + p.c0;
+            for (int c = 0; c < TN; ++c) val[r][c] = wrap_add(val[r][c], wrap_add(wrap_add(corr_row[wrow0 + r], corr_col[acol0 + c]), p.c0));
     }
     if (XOR) {
 #pragma unroll
         for (int r = 0; r < TM; ++r)
 #pragma unroll
-            for (int c = 0; c < TN; ++c) val[r][c] += p.c0;
+            for (int c = 0; c < TN; ++c) val[r][c] = wrap_add(val[r][c], p.c0);
     }
 
     if constexpr (!FUSE) {

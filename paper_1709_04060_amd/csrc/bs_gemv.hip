@@ -139,10 +139,10 @@ __global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams 
 #pragma unroll
         for (int i = 0; i < WB; ++i)
 #pragma unroll
-            for (int j = 0; j < AB; ++j) v += p.coef[i * 4 + j] * acc[i * AB + j][n];
+            for (int j = 0; j < AB; ++j) v = wrap_add(v, wrap_mul(p.coef[i * 4 + j], acc[i * AB + j][n]));
 #pragma unroll
-        for (int o = LANES_PER_ROW / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
-        val[n] = v + colsum_s[n] + p.c0;
+        for (int o = LANES_PER_ROW / 2; o > 0; o >>= 1) v = wrap_add(v, __shfl_xor(v, o));
+        val[n] = wrap_add(v, wrap_add(colsum_s[n], p.c0));
     }
     const bool leader = (g == 0) && mvalid;
 

@@ -1,5 +1,5 @@
 // Status strings and version of libbsgemm.
-#include "bsgemm.h"
+#include "bs_common.h"
 
 extern "C" const char *bs_status_string(bs_status s)
 {
@@ -22,12 +22,18 @@ extern "C" int bs_version(void) { return 100; }
 // engines; non-negative least squares on the relative error, which stays within -18 / +29 % bit-serial,
 // -33 / +12 % int8, -17 / +11 % fp4; over the measured cases the choice costs 0.4 % on average and 17 % at
 // worst against always picking the fastest).  Microseconds.
-static bool fp4_representable(int bits, bs_format fmt) { return bits <= 2 || (bits == 3 && fmt == BS_TWOS_COMPLEMENT); }
+// The dense engines as the library runs them on packed planes: 4-bit floating-point codes for operands of at most two
+// bits while the fp32 accumulation stays exact, int8 otherwise; both count depth indices in 32 bits.
+static bool fp4_usable(int wbits, bs_format wfmt, int abits, bs_format afmt, int64_t K)
+{
+    return wbits <= 2 && abits <= 2 && K * bs::max_abs(wbits, wfmt) * bs::max_abs(abits, afmt) < (int64_t(1) << 24);
+}
 
 extern "C" bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_format afmt, int64_t M, int64_t N, int64_t K)
 {
     if (wbits < 1 || wbits > 4 || abits < 1 || abits > 4 || M <= 0 || N <= 0 || K <= 0) return BS_ENGINE_BITSERIAL;
     if ((wfmt == BS_BIPOLAR && wbits != 1) || (afmt == BS_BIPOLAR && abits != 1)) return BS_ENGINE_BITSERIAL;
+    if (K >= (int64_t(1) << 30)) return BS_ENGINE_BITSERIAL;  // beyond the dense engines' depth range
     if (N <= 4) return BS_ENGINE_BITSERIAL;  // weights streamed once: wbits/8 byte per weight beats a byte or half a byte
     const double pairs = (double)wbits * abits, kk = (double)K / 1024.0;
     const double mnk2 = 2.0 * (double)M * (double)N * (double)K, mn = (double)M * (double)N;
@@ -42,7 +48,7 @@ extern "C" bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_f
         const double t_tiled = 3.64 + rounds * pairs * (0.253 * kk + 0.21);
         t_bitserial = t_stream < t_tiled ? t_stream : t_tiled;
     }
-    if (fp4_representable(wbits, wfmt) && fp4_representable(abits, afmt)) {
+    if (fp4_usable(wbits, wfmt, abits, afmt, K)) {
         const double t_fp4 = 4.2 + 2.2 * kk + 1.1 * abits + mnk2 / 6.63e9 + mn / 3.92e6;
         return t_fp4 < t_bitserial ? BS_ENGINE_DENSE_FP4 : BS_ENGINE_BITSERIAL;  // measured 1.1 - 1.5 x faster than int8 everywhere
     }

@@ -54,7 +54,46 @@ __global__ void __launch_bounds__(256) popcount_rate_kernel(uint32_t *sink, int 
     if (threadIdx.x == 0) sink[blockIdx.x] = s;
 }
 
+// Streaming read: every lane XORs 16-byte loads of a contiguous buffer, four in flight per lane, a workgroup per
+// 16 KiB slice round-robin over the grid; the workgroup stores one word so that the loads are observable.  NT: with
+// the non-temporal hint.
+template <bool NT>
+__global__ void __launch_bounds__(256) stream_read_kernel(const uint4 *__restrict__ src, long long chunks, uint32_t *sink)
+{
+    typedef unsigned v4u __attribute__((ext_vector_type(4)));
+    uint32_t s = 0;
+    for (long long base = (long long)blockIdx.x * 1024; base < chunks; base += (long long)gridDim.x * 1024) {
+        v4u v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const long long c = base + u * 256 + threadIdx.x;
+            v[u] = (v4u){0, 0, 0, 0};
+            if (c < chunks) {
+                const v4u *q = reinterpret_cast<const v4u *>(src + c);
+                v[u] = NT ? __builtin_nontemporal_load(q) : *q;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s ^= __shfl_xor(s, o);
+    if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], s);
+}
+
 }  // namespace
+
+extern "C" bs_status bs_probe_stream_read(const void *src, int64_t bytes, uint32_t *sink, int workgroups, int non_temporal,
+                                          void *stream)
+{
+    if (!src || !sink || bytes <= 0 || (bytes & 15) || workgroups <= 0) return BS_ERR_INVALID_ARG;
+    if (!bs::aligned(src, 16) || !bs::aligned(sink, 4)) return BS_ERR_ALIGNMENT;
+    const long long chunks = bytes / 16;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (non_temporal) stream_read_kernel<true><<<dim3((unsigned)workgroups), 256, 0, st>>>(static_cast<const uint4 *>(src), chunks, sink);
+    else stream_read_kernel<false><<<dim3((unsigned)workgroups), 256, 0, st>>>(static_cast<const uint4 *>(src), chunks, sink);
+    return bs::after_launch();
+}
 
 extern "C" bs_status bs_probe_popcount_rate(uint32_t *sink, int workgroups, int passes, void *stream)
 {

@@ -22,3 +22,24 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(autouse=True)
+def _guard_bands(request):
+    """GPU tests: every output buffer the binding allocates is fenced by sentinel words, checked when the test ends."""
+    if "gpu" not in request.keywords:
+        yield
+        return
+    import torch
+    if not torch.cuda.is_available():
+        yield
+        return
+    import gpu_util
+    gpu_util.install_guarded_allocator()
+    try:
+        yield
+        gpu_util.check_guards()
+    finally:
+        import paper_1709_04060_amd as bs
+        bs.set_output_allocator(None)
+        gpu_util._live_guards.clear()

@@ -47,7 +47,19 @@ def test_argument_errors_are_rejected_on_the_host():
     assert lib.bs_gemm(p, 1, 0, p, 1, 0, 0, 4, 64, p, 4, None) == bs.BS_ERR_INVALID_ARG
     assert lib.bs_gemm(p, 1, 0, p, 1, 0, 4, 4, 64, p, 3, None) == bs.BS_ERR_INVALID_ARG      # ldc < N
     assert lib.bs_gemm(p + 8, 1, 0, p, 1, 0, 4, 4, 64, p, 4, None) == bs.BS_ERR_ALIGNMENT
-    assert lib.bs_gemm(p, 4, 1, p, 4, 0, 4, 4, 1 << 23, p, 4, None) == bs.BS_ERR_OVERFLOW_RISK
+    # |C| <= K max|w| max|a| must stay below 2^31 (refused cases only: an accepted call would launch on the fake address)
+    assert lib.bs_gemm(p, 4, 1, p, 4, 0, 4, 4, 17895698, p, 4, None) == bs.BS_ERR_OVERFLOW_RISK          # 8 * 15 * K
+    assert lib.bs_gemm(p, 4, 0, p, 4, 0, 4, 4, 9544372, p, 4, None) == bs.BS_ERR_OVERFLOW_RISK           # 15 * 15 * K
+    assert lib.bs_gemm(p, 2, 1, p, 2, 0, 4, 4, 357913942, p, 4, None) == bs.BS_ERR_OVERFLOW_RISK         # 2 * 3 * K
+    assert lib.bs_gemm(p, 1, 2, p, 2, 0, 4, 4, 715827883, p, 4, None) == bs.BS_ERR_OVERFLOW_RISK         # 1 * 3 * K
+    assert lib.bs_gemm(p, 1, 2, p, 1, 2, 4, 4, 1 << 31, p, 4, None) == bs.BS_ERR_OVERFLOW_RISK
+    # the approximate mode sums a subset of the plane pairs: bounded by the unsigned ranges, 15 * 15 * K
+    assert lib.bs_gemm_topbits(p, 4, 1, p, 4, 0, 4, 4, 9544372, 3, p, 4, None) == bs.BS_ERR_OVERFLOW_RISK
+    # engines: unknown value; the fp4 matrix-core kernel takes operands of at most two bits and K max|w| max|a| < 2^24
+    assert lib.bs_gemm_on(7, p, 1, 0, p, 1, 0, 4, 4, 64, p, 4, None) == bs.BS_ERR_INVALID_ARG
+    assert lib.bs_gemm_on(bs.BS_ENGINE_DENSE_FP4, p, 3, 1, p, 2, 0, 4, 4, 64, p, 4, None) == bs.BS_ERR_UNSUPPORTED
+    assert lib.bs_gemm_on(bs.BS_ENGINE_DENSE_FP4, p, 2, 1, p, 2, 0, 4, 4, 2796203, p, 4, None) == bs.BS_ERR_UNSUPPORTED
+    assert lib.bs_gemm_threshold_on(bs.BS_ENGINE_DENSE_I8, p, 1, 2, p, 1, 2, 4, 4, 1 << 30, p, 1, p, None) == bs.BS_ERR_UNSUPPORTED
     assert lib.bs_gemm_threshold(p, 1, 0, p, 1, 0, 4, 4, 64, None, 2, p, None) == bs.BS_ERR_INVALID_ARG
     assert lib.bs_gemm_threshold(p, 1, 0, p, 1, 0, 4, 4, 64, p, 5, p, None) == bs.BS_ERR_UNSUPPORTED
     assert lib.bs_pack_planes(p, 7, 4, 64, 64, 0, 1, 0, p, None) == bs.BS_ERR_INVALID_ARG      # dtype
@@ -136,7 +148,7 @@ def test_engine_choice_rules():
     assert E(4, TC, 4, U, 8192, 8192, 8192) == I8
     assert E(2, TC, 2, U, 4096, 4096, 4096) == FP4
     assert E(1, BP, 2, U, 4096, 4096, 4096) == FP4
-    assert E(3, TC, 2, U, 4096, 4096, 4096) == FP4
+    assert E(3, TC, 2, U, 4096, 4096, 4096) == I8      # the plane loader's fp4 path takes at most two planes
     assert E(3, U, 2, U, 4096, 4096, 4096) == I8       # 5 and 7 are not E2M1 numbers
     # small layers stay bit-serial
     assert E(1, BP, 1, BP, 256, 256, 1024) == BSER

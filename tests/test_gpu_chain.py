@@ -7,7 +7,7 @@ import torch
 import oracle
 import paper_1709_04060_amd as bs
 from paper_1709_04060_amd import workloads
-from gpu_util import FMT, assert_equal, dev, draw, planes_to_dev, planes_to_numpy
+from gpu_util import FMT, assert_equal, dev, draw, planes_to_dev, planes_to_numpy, guarded_full
 
 pytestmark = pytest.mark.gpu
 U, TC, BP = oracle.UNSIGNED, oracle.TWOS_COMPLEMENT, oracle.BIPOLAR
@@ -41,7 +41,7 @@ def test_conv_threshold(H, W, C, F, k, s, p, w, wf, a, af, obits):
     Cp = 32 * ((C + 31) // 32)
     xp = bs.bs_pack_planes(dev(x.reshape(H * W, C)), a, FMT[af])
     Fp = bs.bs_pack_planes(dev(pad_last(filt, Cp).reshape(F, -1)), w, FMT[wf])
-    out = torch.full((obits, want.shape[1], bs.bs_words_per_row(F)), -1, dtype=torch.int64, device="cuda")
+    out = guarded_full((obits, want.shape[1], bs.bs_words_per_row(F)), -1, torch.int64)
     bs.bs_conv_threshold(xp, FMT[af], H, W, C, Fp, FMT[wf], k, k, s, p, dev(thr), obits, out=out)
     assert_equal(planes_to_numpy(out), want, "conv_threshold")
     # and the two-call route gives the same planes
@@ -128,7 +128,7 @@ def test_conv_and_pool_on_a_batch(B, H, W, C, F, k, s, p, w, wf, a, af, obits):
     Cp = 32 * ((C + 31) // 32)
     xp = bs.bs_pack_planes(dev(x.reshape(B * H * W, C)), a, FMT[af])
     Fp = bs.bs_pack_planes(dev(pad_last(filt, Cp).reshape(F, -1)), w, FMT[wf])
-    out = torch.full((obits, B * OH * OW, bs.bs_words_per_row(F)), -1, dtype=torch.int64, device="cuda")
+    out = guarded_full((obits, B * OH * OW, bs.bs_words_per_row(F)), -1, torch.int64)
     bs.bs_conv_threshold_batch(xp, FMT[af], B, H, W, C, Fp, FMT[wf], k, k, s, p, dev(thr), obits, out=out)
     assert_equal(planes_to_numpy(out), want, "conv_threshold_batch")
     # the two-call route on the batch: lowered columns of all images side by side, then the plain GEMM

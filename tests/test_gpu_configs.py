@@ -7,7 +7,7 @@ import torch
 import oracle
 import paper_1709_04060_amd as bs
 from paper_1709_04060_amd import workloads
-from gpu_util import assert_equal, dev, planes_to_numpy
+from gpu_util import assert_equal, dev, gemm_all_engines, gemm_threshold_all_engines, planes_to_numpy
 
 pytestmark = pytest.mark.gpu
 U, TC, BP = bs.BS_UNSIGNED, bs.BS_TWOS_COMPLEMENT, bs.BS_BIPOLAR
@@ -27,8 +27,8 @@ def test_cfg2_w2a2_4096_cubed():
     d = workloads.cfg2_square()
     Wp = bs.bs_pack_planes(dev(d["W"]), 2, TC)
     Ap = bs.bs_pack_planes(dev(d["A"]), 2, U, depth_is_strided=True)
-    C = bs.bs_gemm(Wp, TC, Ap, U, 4096)
-    assert_equal(C.cpu().numpy(), oracle.gemm(d["W"], d["A"]), "cfg2 C")
+    # the library's own choice, the AND-popcount kernel and both matrix-core kernels: one result, the oracle's
+    assert_equal(gemm_all_engines(Wp, TC, Ap, U, 4096), oracle.gemm(d["W"], d["A"]), "cfg2 C")
     assert_equal(planes_to_numpy(Ap), oracle.pack(d["A"].T, 2, oracle.UNSIGNED), "cfg2 A planes")
 
 
@@ -62,11 +62,11 @@ def test_cfg4_conv2_lowered():
     Kl = bs.bs_lowered_depth(C, k, k)
     assert Kl == 2400 and tuple(low.shape) == (2, 729, bs.bs_words_per_row(2400))
     Fp = bs.bs_pack_planes(dev(filt.reshape(F, -1)), 1, BP)                 # C = 96: no channel padding needed
-    yp = bs.bs_gemm_threshold(Fp, BP, low, U, Kl, dev(d["thr"]), 2)
+    yp = gemm_threshold_all_engines(Fp, BP, low, U, Kl, dev(d["thr"]), 2)
     conv = oracle.conv_direct(x, filt, s, p)                                # [27][27][256], direct definition
     Cmat = conv.reshape(729, F).T.copy()
-    assert_equal(planes_to_numpy(yp), oracle.threshold_pack(Cmat, d["thr"], 2), "cfg4 packed output")
-    assert_equal(bs.bs_gemm(Fp, BP, low, U, Kl).cpu().numpy(), Cmat, "cfg4 int32")
+    assert_equal(yp, oracle.threshold_pack(Cmat, d["thr"], 2), "cfg4 packed output")
+    assert_equal(gemm_all_engines(Fp, BP, low, U, Kl), Cmat, "cfg4 int32")
     L = oracle.im2col_plain(x, k, k, s, p)
     assert_equal(planes_to_numpy(low), oracle.pack(L.T.copy(), 2, oracle.UNSIGNED), "cfg4 lowered matrix")
 
@@ -76,10 +76,10 @@ def test_cfg5_w4a4_batch_sweep(n):
     d = workloads.cfg5_w4a4(n)
     Wp = bs.bs_pack_planes(dev(d["W"]), 4, TC)
     Ap = bs.bs_pack_planes(dev(d["A"]), 4, U, depth_is_strided=True)
-    yp = bs.bs_gemm_threshold(Wp, TC, Ap, U, 8192, dev(d["thr"]), 4)
+    yp = gemm_threshold_all_engines(Wp, TC, Ap, U, 8192, dev(d["thr"]), 4)   # bit-serial and int8 matrix cores
     C = oracle.gemm(d["W"], d["A"])
-    assert_equal(planes_to_numpy(yp), oracle.threshold_pack(C, d["thr"], 4), "cfg5 packed output n=%d" % n)
+    assert_equal(yp, oracle.threshold_pack(C, d["thr"], 4), "cfg5 packed output n=%d" % n)
     Y = oracle.threshold(C, d["thr"])
     assert len(np.unique(Y)) == 16                                          # all 16 levels occur
     if n <= 1024:
-        assert_equal(bs.bs_gemm(Wp, TC, Ap, U, 8192).cpu().numpy(), C, "cfg5 int32 n=%d" % n)
+        assert_equal(gemm_all_engines(Wp, TC, Ap, U, 8192), C, "cfg5 int32 n=%d" % n)

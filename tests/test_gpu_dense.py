@@ -6,7 +6,7 @@ import torch
 import oracle
 import paper_1709_04060_amd as bs
 from paper_1709_04060_amd import workloads
-from gpu_util import FMT, assert_equal, dev, draw, planes_to_numpy
+from gpu_util import FMT, assert_equal, dev, draw, planes_to_numpy, guarded_full
 
 pytestmark = pytest.mark.gpu
 U, TC, BP = oracle.UNSIGNED, oracle.TWOS_COMPLEMENT, oracle.BIPOLAR
@@ -76,7 +76,7 @@ def test_gemm_i8_threshold(M, K, N, obits):
     C = oracle.gemm(W, A)
     T = (1 << obits) - 1
     thr = np.sort(rng.integers(int(C.min()) - 2, int(C.max()) + 3, size=(M, T)), axis=1).astype(np.int32)
-    out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
+    out = guarded_full((obits, N, bs.bs_words_per_row(M)), -1, torch.int64)
     bs.bs_gemm_i8_threshold(dev(padded(W)), dev(padded(A.T.copy())), K, dev(thr), obits, out=out)
     assert_equal(planes_to_numpy(out), oracle.threshold_pack(C, thr, obits), "gemm_i8_threshold")
 
@@ -131,8 +131,6 @@ def test_dense_partial_last_stage(M, N, kbytes):
     """Depths of whole 16-byte chunks that are no multiple of the 64-byte stage (int8: K = kbytes, fp4: K = 2 kbytes;
     1200 bytes is conv2's lowered depth in E2M1 codes): the direct-to-LDS kernels complete the last stage with
     zeros.  Rows are followed in memory by a guard value that must not leak in; all three tile sizes."""
-    if kbytes == 1200 and M > 2048:
-        pytest.skip("covered at the smaller sizes; keeps the oracle products short")
     rng = np.random.default_rng(M + N + kbytes)
     # int8 engine, operands with a leading dimension larger than the depth and guard bytes behind every row
     K = kbytes

@@ -9,7 +9,7 @@ import torch
 import oracle
 import paper_1709_04060_amd as bs
 from paper_1709_04060_amd import workloads
-from gpu_util import FMT, assert_equal, dev, draw, planes_to_numpy
+from gpu_util import FMT, assert_equal, dev, draw, planes_to_numpy, guarded_full
 
 pytestmark = pytest.mark.gpu
 U, TC, BP = oracle.UNSIGNED, oracle.TWOS_COMPLEMENT, oracle.BIPOLAR
@@ -93,7 +93,7 @@ def test_gemm_fp4_threshold(M, K, N, obits):
     C = oracle.gemm(W, A)
     T = (1 << obits) - 1
     thr = np.sort(rng.integers(int(C.min()) - 2, int(C.max()) + 3, size=(M, T)), axis=1).astype(np.int32)
-    out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
+    out = guarded_full((obits, N, bs.bs_words_per_row(M)), -1, torch.int64)
     bs.bs_gemm_fp4_threshold(to_fp4(W, 1, BP), to_fp4(A.T.copy(), 2, U), K, dev(thr), obits, out=out)
     assert_equal(planes_to_numpy(out), oracle.threshold_pack(C, thr, obits), "gemm_fp4_threshold")
 

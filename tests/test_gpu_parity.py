@@ -6,7 +6,8 @@ import torch
 
 import oracle
 import paper_1709_04060_amd as bs
-from gpu_util import FMT, assert_equal, dev, draw, planes_to_dev, planes_to_numpy
+from gpu_util import (FMT, assert_equal, dev, draw, gemm_all_engines, gemm_threshold_all_engines, guarded_full, planes_to_dev,
+                      planes_to_numpy)
 
 pytestmark = pytest.mark.gpu
 U, TC, BP = oracle.UNSIGNED, oracle.TWOS_COMPLEMENT, oracle.BIPOLAR
@@ -67,7 +68,7 @@ def test_pack_respects_leading_dimension_and_overwrites_padding():
     big = draw(rng, (40, 300), 2, U)
     X = big[:, :200]
     t = dev(big)[:, :200]                      # ld = 300 > depth
-    out = torch.full((2, 40, bs.bs_words_per_row(200)), -1, dtype=torch.int64, device="cuda")
+    out = guarded_full((2, 40, bs.bs_words_per_row(200)), -1, torch.int64)
     bs.bs_pack_planes(t, 2, bs.BS_UNSIGNED, out=out)
     assert_equal(planes_to_numpy(out), oracle.pack(X, 2, U), "pack with ld")
     tt = dev(big.T.copy())[:200, :]            # strided: [depth][rows], all 40 rows, ld = 40
@@ -85,7 +86,8 @@ BIP = [(1, BP, a, af) for a in (1, 2, 3, 4) for af in (U, TC)] + [(w, wf, 1, BP)
 def run_gemm(W, A, w, wf, a, af):
     Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
     Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
-    return bs.bs_gemm(Wp, FMT[wf], Ap, FMT[af], W.shape[1]).cpu().numpy()
+    # every engine that takes the case must give the same matrix (checked inside); the caller compares it with the oracle
+    return gemm_all_engines(Wp, FMT[wf], Ap, FMT[af], W.shape[1])
 
 
 @pytest.mark.parametrize("w,wf,a,af", ALL_WA + BIP)
@@ -129,9 +131,8 @@ def test_few_column_path(N, M, K, w, wf, a, af, obits):
     thr = make_thr(rng, want, obits)
     Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
     Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
-    out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
-    bs.bs_gemm_threshold(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits, out=out)
-    assert_equal(planes_to_numpy(out), oracle.threshold_pack(want, thr, obits), "gemv fused")
+    got = gemm_threshold_all_engines(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits)
+    assert_equal(got, oracle.threshold_pack(want, thr, obits), "gemv fused")
 
 
 @pytest.mark.parametrize("N", [5, 8, 12, 16])
@@ -148,9 +149,8 @@ def test_few_columns_many_rows(N, w, wf, a, af, obits):
         thr = make_thr(rng, want, obits)
         Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
         Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
-        out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
-        bs.bs_gemm_threshold(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits, out=out)
-        assert_equal(planes_to_numpy(out), oracle.threshold_pack(want, thr, obits), "fused %dx%dx%d" % (M, K, N))
+        got = gemm_threshold_all_engines(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits)
+        assert_equal(got, oracle.threshold_pack(want, thr, obits), "fused %dx%dx%d" % (M, K, N))
 
 
 @pytest.mark.parametrize("M,K,N", [(1, 1, 1), (64, 64, 64), (65, 129, 63), (200, 3000, 130), (4, 5000, 2), (300, 100, 4),
@@ -164,13 +164,14 @@ def test_w1a1_bipolar_xor_path(M, K, N):
     thr = make_thr(rng, want, 1)
     Wp = bs.bs_pack_planes(dev(W), 1, bs.BS_BIPOLAR)
     Ap = bs.bs_pack_planes(dev(A), 1, bs.BS_BIPOLAR, depth_is_strided=True)
+    assert_equal(gemm_threshold_all_engines(Wp, bs.BS_BIPOLAR, Ap, bs.BS_BIPOLAR, K, dev(thr), 1),
+                 oracle.threshold_pack(want, thr, 1), "W1A1 fused")
     got = bs.bs_gemm_threshold(Wp, bs.BS_BIPOLAR, Ap, bs.BS_BIPOLAR, K, dev(thr), 1)
-    assert_equal(planes_to_numpy(got), oracle.threshold_pack(want, thr, 1), "W1A1 fused")
     # a binarised layer chains: the 1-bit output planes are the next layer's bipolar operand
     W2 = draw(rng, (33, M), 1, BP)
     want2 = oracle.gemm(W2, (2 * oracle.threshold(want, thr).astype(np.int8) - 1))
-    got2 = bs.bs_gemm(bs.bs_pack_planes(dev(W2), 1, bs.BS_BIPOLAR), bs.BS_BIPOLAR, got, bs.BS_BIPOLAR, M)
-    assert_equal(got2.cpu().numpy(), want2, "W1A1 chained")
+    got2 = gemm_all_engines(bs.bs_pack_planes(dev(W2), 1, bs.BS_BIPOLAR), bs.BS_BIPOLAR, got, bs.BS_BIPOLAR, M)
+    assert_equal(got2, want2, "W1A1 chained")
 
 
 @pytest.mark.parametrize("w,wf,a,af", [(2, TC, 2, U), (4, TC, 4, U), (3, U, 4, TC), (4, U, 1, U)])
@@ -188,23 +189,30 @@ def test_gemm_topbits(w, wf, a, af, M, K, N):
 
 
 @pytest.mark.parametrize("N", [1, 6])
-def test_gemm_very_deep_extreme_values(N):
-    """Depth 2^22 with extremal W4A4 values: |C| = 8 * 15 * 2^22 = 5.03e8, a quarter of the int32 range,
-    through thousands of depth stages (few-column kernel for N = 1, tiled kernel for N = 6)."""
-    K, M = 1 << 22, 5
+@pytest.mark.parametrize("K", [1 << 22, 17895697])
+def test_gemm_very_deep_extreme_values(N, K):
+    """Extremal W4A4 values through thousands of depth stages (few-column kernel for N = 1, tiled kernel for N = 6,
+    the int8 matrix-core kernel for both).  K = 17895697 is the deepest product the library accepts for these
+    formats: |C| = 8 * 15 * K = 2147483640 <= 2^31 - 1, so partial sums of plane-pair terms wrap around on the way
+    and the result must still be exact."""
+    M = 5
     rng = np.random.default_rng(N)
     W = np.full((M, K), -8, dtype=np.int8)
     A = np.full((K, N), 15, dtype=np.int8)
     W[1] = draw(rng, (K,), 4, TC)
+    W[2] = 7
     if N > 1:
         A[:, -1] = draw(rng, (K,), 4, U)
     Wp = bs.bs_pack_planes(dev(W), 4, bs.BS_TWOS_COMPLEMENT)
-    Ap = bs.bs_pack_planes(dev(A), 4, bs.BS_UNSIGNED, depth_is_strided=True)
-    got = bs.bs_gemm(Wp, bs.BS_TWOS_COMPLEMENT, Ap, bs.BS_UNSIGNED, K).cpu().numpy()
+    # packed from the transposed copy: the transposing pack walks the depth in the launch grid's second dimension,
+    # which this depth exceeds for a source without 4-element alignment (it is refused there)
+    Ap = bs.bs_pack_planes(dev(np.ascontiguousarray(A.T)), 4, bs.BS_UNSIGNED)
+    got = gemm_all_engines(Wp, bs.BS_TWOS_COMPLEMENT, Ap, bs.BS_UNSIGNED, K)
     assert_equal(got, oracle.gemm(W, A), "deep W4A4")
-    assert got[0, 0] == -8 * 15 * K
-    # one more doubling of the depth would be refused
-    assert bs.load_library().bs_gemm(Wp.data_ptr(), 4, 1, Ap.data_ptr(), 4, 0, M, N, 1 << 23, got.ctypes.data, N, None) \
+    assert got[0, 0] == -8 * 15 * K and got[2, 0] == 7 * 15 * K
+    # 2^31 / (8 * 15) = 17895697.07: one index more is refused (the argument check alone is exercised here)
+    lib = bs.load_library()
+    assert lib.bs_gemm(Wp.data_ptr(), 4, 1, Ap.data_ptr(), 4, 0, M, N, 17895698, got.ctypes.data, N, None) \
         == bs.BS_ERR_OVERFLOW_RISK
 
 
@@ -232,7 +240,7 @@ def test_threshold_activate(M, N, obits):
     rng = np.random.default_rng(M * 7 + N + obits)
     C = rng.integers(-500, 500, size=(M, N)).astype(np.int32)
     thr = make_thr(rng, C, obits)
-    out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
+    out = guarded_full((obits, N, bs.bs_words_per_row(M)), -1, torch.int64)
     bs.bs_threshold_activate(dev(C), dev(thr), obits, out=out)
     assert_equal(planes_to_numpy(out), oracle.threshold_pack(C, thr, obits), "threshold")
 
@@ -249,9 +257,8 @@ def test_gemm_threshold_fused(M, K, N, w, wf, a, af, obits):
     thr = make_thr(rng, C, obits)
     Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
     Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
-    out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
-    bs.bs_gemm_threshold(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits, out=out)
-    assert_equal(planes_to_numpy(out), oracle.threshold_pack(C, thr, obits), "fused gemm+threshold")
+    got = gemm_threshold_all_engines(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits)
+    assert_equal(got, oracle.threshold_pack(C, thr, obits), "fused gemm+threshold")
 
 
 # ------------------------------------------------------------------ S2 lowering

@@ -24,3 +24,18 @@ def test_probe_rejects_bad_arguments():
         with pytest.raises(bs.BsError) as e:
             bs.bs_probe_popcount_rate(sink, passes)
         assert e.value.status == bs.BS_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("nt", [False, True])
+def test_stream_read_probe_reads_every_byte_once(nt):
+    """The XOR of the workgroups' words equals the XOR of all 32-bit words of the buffer (ragged last slice)."""
+    n = (5 * 16384 + 16 * 37) // 4
+    g = torch.Generator(device="cpu").manual_seed(7)
+    src = torch.randint(-2 ** 31, 2 ** 31 - 1, (n,), dtype=torch.int32, generator=g)
+    sink = torch.zeros((3,), dtype=torch.int32, device="cuda")
+    assert bs.bs_probe_stream_read(src.cuda(), sink, non_temporal=nt) == 4 * n
+    torch.cuda.synchronize()
+    import numpy as np
+    want = int(np.bitwise_xor.reduce(src.numpy().view(np.uint32)))
+    got = int(np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32)))
+    assert got == want

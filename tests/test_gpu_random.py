@@ -7,7 +7,7 @@ import torch
 
 import oracle
 import paper_1709_04060_amd as bs
-from gpu_util import FMT, assert_equal, dev, draw, planes_to_numpy
+from gpu_util import FMT, assert_equal, dev, draw, gemm_all_engines, gemm_threshold_all_engines, guarded_full, planes_to_numpy
 
 pytestmark = pytest.mark.gpu
 U, TC, BP = oracle.UNSIGNED, oracle.TWOS_COMPLEMENT, oracle.BIPOLAR
@@ -43,12 +43,10 @@ def test_random_bit_serial(seed):
     what = "seed %d W%d(%d)A%d(%d) %dx%dx%d o=%d" % (seed, w, wf, a, af, M, K, N, obits)
     Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
     Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
-    assert_equal(bs.bs_gemm(Wp, FMT[wf], Ap, FMT[af], K).cpu().numpy(), C, "bs_gemm " + what)
-    out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
-    bs.bs_gemm_threshold(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits, out=out)
+    assert_equal(gemm_all_engines(Wp, FMT[wf], Ap, FMT[af], K), C, "bs_gemm " + what)
     want = oracle.threshold_pack(C, thr, obits)
-    assert_equal(planes_to_numpy(out), want, "bs_gemm_threshold " + what)
-    out2 = torch.full_like(out, -1)
+    assert_equal(gemm_threshold_all_engines(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits), want, "bs_gemm_threshold " + what)
+    out2 = guarded_full((obits, N, bs.bs_words_per_row(M)), -1, torch.int64)
     bs.bs_threshold_activate(dev(C), dev(thr), obits, out=out2)
     assert_equal(planes_to_numpy(out2), want, "bs_threshold_activate " + what)
 
@@ -64,7 +62,7 @@ def test_random_dense_engines(seed):
     want = oracle.threshold_pack(C, thr, obits)
     W8, A8 = bs.bs_unpack_planes(Wp, FMT[wf], K), bs.bs_unpack_planes(Ap, FMT[af], K)
     assert_equal(bs.bs_gemm_i8(W8, A8, K).cpu().numpy(), C, "bs_gemm_i8 " + what)
-    out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
+    out = guarded_full((obits, N, bs.bs_words_per_row(M)), -1, torch.int64)
     bs.bs_gemm_i8_threshold(W8, A8, K, dev(thr), obits, out=out)
     assert_equal(planes_to_numpy(out), want, "bs_gemm_i8_threshold " + what)
     rep = lambda b, f: b <= 2 or (b == 3 and f == TC)
@@ -105,7 +103,7 @@ def test_random_convolution_and_pooling(seed):
         fpad[..., C:] = -1                          # any value does: the activation pad bits are zero
     xp = bs.bs_pack_planes(dev(x.reshape(H * W, C)), a, FMT[af])
     Fp = bs.bs_pack_planes(dev(fpad.reshape(F, -1)), w, FMT[wf])
-    out = torch.full((obits, OH * OW, bs.bs_words_per_row(F)), -1, dtype=torch.int64, device="cuda")
+    out = guarded_full((obits, OH * OW, bs.bs_words_per_row(F)), -1, torch.int64)
     bs.bs_conv_threshold(xp, FMT[af], H, W, C, Fp, FMT[wf], k, k, s, p, dev(thr), obits, out=out)
     assert_equal(planes_to_numpy(out), want, "bs_conv_threshold " + what)
     low = bs.bs_im2col_interleaved(xp, H, W, C, k, k, s, p)
@@ -147,7 +145,7 @@ def test_random_large_shapes(seed):
     Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
     Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
     assert_equal(bs.bs_gemm(Wp, FMT[wf], Ap, FMT[af], K).cpu().numpy(), C, "bs_gemm " + what)
-    out = torch.full((obits, N, bs.bs_words_per_row(M)), -1, dtype=torch.int64, device="cuda")
+    out = guarded_full((obits, N, bs.bs_words_per_row(M)), -1, torch.int64)
     bs.bs_gemm_threshold(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits, out=out)
     assert_equal(planes_to_numpy(out), want, "bs_gemm_threshold " + what)
     W8, A8 = bs.bs_unpack_planes(Wp, FMT[wf], K), bs.bs_unpack_planes(Ap, FMT[af], K)
