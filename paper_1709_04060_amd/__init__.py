@@ -15,7 +15,8 @@ import os
 import torch  # imported before the library so that both share one HIP runtime
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libbsgemm.so")
+# BSGEMM_LIBRARY names another build of the library (an instrumented one, say); the default is the in-tree build
+LIB_PATH = os.environ.get("BSGEMM_LIBRARY") or os.path.join(_HERE, "libbsgemm.so")
 
 BS_OK = 0
 BS_ERR_INVALID_ARG, BS_ERR_UNSUPPORTED, BS_ERR_ALIGNMENT, BS_ERR_OVERFLOW_RISK, BS_ERR_LAUNCH = -1, -2, -3, -4, -5
@@ -218,10 +219,12 @@ def bs_pack_planes(src: torch.Tensor, bits: int, fmt: int, depth_is_strided: boo
     rows, depth = (src.shape[1], src.shape[0]) if depth_is_strided else (src.shape[0], src.shape[1])
     if src.shape[0] > 1 and src.stride(0) < src.shape[1]:
         raise ValueError("src rows overlap (row stride below the row length)")
+    # a single row has no meaningful row stride (frameworks report anything): pass the row length
+    ld = src.stride(0) if src.shape[0] > 1 else src.shape[1]
     if out is None:
         out = _planes(bits, rows, depth, src.device)
     _want_planes(out, "out", depth, bits=bits, rows=rows)
-    st = load_library().bs_pack_planes(_dev(src, "src"), dtype, rows, depth, src.stride(0), int(bool(depth_is_strided)),
+    st = load_library().bs_pack_planes(_dev(src, "src"), dtype, rows, depth, ld, int(bool(depth_is_strided)),
                                        bits, fmt, _dev(out, "out"), _stream())
     _check(st, "bs_pack_planes")
     return out

@@ -75,9 +75,16 @@ __device__ __forceinline__ uint4 mask_tail(uint4 v, int k, int K)
 // power of two with INT_MAX (never reached, which also zeroes rows past M); every output is
 // compared with its row's T thresholds, the count's OB bits are placed at the row's position
 // of one 32-row word per plane, and the words leave as whole dwords.
-template <int OB, int WTM, int WTN, bool FP4, int WGM, int WGN>
+// Turns an accumulator into the int32 product.  The kernels on unpacked operands accumulate the product itself
+// (PlainResult); the kernel on packed planes accumulates a product of unsigned codes and adds per-row and per-column
+// terms (see bs_planes_mfma.hip).  row, col: position inside the workgroup's tile.
+struct PlainResult {
+    template <class ACC> __device__ __forceinline__ int operator()(ACC a, int, int) const { return (int)a; }
+};
+
+template <int OB, int WTM, int WTN, bool FP4, int WGM, int WGN, class RESULT>
 __device__ __forceinline__ void dense_threshold_planes(const DenseParams &p, typename AccOf<FP4>::type (&acc)[WTM][WTN],
-                                                       unsigned char *lds, int m0, int n0)
+                                                       unsigned char *lds, int m0, int n0, const RESULT &result)
 {
     constexpr int T = (1 << OB) - 1;
     constexpr int TS = OB == 1 ? 1 : OB == 2 ? 4 : OB == 3 ? 8 : 16;  // table entries per row
@@ -116,7 +123,7 @@ __device__ __forceinline__ void dense_threshold_planes(const DenseParams &p, typ
             }
 #pragma unroll
             for (int b = 0; b < WTN; ++b) {
-                const int c = (int)acc[a][b][v];
+                const int c = result(acc[a][b][v], rbase + rr, (wn * WTN + b) * 32 + li);
                 uint32_t y = 0;
 #pragma unroll
                 for (int e = 0; e < T; ++e)  // y += (c >= t): compare into the carry mask, add the carry
@@ -145,9 +152,9 @@ __device__ __forceinline__ void dense_threshold_planes(const DenseParams &p, typ
 
 // Epilogue shared by the two dense kernels: int32 store, or successive thresholding with
 // the packed-plane output.  `lds` is the (no longer needed) operand space of the caller.
-template <int WTM, int WTN, bool FUSE, bool FP4, int WGM = 2, int WGN = 2>
+template <int WTM, int WTN, bool FUSE, bool FP4, int WGM = 2, int WGN = 2, class RESULT = PlainResult>
 __device__ __forceinline__ void dense_epilogue(const DenseParams &p, typename AccOf<FP4>::type (&acc)[WTM][WTN],
-                                               unsigned char *lds, int m0, int n0, int tile_m)
+                                               unsigned char *lds, int m0, int n0, int tile_m, const RESULT &result = RESULT())
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
@@ -162,15 +169,16 @@ __device__ __forceinline__ void dense_epilogue(const DenseParams &p, typename Ac
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int m = m0 + (wm * WTM + a) * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-                    if (m < p.M && n < p.N) p.C[(long long)m * p.ldc + n] = (int)acc[a][b][v];
+                    if (m < p.M && n < p.N)
+                        p.C[(long long)m * p.ldc + n] = result(acc[a][b][v], m - m0, n - n0);
                 }
             }
     } else {
         switch (p.obits) {  // uniform
-        case 1: dense_threshold_planes<1, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0); break;
-        case 2: dense_threshold_planes<2, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0); break;
-        case 3: dense_threshold_planes<3, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0); break;
-        default: dense_threshold_planes<4, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0); break;
+        case 1: dense_threshold_planes<1, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0, result); break;
+        case 2: dense_threshold_planes<2, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0, result); break;
+        case 3: dense_threshold_planes<3, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0, result); break;
+        default: dense_threshold_planes<4, WTM, WTN, FP4, WGM, WGN>(p, acc, lds, m0, n0, result); break;
         }
     }
 }

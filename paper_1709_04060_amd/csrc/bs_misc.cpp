@@ -26,7 +26,8 @@ extern "C" int bs_version(void) { return 100; }
 // bits while the fp32 accumulation stays exact, int8 otherwise; both count depth indices in 32 bits.
 static bool fp4_usable(int wbits, bs_format wfmt, int abits, bs_format afmt, int64_t K)
 {
-    return wbits <= 2 && abits <= 2 && K * bs::max_abs(wbits, wfmt) * bs::max_abs(abits, afmt) < (int64_t(1) << 24);
+    (void)wfmt; (void)afmt;  // the kernel multiplies unsigned codes, whatever the format
+    return wbits <= 2 && abits <= 2 && K * ((int64_t(1) << wbits) - 1) * ((int64_t(1) << abits) - 1) < (int64_t(1) << 24);
 }
 
 extern "C" bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_format afmt, int64_t M, int64_t N, int64_t K)

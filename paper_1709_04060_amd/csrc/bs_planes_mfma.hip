@@ -4,28 +4,38 @@
 // operands stay w/8 and a/8 byte per element in device memory, nothing unpacked is ever written
 // there, and no extra buffer or launch is needed.  The loader of the kernel turns plane bits into
 // operand codes on their way to LDS:
-//   fp4 kind   operands of at most 2 bits (any format): every value is a number of the 4-bit E2M1
-//              floating-point format; v_mfma_f32_32x32x64_f8f6f4, 128 depth indices per 64-byte
-//              LDS row and stage, exact while K max|w| max|a| < 2^24;
+//   fp4 kind   operands of at most 2 bits; v_mfma_f32_32x32x64_f8f6f4 on 4-bit E2M1 floating-point
+//              codes, 128 depth indices per 64-byte LDS row and stage;
 //   int8 kind  operands of up to 4 bits; v_mfma_i32_32x32x32_i8, 64 depth indices per row and stage.
 //
-// Expansion.  A thread owns one row of the stacked [W rows; A rows] tile.  For two planes x0, x1 the
-// even-indexed bits of both are merged into one word of 2-bit fields (x0 & 0x55..) | (x1 & 0x55..) << 1,
-// the odd-indexed ones likewise; a byte of such a word holds four fields, which one byte-permute and one
-// packed 16-bit multiply spread to the low bits of four bytes; those bytes index a four-entry code table
-// held in a register through one more byte-permute instruction (v_perm_b32).  The table carries the format (unsigned, two's
-// complement, bipolar), so one code path serves all of them.  A bipolar operand (value 2 bit - 1) takes
-// a synthetic second plane "index < K": padding bits then decode to 0 instead of -1.  Operands with
-// fewer planes than the kernel variant handles get their missing planes masked to zero.  Planes 2 and
-// 3 (int8 kind) go through a second table holding 4 b2 + 8 b3 (or -8 b3), added byte-wise.
+// What makes the expansion cheap (it runs on the vector unit, and a SIMD does not execute vector and
+// matrix instructions at the same time: measured, 16 simple vector instructions behind every matrix
+// instruction double the time of a matrix-only loop).
+//  1. Unsigned codes, corrected afterwards.  Every format is an affine function of an unsigned code u:
+//     unsigned v = u; two's complement v = u - T with u = code xor T, T = 2^(bits-1) (top plane
+//     inverted); bipolar v = 2 u - 1.  With v_w = aw u_w + bw and v_a = aa u_a + ba,
+//       C[m][n] = aw aa (U_w . U_a)[m][n] + aw ba rowsum(U_w)[m] + bw aa rowsum(U_a)[n] + bw ba K,
+//     and the row sums are weighted popcounts of the planes the loader moves anyway (the same trick as
+//     the popcount correction of the AND-popcount kernels for bipolar operands).  So the matrix
+//     instruction only ever sees unsigned codes, whose bits ARE the plane bits: no table look-up.
+//     In the E2M1 format the codes 0000..0011 are 0, 0.5, 1, 1.5, i.e. linear in their two low bits: a
+//     2-bit code in the low bits of a nibble is the number u / 2 (a 1-bit operand goes to bit 1 and is
+//     u itself); the factor is taken out again when the exact fp32 sum is converted.
+//  2. Any order of the depth indices.  The contraction runs over matching positions of the two
+//     operands, so the loader may place the indices of a 32-index word in whatever order is cheapest,
+//     as long as both operands use the same one.  The planes of a word are merged with masks and
+//     shifts (even- and odd-indexed bits first, then pairs of 2-bit fields), which leaves the codes in
+//     a fixed permuted order, and they are stored as they come: 12 vector instructions per 32 codes
+//     for two planes to nibbles, 36 for four planes to bytes.
+// Padding bits are zero in every plane, hence zero codes, except in an inverted top plane, which is
+// masked with "index < K".
 //
-// Pipeline.  Two LDS stage buffers of 64-byte rows (XOR-swizzled 16-byte chunks, the layout of the
-// direct-to-LDS dense kernel), one barrier per stage in the middle of the stage: the first half of
-// iteration i expands the second half of stage i + 1 and multiplies depth step 0 of stage i, the
-// second half expands the first half of stage i + 2 and multiplies depth step 1; plane words are
-// requested from memory one iteration before they are expanded.  Expansion (VALU) and matrix
-// instructions are issued interleaved from the same basic block, so the vector and the matrix
-// pipe work at the same time.
+// Pipeline.  A thread owns one row of the stacked [W rows; A rows] tile.  Four LDS stage buffers of 64-byte rows
+// (XOR-swizzled 16-byte chunks, the layout of the direct-to-LDS dense kernel): a period of two stages is multiplied
+// from two of them while the next period's stages are expanded into the other two, with one barrier per period.
+// Plane words are requested a period ahead, 16 bytes per row and plane: every lane of such a request touches
+// another cache line, and those look-ups bound the loader (with all lanes on one row the W4A4 8192^3 product took
+// 555 instead of 1105 us), hence as few and as wide requests as the registers allow.
 #include "bs_dense_common.h"
 #include "bs_gemm_kernel.h"
 
@@ -34,89 +44,74 @@ namespace {
 
 using namespace bs::dense;
 
+struct OperandCoding {
+    int bits;
+    int shift;              // slot of plane 0 (fp4 kind: 2 - bits, so that a 1-bit operand sits in the nibble's bit 1)
+    int top;                // slot whose plane is inverted (two's complement), or -1
+};
+
 struct PlanesParams {
     DenseParams d;          // epilogue fields (M, N, C, ldc, thr, T, obits, Y, Yd, gx, gy); W, A, ld*, K unused
     const uint32_t *Wp;     // [wbits][M][Kd]
     const uint32_t *Ap;     // [abits][N][Kd]
     int Kd;                 // dwords per packed row
-    int wbits, abits;
-    int wbip, abip;         // operand is bipolar
+    OperandCoding cw, ca;
     int K32;                // depth in indices (below 2^30)
     int nst;                // stages: ceil(K / indices per stage)
-    uint32_t lutW[4];       // code tables of the weight operand: fp4 {even nibble, odd nibble}; int8 {planes 0-1, planes 2-3}
-    uint32_t lutA[4];
+    int nper;               // periods of two stages: ceil(nst / 2)
+    // C = mul * P + row_coef * rowsum(U_w)[m] + row_const + col_coef * rowsum(U_a)[n],  P = acc * acc_scale = U_w . U_a
+    int mul, row_coef, row_const, col_coef;
+    float acc_scale;
 };
 
-typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+// (a & m) | (b & ~m): one v_bfi_b32
+__device__ __forceinline__ uint32_t bitsel(uint32_t m, uint32_t a, uint32_t b) { return (a & m) | (b & ~m); }
 
-// A word of 2-bit fields (four per byte) split into its even and odd nibbles, one nibble per byte.
-struct FieldWord {
-    uint32_t lo, hi;  // byte g: fields 0, 1 of byte g of the word | fields 2, 3
+// Even- and odd-indexed bits of two planes merged into 2-bit fields (lo | hi << 1): 16 fields per word each.
+// (hi & 0x55..) << 1 is (hi << 1) under the complementary mask, so each merge is a shift and a bit select.
+__device__ __forceinline__ void merge_pair(uint32_t lo, uint32_t hi, uint32_t &even, uint32_t &odd)
+{
+    even = bitsel(0x55555555u, lo, hi << 1);
+    odd = bitsel(0x55555555u, lo >> 1, hi);
+}
+
+// 32 depth indices of two planes -> 32 nibbles 00 hi lo (16 bytes), in the loader's fixed order of the indices
+__device__ __forceinline__ uint4 expand32_fp4(uint32_t lo, uint32_t hi)
+{
+    uint32_t e, o;
+    merge_pair(lo, hi, e, o);
+    return make_uint4(e & 0x33333333u, (e >> 2) & 0x33333333u, o & 0x33333333u, (o >> 2) & 0x33333333u);
+}
+
+// 32 depth indices of four planes -> 32 bytes 0000 x3 x2 x1 x0 (two 16-byte chunks), in the loader's fixed order
+__device__ __forceinline__ void expand32_i8(const uint32_t (&x)[4], uint4 &out0, uint4 &out1)
+{
+    uint32_t e01, o01, e23, o23;
+    merge_pair(x[0], x[1], e01, o01);
+    merge_pair(x[2], x[3], e23, o23);
+    uint32_t n[4];  // 8 nibble codes each: fields of planes 0-1 in the low half of every nibble, of planes 2-3 above
+    n[0] = bitsel(0x33333333u, e01, e23 << 2);
+    n[1] = bitsel(0x33333333u, e01 >> 2, e23);
+    n[2] = bitsel(0x33333333u, o01, o23 << 2);
+    n[3] = bitsel(0x33333333u, o01 >> 2, o23);
+    out0 = make_uint4(n[0] & 0x0F0F0F0Fu, (n[0] >> 4) & 0x0F0F0F0Fu, n[1] & 0x0F0F0F0Fu, (n[1] >> 4) & 0x0F0F0F0Fu);
+    out1 = make_uint4(n[2] & 0x0F0F0F0Fu, (n[2] >> 4) & 0x0F0F0F0Fu, n[3] & 0x0F0F0F0Fu, (n[3] >> 4) & 0x0F0F0F0Fu);
+}
+
+// accumulator -> int32 product: scale out the E2M1 half steps, then the affine terms of the two formats
+struct PlanesResult {
+    int mul;
+    float acc_scale;
+    const int *row_term, *col_term;  // LDS, indexed by the row / column inside the tile
+    __device__ __forceinline__ int operator()(float a, int row, int col) const
+    {
+        return wrap_add(wrap_mul(mul, (int)(a * acc_scale)), wrap_add(row_term[row], col_term[col]));
+    }
+    __device__ __forceinline__ int operator()(int a, int row, int col) const
+    {
+        return wrap_add(wrap_mul(mul, a), wrap_add(row_term[row], col_term[col]));
+    }
 };
-__device__ __forceinline__ FieldWord split_nibbles(uint32_t c)
-{
-    FieldWord f;
-    f.lo = c & 0x0F0F0F0Fu;
-    f.hi = (c >> 4) & 0x0F0F0F0Fu;
-    return f;
-}
-
-// The four fields of byte g -> the low two bits of four bytes.  A byte-permute puts the byte's low nibble into
-// the low half-word and its high nibble into the high half-word; one packed 16-bit multiply by (1 + 2^6) moves
-// the second field of each nibble from bits 2-3 to bits 8-9 (its other copies are masked off).
-template <int G>
-__device__ __forceinline__ uint32_t spread_fields(const FieldWord &f)
-{
-    const uint32_t in = __builtin_amdgcn_perm(f.hi, f.lo, 0x0c000c00u | (uint32_t)G | ((uint32_t)(4 + G) << 16));
-    const u16x2 m = __builtin_bit_cast(u16x2, in) * (u16x2){0x41, 0x41};
-    return __builtin_bit_cast(uint32_t, m) & 0x03030303u;
-}
-
-// even-indexed and odd-indexed bits of two planes merged into 2-bit fields (plane 0 | plane 1 << 1)
-__device__ __forceinline__ void merge_planes(uint32_t x0, uint32_t x1, FieldWord &even, FieldWord &odd)
-{
-    even = split_nibbles((x0 & 0x55555555u) | ((x1 & 0x55555555u) << 1));
-    odd = split_nibbles(((x0 >> 1) & 0x55555555u) | (x1 & 0xAAAAAAAAu));
-}
-
-template <int G>
-__device__ __forceinline__ uint32_t codes8_fp4(const FieldWord &e, const FieldWord &o, uint32_t lut_lo, uint32_t lut_hi)
-{
-    return __builtin_amdgcn_perm(0u, lut_lo, spread_fields<G>(e)) | __builtin_amdgcn_perm(0u, lut_hi, spread_fields<G>(o));
-}
-
-// 32 depth indices of two planes -> 32 E2M1 codes (16 bytes; low nibble = even index)
-__device__ __forceinline__ uint4 expand32_fp4(uint32_t x0, uint32_t x1, uint32_t lut_lo, uint32_t lut_hi)
-{
-    FieldWord e, o;
-    merge_planes(x0, x1, e, o);
-    return make_uint4(codes8_fp4<0>(e, o, lut_lo, lut_hi), codes8_fp4<1>(e, o, lut_lo, lut_hi),
-                      codes8_fp4<2>(e, o, lut_lo, lut_hi), codes8_fp4<3>(e, o, lut_lo, lut_hi));
-}
-
-// eight depth indices of four planes -> eight int8 values (two dwords).  The two tables' bytes add without carries
-// between bytes: planes 0-1 give 0..3 whenever planes 2-3 exist.
-template <int G>
-__device__ __forceinline__ void values8_i8(const FieldWord (&e)[2], const FieldWord (&o)[2], uint32_t lut01, uint32_t lut23,
-                                           uint32_t &d0, uint32_t &d1)
-{
-    const uint32_t ve = __builtin_amdgcn_perm(0u, lut01, spread_fields<G>(e[0])) + __builtin_amdgcn_perm(0u, lut23, spread_fields<G>(e[1]));
-    const uint32_t vo = __builtin_amdgcn_perm(0u, lut01, spread_fields<G>(o[0])) + __builtin_amdgcn_perm(0u, lut23, spread_fields<G>(o[1]));
-    d0 = __builtin_amdgcn_perm(vo, ve, 0x05010400u);  // e0 o0 e1 o1
-    d1 = __builtin_amdgcn_perm(vo, ve, 0x07030602u);  // e2 o2 e3 o3
-}
-
-// 32 depth indices of four planes -> 32 int8 values (two 16-byte chunks)
-__device__ __forceinline__ void expand32_i8(const uint32_t (&x)[4], uint32_t lut01, uint32_t lut23, uint4 &out0, uint4 &out1)
-{
-    FieldWord e[2], o[2];
-    merge_planes(x[0], x[1], e[0], o[0]);
-    merge_planes(x[2], x[3], e[1], o[1]);
-    values8_i8<0>(e, o, lut01, lut23, out0.x, out0.y);
-    values8_i8<1>(e, o, lut01, lut23, out0.z, out0.w);
-    values8_i8<2>(e, o, lut01, lut23, out1.x, out1.y);
-    values8_i8<3>(e, o, lut01, lut23, out1.z, out1.w);
-}
 
 // FP4: operand kind.  WTM x WTN MFMA tiles of 32 x 32 per wavefront, WGM x WGN wavefronts; the workgroup has as many
 // threads as the stacked tile has rows (one row per thread).
@@ -124,13 +119,15 @@ template <bool FP4, int WTM, int WTN, int WGM, int WGN, bool FUSE>
 __global__ void __launch_bounds__(64 * WGM * WGN)
 planes_mfma_kernel(const PlanesParams p)
 {
-    constexpr int NB = FP4 ? 2 : 4;              // planes the expansion handles
+    constexpr int NB = FP4 ? 2 : 4;              // code-bit slots the expansion handles
     constexpr int DW = FP4 ? 4 : 2;              // plane dwords per row and stage (128 or 64 depth indices)
+    constexpr int PW = 2 * DW;                   // ... and period (two stages)
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN, NT = 64 * WGM * WGN;
     static_assert(BM + BN == NT, "one stacked row per thread");
     static_assert(BM % 64 == 0, "a wavefront's rows belong to one operand");
     constexpr int TILE = NT * DK;                // bytes per stage buffer
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * TILE];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[4 * TILE];  // two stages being multiplied, two being written
+    __shared__ int terms[NT];                    // per-row terms of the result: W rows, then A rows (columns of C)
 
     bs::prefetch_kernel_arguments<(int)sizeof(PlanesParams)>();
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -139,68 +136,80 @@ planes_mfma_kernel(const PlanesParams p)
     const int tile_m = blockIdx.x / p.d.gx, tile_n = blockIdx.x % p.d.gx;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-    // ---- this thread's row: operand, plane pointers, plane masks, code tables ----
+    // ---- this thread's row: operand, the plane each code-bit slot takes, masks ----
     const bool isW = tid < BM;
-    const int bits = isW ? p.wbits : p.abits;
-    const bool bip = (isW ? p.wbip : p.abip) != 0;
+    const OperandCoding cd = isW ? p.cw : p.ca;
     const int rows = isW ? p.d.M : p.d.N;
     int row = isW ? m0 + tid : n0 + (tid - BM);
     if (row >= rows) row = rows - 1;             // clamped: its products land in outputs that are never stored
     const uint32_t *base = (isW ? p.Wp : p.Ap) + (size_t)row * p.Kd;
     const uint32_t *pl_ptr[NB];
-    uint32_t keep[NB];                           // all ones for a plane the operand has
+    uint32_t plain[NB], flipped[NB];             // all ones where the slot holds a plane as it is / the inverted top plane
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
-        const int qe = q < bits ? q : bits - 1;  // a missing plane reads an existing one (and is masked off)
-        pl_ptr[q] = base + (size_t)qe * rows * p.Kd;
-        keep[q] = (q < bits) ? 0xFFFFFFFFu : 0u;
+        const int pl = q - cd.shift;             // plane of this slot
+        const bool has = pl >= 0 && pl < cd.bits;
+        pl_ptr[q] = base + (size_t)(has ? pl : 0) * rows * p.Kd;  // an empty slot reads plane 0 and is masked off
+        plain[q] = (has && q != cd.top) ? 0xFFFFFFFFu : 0u;
+        flipped[q] = (has && q == cd.top) ? 0xFFFFFFFFu : 0u;
+        // plain data from here on: x = (r & plain) | (~r & flipped) is one three-input bit operation per word; knowing how
+        // the masks came about, the compiler would build selects on their conditions instead
+        asm volatile("" : "+v"(plain[q]), "+v"(flipped[q]));
     }
-    const uint32_t valid_on = bip ? 0xFFFFFFFFu : 0u;  // bipolar: plane 1 := "index < K"
-    const uint32_t lutX = isW ? p.lutW[0] : p.lutA[0], lutY = isW ? p.lutW[1] : p.lutA[1];
+    int popc[NB];                                // popcounts of this row's slots over the depth (for the row-sum terms)
+#pragma unroll
+    for (int q = 0; q < NB; ++q) popc[q] = 0;
     unsigned char *const my_row = lds + tid * DK;
     const int wsw = (tid >> 1) & 3;              // chunk swizzle of this row
 
-    uint32_t R[2][NB][DW];
-    auto fetch = [&](int set, int stage) {
-        const int s = stage < p.nst ? stage : p.nst - 1;  // past the depth: any valid address; the result is never multiplied
+    // Plane words of one period (two stages) of this row: one request per slot and period where 16 bytes hold both
+    // stages (int8 kind), two where they hold one (fp4 kind).  Every lane of a request reads another row, i.e. another
+    // cache line, and those line look-ups are what bounds the loader: the fewer requests the better.
+    uint32_t R[NB][PW];
+    auto fetch = [&](int period) {
+        const int s = period < p.nper ? period : p.nper - 1;  // past the depth: any valid address; the words are zeroed on use
 #pragma unroll
         for (int q = 0; q < NB; ++q) {
-            if constexpr (DW == 4) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(pl_ptr[q] + s * 4);
-                R[set][q][0] = v.x; R[set][q][1] = v.y; R[set][q][2] = v.z; R[set][q][3] = v.w;
-            } else {
-                const uint2 v = *reinterpret_cast<const uint2 *>(pl_ptr[q] + s * 2);
-                R[set][q][0] = v.x; R[set][q][1] = v.y;
+            const uint4 v = *reinterpret_cast<const uint4 *>(pl_ptr[q] + s * PW);
+            R[q][0] = v.x; R[q][1] = v.y; R[q][2] = v.z; R[q][3] = v.w;
+            if constexpr (PW == 8) {
+                // the second stage of the last period may not exist (the row ends with the first): stay inside the row
+                const int o = s * PW + 4 < p.Kd ? s * PW + 4 : p.Kd - 4;
+                const uint4 u = *reinterpret_cast<const uint4 *>(pl_ptr[q] + o);
+                R[q][4] = u.x; R[q][5] = u.y; R[q][6] = u.z; R[q][7] = u.w;
             }
         }
     };
-    // Expands plane dword dwi of the stage held in register set `set` and writes its chunks into buffer `buf`.
-    auto expand_dword = [&](int set, int buf, int stage, int dwi) {
-        uint32_t x[NB];
-        x[0] = R[set][0][dwi];                   // every operand has plane 0
-#pragma unroll
-        for (int q = 1; q < NB; ++q) x[q] = R[set][q][dwi] & keep[q];
-        // validity of the 32 indices of this dword (uniform, scalar arithmetic): ones below the depth
-        const int left = p.K32 - 32 * (stage * DW + dwi);
-        const uint32_t vm = left >= 32 ? 0xFFFFFFFFu : (left <= 0 ? 0u : ((1u << left) - 1u));
-        x[1] |= vm & valid_on;
+    // Expands stage `stage` (half `h` of the period in R) and writes its four chunks into stage buffer `buf`.
+    // TAIL: the stage may be the last one (an inverted top plane is cut off at the depth) or lie past the depth (the
+    // pipeline touches up to three such stages at its end; they become zero codes and stay out of the row sums).
+    auto expand_stage = [&](auto tail_c, int buf, int stage, int h) {
+        constexpr bool TAIL = decltype(tail_c)::value;
         unsigned char *dst = my_row + buf * TILE;
-        if constexpr (FP4) {
-            *reinterpret_cast<uint4 *>(dst + 16 * (dwi ^ wsw)) = expand32_fp4(x[0], x[1], lutX, lutY);
-        } else {
-            uint4 o0, o1;
-            expand32_i8(x, lutX, lutY, o0, o1);
-            *reinterpret_cast<uint4 *>(dst + 16 * ((2 * dwi) ^ wsw)) = o0;
-            *reinterpret_cast<uint4 *>(dst + 16 * ((2 * dwi + 1) ^ wsw)) = o1;
-        }
-    };
-    // half 0: the chunks depth step 0 reads (0, 1); half 1: chunks 2, 3
-    auto expand_half = [&](int set, int buf, int stage, int half) {
-        if constexpr (FP4) {
-            expand_dword(set, buf, stage, 2 * half);
-            expand_dword(set, buf, stage, 2 * half + 1);
-        } else {
-            expand_dword(set, buf, stage, half);
+#pragma unroll
+        for (int d = 0; d < DW; ++d) {
+            uint32_t vm = 0xFFFFFFFFu, live = 0xFFFFFFFFu;
+            if constexpr (TAIL) {
+                // validity of the 32 indices of this dword (uniform, scalar arithmetic): ones below the depth
+                const int left = p.K32 - 32 * (stage * DW + d);
+                vm = left >= 32 ? 0xFFFFFFFFu : (left <= 0 ? 0u : ((1u << left) - 1u));
+                live = stage < p.nst ? 0xFFFFFFFFu : 0u;
+            }
+            uint32_t x[NB];
+#pragma unroll
+            for (int q = 0; q < NB; ++q) {
+                const uint32_t r = R[q][h * DW + d];
+                x[q] = TAIL ? (((r & plain[q]) | (~r & flipped[q] & vm)) & live) : ((r & plain[q]) | (~r & flipped[q]));
+                popc[q] += __builtin_popcount(x[q]);
+            }
+            if constexpr (FP4) {
+                *reinterpret_cast<uint4 *>(dst + 16 * (d ^ wsw)) = expand32_fp4(x[0], x[1]);
+            } else {
+                uint4 o0, o1;
+                expand32_i8(x, o0, o1);
+                *reinterpret_cast<uint4 *>(dst + 16 * ((2 * d) ^ wsw)) = o0;
+                *reinterpret_cast<uint4 *>(dst + 16 * ((2 * d + 1) ^ wsw)) = o1;
+            }
         }
     };
 
@@ -230,101 +239,99 @@ planes_mfma_kernel(const PlanesParams p)
 #pragma unroll
             for (int b = 0; b < WTN; ++b) acc[a][b] = mma<FP4>(fa[set][a], fb[set][b], acc[a][b]);
     };
-    // spread the vector work of a half between its matrix instructions
-    auto interleave = [&]() {
+    // spread the other work of a quarter between its matrix instructions: NV vector instructions and one LDS read each
+    auto interleave = [&](auto nv_c) {
+        constexpr int NV = decltype(nv_c)::value;
 #pragma unroll
         for (int r = 0; r < WTM * WTN; ++r) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                          // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x002, FP4 ? 150 / (WTM * WTN) + 1 : 140 / (WTM * WTN) + 1, 0);  // VALU
+            if constexpr (NV > 0) __builtin_amdgcn_sched_group_barrier(0x002, NV, 0);   // VALU
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                          // DS read
         }
     };
+    constexpr std::integral_constant<int, 0> kNoValu{};
+    constexpr std::integral_constant<int, (FP4 ? 80 : 110) / (WTM * WTN) + 1> kExpandValu{};
 
-    // One iteration = one stage (see the header comment).  PAR: parity of the stage = its LDS buffer and register set.
-    auto step = [&](auto par, int i) {
-        constexpr int PAR = decltype(par)::value;
-        expand_half(PAR ^ 1, PAR ^ 1, i + 1, 1);
-        load_frags(1, PAR, 1);
+    // One period = two stages = four depth steps ("quarters").  PP: parity of the period; its stages sit in LDS
+    // buffers 2 PP and 2 PP + 1, the next period's stages are written into the other two.  The fragments of a quarter
+    // are read during the quarter before.  Quarter 1 expands the next period's first stage, quarter 2 its second one;
+    // the barrier behind quarter 2 is the only one of the period: by then every wavefront has written its rows of the
+    // next two stages and has received the last fragments of this period (read in quarter 2), so quarter 3 may read the
+    // next period's first fragments and request the plane words of the period after next into R, which the two
+    // expansions have just released.  TAIL: one of the stages to expand may be the last one or lie past the depth.
+    auto period = [&](auto pp_c, auto tail_c, int P) {
+        constexpr int PP = decltype(pp_c)::value;
+        constexpr int B0 = 2 * PP, B1 = 2 * PP + 1, N0 = 2 * (PP ^ 1), N1 = 2 * (PP ^ 1) + 1;
+        load_frags(1, B0, 1);
         mfmas(0);
-        interleave();
+        interleave(kNoValu);
         __builtin_amdgcn_sched_barrier(0);
-        // every LDS operation of this wavefront is complete (reads of this stage arrived, writes of the next one
-        // done) before anybody goes on
+        expand_stage(tail_c, N0, 2 * P + 2, 0);
+        load_frags(0, B1, 0);
+        mfmas(1);
+        interleave(kExpandValu);
+        __builtin_amdgcn_sched_barrier(0);
+        expand_stage(tail_c, N1, 2 * P + 3, 1);
+        load_frags(1, B1, 1);
+        mfmas(0);
+        interleave(kExpandValu);
+        __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
-        fetch(PAR ^ 1, i + 3);
-        load_frags(0, PAR ^ 1, 0);
-        expand_half(PAR, PAR, i + 2, 0);
+        fetch(P + 2);
+        load_frags(0, N0, 0);
         mfmas(1);
-        interleave();
+        interleave(kNoValu);
         __builtin_amdgcn_sched_barrier(0);
     };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
 
-    fetch(0, 0);
-    fetch(1, 1);
-    expand_half(0, 0, 0, 0);
-    expand_half(0, 0, 0, 1);
-    fetch(0, 2);
-    expand_half(1, 1, 1, 0);
+    // prologue: the first period expanded, the second requested
+    fetch(0);
+    expand_stage(std::true_type{}, 0, 0, 0);
+    expand_stage(std::true_type{}, 1, 1, 1);
+    fetch(1);
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     load_frags(0, 0, 0);
-    int i = 0;
-    for (; i + 1 < p.nst; i += 2) {
-        step(std::integral_constant<int, 0>{}, i);
-        step(std::integral_constant<int, 1>{}, i + 1);
+    int P = 0;
+    for (; 2 * P + 7 <= p.nst; P += 2) {          // the stages expanded here (up to 2 P + 5) lie wholly inside the depth
+        period(I0{}, std::false_type{}, P);
+        period(I1{}, std::false_type{}, P + 1);
     }
-    if (i < p.nst) step(std::integral_constant<int, 0>{}, i);
+    for (; P + 1 < p.nper; P += 2) {
+        period(I0{}, std::true_type{}, P);
+        period(I1{}, std::true_type{}, P + 1);
+    }
+    if (P < p.nper) period(I0{}, std::true_type{}, P);
 
-    dense_epilogue<WTM, WTN, FUSE, FP4, WGM, WGN>(p.d, acc, lds, m0, n0, tile_m);
+    // ---- per-row terms of the affine correction: slot q carries weight 2^(q - shift) of the unsigned code ----
+    {
+        int rs = 0;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) rs = wrap_add(rs, (q - cd.shift >= 0) ? (popc[q] << (q - cd.shift)) : 0);
+        terms[tid] = isW ? wrap_add(wrap_mul(p.row_coef, rs), p.row_const) : wrap_mul(p.col_coef, rs);
+    }
+    __syncthreads();
+    PlanesResult result{p.mul, p.acc_scale, terms, terms + BM};
+    dense_epilogue<WTM, WTN, FUSE, FP4, WGM, WGN>(p.d, acc, lds, m0, n0, tile_m, result);
 }
 
-int fp4_code(int v)
+// v = alpha u + beta with u the unsigned code the kernel multiplies
+void affine_of(int bits, bs_format fmt, int &alpha, int &beta)
 {
-    const int mag = v < 0 ? -v : v;
-    int code;
-    switch (mag) {
-    case 0: code = 0x0; break;
-    case 1: code = 0x2; break;
-    case 2: code = 0x4; break;
-    case 3: code = 0x5; break;
-    case 4: code = 0x6; break;
-    case 6: code = 0x7; break;
-    default: return -1;
-    }
-    return v < 0 ? (code | 0x8) : code;
+    alpha = 1; beta = 0;
+    if (fmt == BS_BIPOLAR) { alpha = 2; beta = -1; }
+    if (fmt == BS_TWOS_COMPLEMENT) beta = -(1 << (bits - 1));
 }
 
-// Value tables of one operand, indexed by the 2-bit field (b_lo | b_hi << 1) of a plane pair.
-void value_tables(int bits, bs_format fmt, int (&v01)[4], int (&v23)[4])
+OperandCoding coding_of(int bits, bs_format fmt, bool fp4)
 {
-    int cw[4] = {0, 0, 0, 0};
-    for (int i = 0; i < bits; ++i) cw[i] = (fmt == BS_TWOS_COMPLEMENT && i == bits - 1) ? -(1 << i) : (1 << i);
-    for (int f = 0; f < 4; ++f) {
-        v01[f] = cw[0] * (f & 1) + cw[1] * (f >> 1);
-        v23[f] = cw[2] * (f & 1) + cw[3] * (f >> 1);
-    }
-    if (fmt == BS_BIPOLAR) {  // plane 1 is the synthetic "index < K" plane
-        v01[0] = 0; v01[1] = 0; v01[2] = -1; v01[3] = 1;
-    }
-}
-
-bool fill_tables(int bits, bs_format fmt, bool fp4, uint32_t (&lut)[4])
-{
-    int v01[4], v23[4];
-    value_tables(bits, fmt, v01, v23);
-    lut[0] = lut[1] = lut[2] = lut[3] = 0;
-    for (int f = 0; f < 4; ++f) {
-        if (fp4) {
-            const int c = fp4_code(v01[f]);
-            if (c < 0 || v23[f] != 0) return false;
-            lut[0] |= (uint32_t)c << (8 * f);
-            lut[1] |= (uint32_t)(c << 4) << (8 * f);
-        } else {
-            lut[0] |= (uint32_t)(v01[f] & 0xFF) << (8 * f);
-            lut[1] |= (uint32_t)(v23[f] & 0xFF) << (8 * f);
-        }
-    }
-    return true;
+    OperandCoding c;
+    c.bits = bits;
+    c.shift = fp4 ? 2 - bits : 0;
+    c.top = fmt == BS_TWOS_COMPLEMENT ? c.shift + bits - 1 : -1;
+    return c;
 }
 
 template <bool FP4, int WTM, int WTN, int WGM, int WGN>
@@ -359,7 +366,8 @@ bool planes_mfma_supported(int wbits, bs_format wfmt, int abits, bs_format afmt,
     if (K >= (int64_t(1) << 30)) return false;  // the kernels count depth indices in 32 bits
     if (!fp4) return true;
     if (wbits > 2 || abits > 2) return false;
-    return K * max_abs(wbits, wfmt) * max_abs(abits, afmt) < (int64_t(1) << 24);  // fp32 accumulation stays exact
+    // the fp32 sum of products of unsigned codes (in quarter steps) stays exact
+    return K * ((int64_t(1) << wbits) - 1) * ((int64_t(1) << abits) - 1) < (int64_t(1) << 24);
 }
 
 bs_status launch_planes_mfma(const PlanesGemm &q, bool fp4, bool fuse, hipStream_t st)
@@ -371,12 +379,21 @@ bs_status launch_planes_mfma(const PlanesGemm &q, bool fp4, bool fuse, hipStream
     p.d.thr = q.thr; p.d.obits = q.obits; p.d.T = fuse ? (1 << q.obits) - 1 : 0;
     p.d.Y = q.Y; p.d.Yd = q.Yd;
     p.Wp = q.W; p.Ap = q.A; p.Kd = q.Kd;
-    p.wbits = q.wbits; p.abits = q.abits;
-    p.wbip = q.wfmt == BS_BIPOLAR; p.abip = q.afmt == BS_BIPOLAR;
+    p.cw = coding_of(q.wbits, q.wfmt, fp4);
+    p.ca = coding_of(q.abits, q.afmt, fp4);
     p.K32 = (int)q.K;
+    int aw, bw, aa, ba;
+    affine_of(q.wbits, q.wfmt, aw, bw);
+    affine_of(q.abits, q.afmt, aa, ba);
+    p.mul = aw * aa;
+    p.row_coef = aw * ba;
+    p.row_const = (int)((unsigned)(bw * ba) * (unsigned)q.K);   // modulo 2^32, like every sum of terms
+    p.col_coef = bw * aa;
+    // a 2-bit code in an E2M1 nibble is the number u / 2
+    p.acc_scale = fp4 ? (float)((q.wbits == 2 ? 2 : 1) * (q.abits == 2 ? 2 : 1)) : 1.0f;
     const int per_stage = fp4 ? 128 : 64;
     p.nst = (int)((q.K + per_stage - 1) / per_stage);
-    if (!fill_tables(q.wbits, q.wfmt, fp4, p.lutW) || !fill_tables(q.abits, q.afmt, fp4, p.lutA)) return BS_ERR_UNSUPPORTED;
+    p.nper = (p.nst + 1) / 2;
     return fp4 ? launch_kind<true>(p, fuse, st) : launch_kind<false>(p, fuse, st);
 }
 

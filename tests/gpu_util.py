@@ -43,21 +43,14 @@ ENGINE_NAMES = {bs.BS_ENGINE_AUTO: "auto", bs.BS_ENGINE_BITSERIAL: "bit-serial",
                 bs.BS_ENGINE_DENSE_FP4: "fp4 matrix cores"}
 
 
-def _max_abs(bits, fmt):
-    """Largest magnitude of a value of the format (bs format constants)."""
-    if fmt == bs.BS_BIPOLAR:
-        return 1
-    return (1 << (bits - 1)) if fmt == bs.BS_TWOS_COMPLEMENT else (1 << bits) - 1
-
-
 def engines_for(wbits, wfmt, abits, afmt, K):
     """Every engine that can take a wbits x abits product of depth K from packed planes (bs format constants):
     the library's own choice, the AND-popcount kernels, the int8 matrix-core kernel, and the fp4 one for operands
-    of at most two bits while the fp32 accumulation is exact."""
+    of at most two bits while its fp32 sum of products of unsigned codes is exact."""
     e = [bs.BS_ENGINE_AUTO, bs.BS_ENGINE_BITSERIAL]
     if K < (1 << 30):
         e.append(bs.BS_ENGINE_DENSE_I8)
-        if wbits <= 2 and abits <= 2 and K * _max_abs(wbits, wfmt) * _max_abs(abits, afmt) < (1 << 24):
+        if wbits <= 2 and abits <= 2 and K * ((1 << wbits) - 1) * ((1 << abits) - 1) < (1 << 24):
             e.append(bs.BS_ENGINE_DENSE_FP4)
     return e
 

@@ -55,10 +55,10 @@ def test_argument_errors_are_rejected_on_the_host():
     assert lib.bs_gemm(p, 1, 2, p, 1, 2, 4, 4, 1 << 31, p, 4, None) == bs.BS_ERR_OVERFLOW_RISK
     # the approximate mode sums a subset of the plane pairs: bounded by the unsigned ranges, 15 * 15 * K
     assert lib.bs_gemm_topbits(p, 4, 1, p, 4, 0, 4, 4, 9544372, 3, p, 4, None) == bs.BS_ERR_OVERFLOW_RISK
-    # engines: unknown value; the fp4 matrix-core kernel takes operands of at most two bits and K max|w| max|a| < 2^24
+    # engines: unknown value; the fp4 matrix-core kernel takes operands of at most two bits and 9 K < 2^24 for two planes each
     assert lib.bs_gemm_on(7, p, 1, 0, p, 1, 0, 4, 4, 64, p, 4, None) == bs.BS_ERR_INVALID_ARG
     assert lib.bs_gemm_on(bs.BS_ENGINE_DENSE_FP4, p, 3, 1, p, 2, 0, 4, 4, 64, p, 4, None) == bs.BS_ERR_UNSUPPORTED
-    assert lib.bs_gemm_on(bs.BS_ENGINE_DENSE_FP4, p, 2, 1, p, 2, 0, 4, 4, 2796203, p, 4, None) == bs.BS_ERR_UNSUPPORTED
+    assert lib.bs_gemm_on(bs.BS_ENGINE_DENSE_FP4, p, 2, 1, p, 2, 0, 4, 4, 1864136, p, 4, None) == bs.BS_ERR_UNSUPPORTED   # 9 K >= 2^24
     assert lib.bs_gemm_threshold_on(bs.BS_ENGINE_DENSE_I8, p, 1, 2, p, 1, 2, 4, 4, 1 << 30, p, 1, p, None) == bs.BS_ERR_UNSUPPORTED
     assert lib.bs_gemm_threshold(p, 1, 0, p, 1, 0, 4, 4, 64, None, 2, p, None) == bs.BS_ERR_INVALID_ARG
     assert lib.bs_gemm_threshold(p, 1, 0, p, 1, 0, 4, 4, 64, p, 5, p, None) == bs.BS_ERR_UNSUPPORTED

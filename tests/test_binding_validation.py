@@ -145,10 +145,11 @@ def test_dense_operands():
 
 def test_engine_choice_respects_the_dense_engines_depth_limits():
     """bs_choose_engine never names an engine whose kernel would refuse the call: the fp4 kernel needs
-    K max|w| max|a| < 2^24, both dense kernels K < 2^30."""
+    K (2^wbits - 1) (2^abits - 1) < 2^24, both dense kernels K < 2^30."""
     E = bs.bs_choose_engine
     assert E(2, TC, 2, U, 4096, 4096, 4096) == bs.BS_ENGINE_DENSE_FP4
-    assert E(2, TC, 2, U, 4096, 4096, 2796203) == bs.BS_ENGINE_DENSE_I8      # 2 * 3 * K >= 2^24: int32 accumulation instead
+    assert E(2, TC, 2, U, 4096, 4096, 1864136) == bs.BS_ENGINE_DENSE_I8      # 3 * 3 * K >= 2^24: int32 accumulation instead
+    assert E(2, TC, 2, U, 4096, 4096, 1864135) == bs.BS_ENGINE_DENSE_FP4
     assert E(1, BP, 1, BP, 4096, 4096, 1 << 24) == bs.BS_ENGINE_DENSE_I8
     assert E(1, BP, 1, BP, 4096, 4096, (1 << 24) - 1) == bs.BS_ENGINE_DENSE_FP4
     assert E(1, BP, 4, U, 4096, 4096, 1 << 30) == bs.BS_ENGINE_BITSERIAL
