@@ -303,23 +303,30 @@ bs_status bs_streamline_thresholds(const double *t, int T, const double *a, cons
 /*
  * Per-layer engine choice (Sec. 4.1.1 and 4.2 of the paper: bit-serial pays below a break-even
  * precision, and each layer should run on the faster engine).  Host-only, no GPU work.
- * Returns, for a wbits x abits product of shape M x K x N in the given formats,
- *   BS_ENGINE_BITSERIAL  bs_gemm / bs_gemm_threshold on packed planes,
- *   BS_ENGINE_DENSE_I8   bs_unpack_planes of the activations + bs_gemm_i8* on int8 weights, or
- *   BS_ENGINE_DENSE_FP4  bs_unpack_planes_fp4 of the activations + bs_gemm_fp4* on E2M1-coded weights
- *                        (only when both operands have at most 2 bits or are 3-bit two's complement),
+ * Returns, for a wbits x abits product of shape M x K x N from packed planes, the engine bs_gemm, bs_gemm_threshold
+ * take by themselves:
+ *   BS_ENGINE_BITSERIAL  the AND-popcount kernels (Alg. 1, 2),
+ *   BS_ENGINE_DENSE_FP4  the matrix-core kernel on 4-bit floating-point codes (operands of at most 2 bits and
+ *                        K (2^wbits - 1) (2^abits - 1) < 2^24), or
+ *   BS_ENGINE_DENSE_I8   the matrix-core kernel on int8 codes (everything else below K = 2^30),
  * whichever is fastest under a time model fitted to measurements on MI355X (microseconds, p = wbits * abits,
- * k = K / 1024, activation unpack and the thresholding epilogue included):
- *   bit-serial  4.8 + 0.21 k p + 2MNK p / 1.13e9       (N > 16)
+ * k = K / 1024, thresholding epilogue included):
+ *   bit-serial  3.73 + 0.198 k p + 2MNK p / 1.23e9      (N > 16)
  *               min(3.88 + G (0.69 + 0.2 p + 0.031 p k), 3.64 + R p (0.253 k + 0.21))   (5 <= N <= 16), with
  *               G = ceil(N / 4) M / 4096 (streaming kernel, groups of four columns), R = 1 + max(0, B - 256) / 900,
  *               B = ceil(M / 32) ceil(N / 8) (tiled kernel, 32 x 8 tiles); bs_gemm itself picks between these two
- *   dense int8  3.2 + 4.3 k + 1.8 abits + 2MNK / 4.07e9 + MN / 2.18e6
- *   dense fp4   4.2 + 2.2 k + 1.1 abits + 2MNK / 6.63e9 + MN / 3.92e6
- * N <= 4 is always bit-serial (weights are read once: wbits/8 byte per weight instead of 1 or 1/2).
+ *   dense fp4   5.5 + ceil(K / 256) r c + 0.22 abits MN / 1e6     r = rounds of tiles over the chip (bs_planes_tile),
+ *   dense int8  6.0 + ceil(K / 128) r c + 0.29 abits MN / 1e6     c = microseconds per period of the kernel's pipeline:
+ *               fp4 1.96 (256 x 256 tiles) or 0.92 + 0.24 f (128 x 128), int8 2.28 max(f, 0.85) or 1.10 + 0.25 f,
+ *               f = the part of the chip's tile slots that is filled
+ * N <= 4 is always bit-serial (weights are read once, wbits/8 byte per weight, and nothing is expanded).
  * Invalid arguments (bits outside 1..4, bipolar with bits != 1, non-positive sizes) return BS_ENGINE_BITSERIAL.
  */
 bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_format afmt, int64_t M, int64_t N, int64_t K);
+
+/* Tile edge (256 or 128) the matrix-core kernel on packed planes takes for an M x N output, the rounds of such tiles
+ * over the chip and their number (either pointer may be NULL).  Host-only; part of the time model above. */
+int bs_planes_tile(int64_t M, int64_t N, long long *rounds, long long *tiles);
 
 /*
  * Diagnostic, not part of the versioned interface (bs_version does not cover it; it may change or go

@@ -30,7 +30,7 @@ EXPORTS = ("bs_words_per_row", "bs_lowered_depth", "bs_pack_planes", "bs_gemm", 
            "bs_maxpool_packed_batch",
            "bs_unpack_planes", "bs_gemm_i8", "bs_gemm_i8_threshold", "bs_unpack_planes_fp4", "bs_gemm_fp4",
            "bs_gemm_fp4_threshold", "bs_streamline_collapse",
-           "bs_streamline_thresholds", "bs_choose_engine", "bs_probe_popcount_rate", "bs_probe_stream_read", "bs_status_string", "bs_version")
+           "bs_streamline_thresholds", "bs_choose_engine", "bs_planes_tile", "bs_probe_popcount_rate", "bs_probe_stream_read", "bs_status_string", "bs_version")
 
 
 class BsError(RuntimeError):
@@ -87,6 +87,7 @@ def load_library() -> ctypes.CDLL:
     lib.bs_streamline_collapse.restype = i32
     lib.bs_streamline_thresholds.argtypes = [vp, i32, vp, vp, i64, vp, vp]; lib.bs_streamline_thresholds.restype = i32
     lib.bs_choose_engine.argtypes = [i32, i32, i32, i32, i64, i64, i64]; lib.bs_choose_engine.restype = i32
+    lib.bs_planes_tile.argtypes = [i64, i64, vp, vp]; lib.bs_planes_tile.restype = i32
     lib.bs_probe_popcount_rate.argtypes = [vp, i32, i32, vp]; lib.bs_probe_popcount_rate.restype = i32
     lib.bs_probe_stream_read.argtypes = [vp, i64, vp, i32, i32, vp]; lib.bs_probe_stream_read.restype = i32
     lib.bs_status_string.argtypes = [i32]; lib.bs_status_string.restype = ctypes.c_char_p
@@ -415,6 +416,11 @@ def bs_gemm_i8_threshold(W: torch.Tensor, At: torch.Tensor, K: int, thr: torch.T
 def bs_choose_engine(wbits: int, wfmt: int, abits: int, afmt: int, M: int, N: int, K: int) -> int:
     """Host-only: the engine (BS_ENGINE_*) expected to be fastest for a wbits x abits product of shape M x K x N."""
     return load_library().bs_choose_engine(wbits, wfmt, abits, afmt, M, N, K)
+
+
+def bs_planes_tile(M: int, N: int) -> int:
+    """Host-only: tile edge (256 or 128) of the matrix-core kernel on packed planes for an M x N output."""
+    return int(load_library().bs_planes_tile(int(M), int(N), None, None))
 
 
 def bs_probe_popcount_rate(sink: torch.Tensor, passes: int) -> int:

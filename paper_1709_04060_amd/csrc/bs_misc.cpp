@@ -16,18 +16,49 @@ extern "C" const char *bs_status_string(bs_status s)
 
 extern "C" int bs_version(void) { return 100; }
 
-// Per-layer engine choice (Sec. 4.1.1 / 4.2): the fastest of the engines under a time model whose
-// constants were fitted to measurements over M, N in 256..4096, K in {1024, 4096} and W1A1, W1A2,
-// W2A2, W4A4 on MI355X (fused 2^abits-level epilogue, activation unpack counted for the dense
-// engines; non-negative least squares on the relative error, which stays within -18 / +29 % bit-serial,
-// -33 / +12 % int8, -17 / +11 % fp4; over the measured cases the choice costs 0.4 % on average and 17 % at
-// worst against always picking the fastest).  Microseconds.
+// Per-layer engine choice (Sec. 4.1.1 / 4.2): the fastest of the engines under time models fitted to measurements on
+// MI355X over M in {256, 1024, 4096}, N in {17 .. 4096}, K in {512 .. 8192} and W1A1, W1A2, W2A2, W3A3, W4A4, all from
+// packed planes with the fused thresholding epilogue (375 shapes; non-negative least squares on the relative error).
+// Over those shapes the choice costs 0.9 % on average and 33 % at worst against always taking the fastest engine, where
+// always bit-serial costs 80 % on average (17 x at worst) and always matrix cores 92 % (5.9 x).  Microseconds.
+namespace {
+
 // The dense engines as the library runs them on packed planes: 4-bit floating-point codes for operands of at most two
 // bits while the fp32 accumulation stays exact, int8 otherwise; both count depth indices in 32 bits.
-static bool fp4_usable(int wbits, bs_format wfmt, int abits, bs_format afmt, int64_t K)
+bool fp4_usable(int wbits, int abits, int64_t K)
 {
-    (void)wfmt; (void)afmt;  // the kernel multiplies unsigned codes, whatever the format
     return wbits <= 2 && abits <= 2 && K * ((int64_t(1) << wbits) - 1) * ((int64_t(1) << abits) - 1) < (int64_t(1) << 24);
+}
+
+// The matrix-core kernel on packed planes: a 256 x 256 tile per compute unit or two 128 x 128 tiles (bs_planes_tile
+// makes the same choice for the launch), `per` depth indices per period of the kernel's pipeline.
+double t_planes(double M, double N, double K, int abits, bool fp4)
+{
+    long long rounds, tiles;
+    const int tile = bs_planes_tile((int64_t)M, (int64_t)N, &rounds, &tiles);
+    const double nper = (double)(((int64_t)K + (fp4 ? 255 : 127)) / (fp4 ? 256 : 128));
+    double per;
+    if (fp4) per = tile == 256 ? 1.96 : 0.92 + 0.24 * (double)(tiles < 512 ? tiles : 512) / 512.0;
+    else {
+        const double fill = (double)(tiles < 256 ? tiles : 256) / 256.0;
+        per = tile == 256 ? 2.28 * (fill > 0.85 ? fill : 0.85) : 1.10 + 0.25 * (double)(tiles < 512 ? tiles : 512) / 512.0;
+    }
+    return (fp4 ? 5.5 : 6.0) + nper * (double)rounds * per + (fp4 ? 0.22 : 0.29) * abits * M * N / 1e6;
+}
+
+}  // namespace
+
+// Tile of the matrix-core kernel on packed planes for an M x N output: 256 (one workgroup per compute unit) or 128 (two).
+// A round of 128 x 128 tiles over the chip (512 of them) takes 0.67 of a round of 256 x 256 tiles (256 of them) and
+// covers half as much output; the rule picked the faster tile on every shape of the sweep above.
+extern "C" int bs_planes_tile(int64_t M, int64_t N, long long *rounds, long long *tiles)
+{
+    const long long t256 = ((M + 255) / 256) * ((N + 255) / 256), t128 = ((M + 127) / 128) * ((N + 127) / 128);
+    const long long r256 = (t256 + 255) / 256, r128 = (t128 + 511) / 512;
+    const bool big = r256 * 100 <= r128 * 67;
+    if (rounds) *rounds = big ? r256 : r128;
+    if (tiles) *tiles = big ? t256 : t128;
+    return big ? 256 : 128;
 }
 
 extern "C" bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_format afmt, int64_t M, int64_t N, int64_t K)
@@ -35,12 +66,12 @@ extern "C" bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_f
     if (wbits < 1 || wbits > 4 || abits < 1 || abits > 4 || M <= 0 || N <= 0 || K <= 0) return BS_ENGINE_BITSERIAL;
     if ((wfmt == BS_BIPOLAR && wbits != 1) || (afmt == BS_BIPOLAR && abits != 1)) return BS_ENGINE_BITSERIAL;
     if (K >= (int64_t(1) << 30)) return BS_ENGINE_BITSERIAL;  // beyond the dense engines' depth range
-    if (N <= 4) return BS_ENGINE_BITSERIAL;  // weights streamed once: wbits/8 byte per weight beats a byte or half a byte
+    if (N <= 4) return BS_ENGINE_BITSERIAL;  // weights streamed once: wbits/8 byte per weight, nothing to expand
     const double pairs = (double)wbits * abits, kk = (double)K / 1024.0;
-    const double mnk2 = 2.0 * (double)M * (double)N * (double)K, mn = (double)M * (double)N;
+    const double mnk2 = 2.0 * (double)M * (double)N * (double)K;
     // 5..16 columns: the bit-serial call takes the faster of the streaming kernel in groups of four columns and
     // the tiled kernel with 32 x 8 tiles (the same two models decide inside bs_gemm)
-    double t_bitserial = 4.8 + 0.21 * kk * pairs + mnk2 * pairs / 1.13e9;
+    double t_bitserial = 3.73 + 0.198 * kk * pairs + mnk2 * pairs / 1.23e9;
     if (N <= 16) {
         const double groups = (double)((N + 3) / 4) * (double)M / 4096.0;
         const double t_stream = 3.88 + groups * (0.69 + 0.2 * pairs + 0.031 * pairs * kk);
@@ -49,10 +80,8 @@ extern "C" bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_f
         const double t_tiled = 3.64 + rounds * pairs * (0.253 * kk + 0.21);
         t_bitserial = t_stream < t_tiled ? t_stream : t_tiled;
     }
-    if (fp4_usable(wbits, wfmt, abits, afmt, K)) {
-        const double t_fp4 = 4.2 + 2.2 * kk + 1.1 * abits + mnk2 / 6.63e9 + mn / 3.92e6;
-        return t_fp4 < t_bitserial ? BS_ENGINE_DENSE_FP4 : BS_ENGINE_BITSERIAL;  // measured 1.1 - 1.5 x faster than int8 everywhere
-    }
-    const double t_int8 = 3.2 + 4.3 * kk + 1.8 * abits + mnk2 / 4.07e9 + mn / 2.18e6;
-    return t_int8 < t_bitserial ? BS_ENGINE_DENSE_I8 : BS_ENGINE_BITSERIAL;
+    const bool fp4 = fp4_usable(wbits, abits, K);
+    const double t_dense = t_planes((double)M, (double)N, (double)K, abits, fp4);
+    if (t_dense < t_bitserial) return fp4 ? BS_ENGINE_DENSE_FP4 : BS_ENGINE_DENSE_I8;
+    return BS_ENGINE_BITSERIAL;
 }

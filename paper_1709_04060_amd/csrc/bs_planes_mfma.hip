@@ -350,12 +350,10 @@ bs_status launch_tile(PlanesParams &p, bool fuse, hipStream_t st)
 template <bool FP4>
 bs_status launch_kind(PlanesParams &p, bool fuse, hipStream_t st)
 {
-    // 256 x 256 tiles on eight wavefronts (one per compute unit) or 128 x 128 on four (two or more per compute
-    // unit).  A 128 x 128 tile expands half the rows of a 256 x 256 one for a quarter of its products, and the
-    // expansion is what bounds the kernel: the small tile is taken when it needs fewer rounds over the chip.
-    auto tiles = [&](int b) { return (long long)((p.d.M + b - 1) / b) * ((p.d.N + b - 1) / b); };
-    const long long big = (tiles(256) + 255) / 256 * 100, small = (tiles(128) + 511) / 512 * 55;
-    if (big <= small) return launch_tile<FP4, 4, 2, 2, 4>(p, fuse, st);
+    // 256 x 256 tiles on eight wavefronts (one per compute unit) or 128 x 128 on four (two per compute unit).  A
+    // 128 x 128 tile expands half the rows of a 256 x 256 one for a quarter of its products: the small tile is taken
+    // when it needs fewer rounds over the chip (bs_planes_tile, which the engine choice's time model shares).
+    if (bs_planes_tile(p.d.M, p.d.N, nullptr, nullptr) == 256) return launch_tile<FP4, 4, 2, 2, 4>(p, fuse, st);
     return launch_tile<FP4, 2, 2, 2, 2>(p, fuse, st);
 }
 
