@@ -212,6 +212,12 @@ bs_status bs_conv_threshold(const uint64_t *in, int abits, bs_format afmt, int H
 bs_status bs_conv_threshold_batch(const uint64_t *in, int abits, bs_format afmt, int B, int H, int W, int C,
                                   const uint64_t *Fp, int wbits, bs_format wfmt, int F, int kh, int kw,
                                   int stride, int pad, const int32_t *thr, int obits, uint64_t *Yp, void *stream);
+/* The same layer on a named engine (see bs_gemm_on; BS_ENGINE_AUTO is bs_conv_threshold_batch): the layer is the product
+ * F x Kl x (B OH OW), and the matrix-core kernels gather the lowered columns from the packed map themselves, so no
+ * lowered matrix exists on any engine. */
+bs_status bs_conv_threshold_batch_on(bs_engine engine, const uint64_t *in, int abits, bs_format afmt, int B, int H, int W,
+                                     int C, const uint64_t *Fp, int wbits, bs_format wfmt, int F, int kh, int kw,
+                                     int stride, int pad, const int32_t *thr, int obits, uint64_t *Yp, void *stream);
 
 /*
  * Max pooling of a few-bit feature map held as packed HWC planes (unsigned codes).  Not a

@@ -26,7 +26,7 @@ BS_I8, BS_I32 = 0, 1
 BS_ENGINE_BITSERIAL, BS_ENGINE_DENSE_I8, BS_ENGINE_DENSE_FP4, BS_ENGINE_AUTO = 0, 1, 2, 3
 
 EXPORTS = ("bs_words_per_row", "bs_lowered_depth", "bs_pack_planes", "bs_gemm", "bs_gemm_topbits", "bs_threshold_activate",
-           "bs_gemm_threshold", "bs_gemm_on", "bs_gemm_threshold_on", "bs_im2col_interleaved", "bs_im2col_interleaved_batch", "bs_conv_threshold", "bs_conv_threshold_batch", "bs_maxpool_packed",
+           "bs_gemm_threshold", "bs_gemm_on", "bs_gemm_threshold_on", "bs_im2col_interleaved", "bs_im2col_interleaved_batch", "bs_conv_threshold", "bs_conv_threshold_batch", "bs_conv_threshold_batch_on", "bs_maxpool_packed",
            "bs_maxpool_packed_batch",
            "bs_unpack_planes", "bs_gemm_i8", "bs_gemm_i8_threshold", "bs_unpack_planes_fp4", "bs_gemm_fp4",
            "bs_gemm_fp4_threshold", "bs_streamline_collapse",
@@ -71,6 +71,8 @@ def load_library() -> ctypes.CDLL:
     lib.bs_conv_threshold_batch.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, i32, i32, i32, i32, i32, i32, i32, vp, i32,
                                             vp, vp]
     lib.bs_conv_threshold_batch.restype = i32
+    lib.bs_conv_threshold_batch_on.argtypes = [i32] + lib.bs_conv_threshold_batch.argtypes
+    lib.bs_conv_threshold_batch_on.restype = i32
     lib.bs_maxpool_packed_batch.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.bs_maxpool_packed_batch.restype = i32
     lib.bs_maxpool_packed.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp]; lib.bs_maxpool_packed.restype = i32
@@ -319,16 +321,16 @@ def bs_im2col_interleaved_batch(x: torch.Tensor, B: int, H: int, W: int, C: int,
 
 def bs_conv_threshold(x: torch.Tensor, afmt: int, H: int, W: int, C: int, Fp: torch.Tensor, wfmt: int,
                       kh: int, kw: int, stride: int, pad: int, thr: torch.Tensor, obits: int,
-                      out: torch.Tensor | None = None) -> torch.Tensor:
+                      out: torch.Tensor | None = None, engine: int = BS_ENGINE_AUTO) -> torch.Tensor:
     """Convolution + thresholding on packed HWC planes x [abits][H*W][S_C] with filter planes
     Fp [wbits][F][S_Kl]; returns the packed HWC planes [obits][OH*OW][S_F] of the output map."""
-    return bs_conv_threshold_batch(x, afmt, 1, H, W, C, Fp, wfmt, kh, kw, stride, pad, thr, obits, out=out)
+    return bs_conv_threshold_batch(x, afmt, 1, H, W, C, Fp, wfmt, kh, kw, stride, pad, thr, obits, out=out, engine=engine)
 
 
 def bs_conv_threshold_batch(x: torch.Tensor, afmt: int, B: int, H: int, W: int, C: int, Fp: torch.Tensor, wfmt: int,
                             kh: int, kw: int, stride: int, pad: int, thr: torch.Tensor, obits: int,
-                            out: torch.Tensor | None = None) -> torch.Tensor:
-    """bs_conv_threshold for B images: x [abits][B*H*W][S_C] -> [obits][B*OH*OW][S_F]."""
+                            out: torch.Tensor | None = None, engine: int = BS_ENGINE_AUTO) -> torch.Tensor:
+    """bs_conv_threshold for B images: x [abits][B*H*W][S_C] -> [obits][B*OH*OW][S_F].  engine as in bs_gemm."""
     OH, OW = _conv_geometry(x, B, H, W, C, Fp, kh, kw, stride, pad)
     abits = x.shape[0]
     wbits, F, _ = Fp.shape
@@ -336,8 +338,9 @@ def bs_conv_threshold_batch(x: torch.Tensor, afmt: int, B: int, H: int, W: int, 
     if out is None:
         out = _planes(obits, B * OH * OW, F, x.device)
     _want_planes(out, "out", F, bits=obits, rows=B * OH * OW)
-    st = load_library().bs_conv_threshold_batch(_dev(x, "x"), abits, afmt, B, H, W, C, _dev(Fp, "Fp"), wbits, wfmt, F,
-                                                kh, kw, stride, pad, _dev(thr, "thr"), obits, _dev(out, "out"), _stream())
+    st = load_library().bs_conv_threshold_batch_on(int(engine), _dev(x, "x"), abits, afmt, B, H, W, C, _dev(Fp, "Fp"), wbits,
+                                                   wfmt, F, kh, kw, stride, pad, _dev(thr, "thr"), obits, _dev(out, "out"),
+                                                   _stream())
     _check(st, "bs_conv_threshold_batch")
     return out
 

@@ -143,11 +143,14 @@ extern "C" bs_status bs_gemm_threshold(const uint64_t *Wp, int wbits, bs_format 
     return gemm_common(BS_ENGINE_AUTO, Wp, wbits, wfmt, Ap, abits, afmt, M, N, K, nullptr, 0, thr, obits, Yp, true, stream);
 }
 
-extern "C" bs_status bs_conv_threshold_batch(const uint64_t *in, int abits, bs_format afmt, int B, int H, int W, int C,
-                                             const uint64_t *Fp, int wbits, bs_format wfmt, int F, int kh, int kw,
-                                             int stride, int pad, const int32_t *thr, int obits, uint64_t *Yp,
-                                             void *stream)
+extern "C" bs_status bs_conv_threshold_batch_on(bs_engine engine, const uint64_t *in, int abits, bs_format afmt, int B, int H,
+                                                int W, int C, const uint64_t *Fp, int wbits, bs_format wfmt, int F, int kh,
+                                                int kw, int stride, int pad, const int32_t *thr, int obits, uint64_t *Yp,
+                                                void *stream)
 {
+    if (engine != BS_ENGINE_BITSERIAL && engine != BS_ENGINE_DENSE_I8 && engine != BS_ENGINE_DENSE_FP4 &&
+        engine != BS_ENGINE_AUTO)
+        return BS_ERR_INVALID_ARG;
     if (!in || !Fp || !thr || !Yp || B <= 0 || H <= 0 || W <= 0 || C <= 0 || F <= 0 || kh <= 0 || kw <= 0 ||
         stride <= 0 || pad < 0 || obits < 1)
         return BS_ERR_INVALID_ARG;
@@ -182,8 +185,31 @@ extern "C" bs_status bs_conv_threshold_batch(const uint64_t *in, int abits, bs_f
     g.cH = H; g.cW = W; g.cCd = (C + 31) / 32; g.cPix = (int)pix; g.cKW = kw;
     g.cStride = stride; g.cPad = pad; g.cOW = OW; g.cOHW = OH * OW; g.cB = B; g.cKused = (int)(Kl / 32);
     g.cVec = (g.cCd % 4 == 0 && g.cPix % 4 == 0) ? 1 : 0;
+    // Engine (Sec. 4.2): the layer is the product F x Kl x N; the matrix-core kernel gathers the lowered columns itself.
+    if (engine != BS_ENGINE_BITSERIAL) {
+        const bs_engine e = engine == BS_ENGINE_AUTO ? bs_choose_engine(wbits, wfmt, abits, afmt, F, N, Kl) : engine;
+        if (e != BS_ENGINE_BITSERIAL) {
+            PlanesGemm q{};
+            q.W = g.W; q.A = g.A; q.wbits = wbits; q.abits = abits; q.wfmt = wfmt; q.afmt = afmt;
+            q.M = g.M; q.N = g.N; q.K = Kl; q.Kd = g.Kd;
+            q.thr = thr; q.obits = obits; q.Y = g.Y; q.Yd = g.Yd;
+            q.conv = 1;
+            q.cH = H; q.cW = W; q.cCd = g.cCd; q.cPix = g.cPix; q.cKW = kw; q.cStride = stride; q.cPad = pad;
+            q.cOW = OW; q.cOHW = OH * OW; q.cB = B; q.cKused = g.cKused;
+            return launch_planes_mfma(q, e == BS_ENGINE_DENSE_FP4, true, static_cast<hipStream_t>(stream));
+        }
+    }
     const bool corr = (wfmt == BS_BIPOLAR);
     return dispatch_wb(g, wbits, abits, true, corr, true, false, static_cast<hipStream_t>(stream));
+}
+
+extern "C" bs_status bs_conv_threshold_batch(const uint64_t *in, int abits, bs_format afmt, int B, int H, int W, int C,
+                                             const uint64_t *Fp, int wbits, bs_format wfmt, int F, int kh, int kw,
+                                             int stride, int pad, const int32_t *thr, int obits, uint64_t *Yp,
+                                             void *stream)
+{
+    return bs_conv_threshold_batch_on(BS_ENGINE_AUTO, in, abits, afmt, B, H, W, C, Fp, wbits, wfmt, F, kh, kw, stride, pad, thr,
+                                      obits, Yp, stream);
 }
 
 extern "C" bs_status bs_conv_threshold(const uint64_t *in, int abits, bs_format afmt, int H, int W, int C,

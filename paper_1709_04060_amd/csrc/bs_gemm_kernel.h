@@ -139,6 +139,10 @@ struct PlanesGemm {
     int obits;
     uint32_t *Y;
     int Yd;
+    // implicit lowering (conv != 0): A points at packed HWC image planes [abits][B][H][W][cPix dwords] and column n of
+    // the lowered matrix (Sec. 3.2) is gathered from them; fields as in GemmParams
+    int conv;
+    int cH, cW, cCd, cPix, cKW, cStride, cPad, cOW, cOHW, cB, cKused;
 };
 bool planes_mfma_supported(int wbits, bs_format wfmt, int abits, bs_format afmt, int64_t K, bool fp4);
 bs_status launch_planes_mfma(const PlanesGemm &q, bool fp4, bool fuse, hipStream_t st);

@@ -62,6 +62,8 @@ struct PlanesParams {
     // C = mul * P + row_coef * rowsum(U_w)[m] + row_const + col_coef * rowsum(U_a)[n],  P = acc * acc_scale = U_w . U_a
     int mul, row_coef, row_const, col_coef;
     float acc_scale;
+    // implicit lowering (CONV kernels): Ap points at packed HWC image planes; see PlanesGemm
+    int cH, cW, cCd, cPix, cKW, cStride, cPad, cOW, cOHW, cB, cKused;
 };
 
 // (a & m) | (b & ~m): one v_bfi_b32
@@ -115,7 +117,10 @@ struct PlanesResult {
 
 // FP4: operand kind.  WTM x WTN MFMA tiles of 32 x 32 per wavefront, WGM x WGN wavefronts; the workgroup has as many
 // threads as the stacked tile has rows (one row per thread).
-template <bool FP4, int WTM, int WTN, int WGM, int WGN, bool FUSE>
+// CONV: the activation operand is not a packed matrix but packed HWC image planes; the rows of the A part of the tile
+// (columns of the lowered matrix of Sec. 3.2) are gathered from the image, zero words for taps outside of it, so
+// the lowered matrix never exists in memory.
+template <bool FP4, int WTM, int WTN, int WGM, int WGN, bool FUSE, bool CONV = false>
 __global__ void __launch_bounds__(64 * WGM * WGN)
 planes_mfma_kernel(const PlanesParams p)
 {
@@ -128,6 +133,8 @@ planes_mfma_kernel(const PlanesParams p)
     constexpr int TILE = NT * DK;                // bytes per stage buffer
     __shared__ __attribute__((aligned(16))) unsigned char lds[4 * TILE];  // two stages being multiplied, two being written
     __shared__ int terms[NT];                    // per-row terms of the result: W rows, then A rows (columns of C)
+    // lowered dword -> (kernel row << 24 | kernel column << 16 | channel word), -1 past the data
+    __shared__ __attribute__((aligned(16))) int lut[CONV ? kConvMaxLut + 8 : 4];
 
     bs::prefetch_kernel_arguments<(int)sizeof(PlanesParams)>();
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -142,14 +149,34 @@ planes_mfma_kernel(const PlanesParams p)
     const int rows = isW ? p.d.M : p.d.N;
     int row = isW ? m0 + tid : n0 + (tid - BM);
     if (row >= rows) row = rows - 1;             // clamped: its products land in outputs that are never stored
-    const uint32_t *base = (isW ? p.Wp : p.Ap) + (size_t)row * p.Kd;
+    // CONV, A rows: the row is output pixel (b, oh, ow); pix_h, pix_w = top-left input pixel of its window
+    int pix_h = 0, pix_w = 0;
+    size_t row_off = (size_t)row * p.Kd;         // dwords from the start of a plane to this row's words
+    size_t plane_stride = (size_t)rows * p.Kd;
+    if constexpr (CONV) {
+        if (!isW) {
+            const int b = row / p.cOHW, opix = row - b * p.cOHW;
+            const int oh = opix / p.cOW, ow = opix - oh * p.cOW;
+            pix_h = oh * p.cStride - p.cPad;
+            pix_w = ow * p.cStride - p.cPad;
+            row_off = (size_t)b * p.cH * p.cW * p.cPix;            // image b inside a plane
+            plane_stride = (size_t)p.cB * p.cH * p.cW * p.cPix;
+        }
+        for (int q = tid; q < p.Kd + 4; q += NT) {
+            const int tap = q / p.cCd, cdw = q - tap * p.cCd;
+            const int fr = tap / p.cKW, fs = tap - fr * p.cKW;
+            lut[q] = q < p.cKused ? ((fr << 24) | (fs << 16) | cdw) : -1;
+        }
+        __syncthreads();
+    }
+    const uint32_t *base = (isW ? p.Wp : p.Ap) + row_off;
     const uint32_t *pl_ptr[NB];
     uint32_t plain[NB], flipped[NB];             // all ones where the slot holds a plane as it is / the inverted top plane
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
         const int pl = q - cd.shift;             // plane of this slot
         const bool has = pl >= 0 && pl < cd.bits;
-        pl_ptr[q] = base + (size_t)(has ? pl : 0) * rows * p.Kd;  // an empty slot reads plane 0 and is masked off
+        pl_ptr[q] = base + (size_t)(has ? pl : 0) * plane_stride;  // an empty slot reads plane 0 and is masked off
         plain[q] = (has && q != cd.top) ? 0xFFFFFFFFu : 0u;
         flipped[q] = (has && q == cd.top) ? 0xFFFFFFFFu : 0u;
         // plain data from here on: x = (r & plain) | (~r & flipped) is one three-input bit operation per word; knowing how
@@ -166,16 +193,48 @@ planes_mfma_kernel(const PlanesParams p)
     // stages (int8 kind), two where they hold one (fp4 kind).  Every lane of a request reads another row, i.e. another
     // cache line, and those line look-ups are what bounds the loader: the fewer requests the better.
     uint32_t R[NB][PW];
+    // four lowered dwords starting at dword q0 (a multiple of 4) of this row's column, gathered from image plane `img`
+    auto gather4 = [&](const uint32_t *img, int q0) -> uint4 {
+        const int4 l4 = *reinterpret_cast<const int4 *>(&lut[q0]);
+        const int l[4] = {l4.x, l4.y, l4.z, l4.w};
+        if ((p.cCd & 3) == 0 && (p.cPix & 3) == 0) {
+            // the four dwords lie inside one tap of one pixel: one test, one 16-byte load
+            const int ih = pix_h + (l[0] >> 24), iw = pix_w + ((l[0] >> 16) & 0xFF);
+            if (l[0] >= 0 && ih >= 0 && ih < p.cH && iw >= 0 && iw < p.cW)
+                return *reinterpret_cast<const uint4 *>(img + (size_t)(ih * p.cW + iw) * p.cPix + (l[0] & 0xFFFF));
+            return make_uint4(0, 0, 0, 0);
+        }
+        uint32_t e[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            e[t] = 0;
+            const int ih = pix_h + (l[t] >> 24), iw = pix_w + ((l[t] >> 16) & 0xFF);
+            if (l[t] >= 0 && ih >= 0 && ih < p.cH && iw >= 0 && iw < p.cW) e[t] = img[(size_t)(ih * p.cW + iw) * p.cPix + (l[t] & 0xFFFF)];
+        }
+        return make_uint4(e[0], e[1], e[2], e[3]);
+    };
     auto fetch = [&](int period) {
         const int s = period < p.nper ? period : p.nper - 1;  // past the depth: any valid address; the words are zeroed on use
+        // the second stage of the last period may not exist (the row ends with the first): stay inside the row
+        const int o2 = s * PW + 4 < p.Kd ? s * PW + 4 : p.Kd - 4;
+        if (CONV && !isW) {                      // uniform for the wavefront
+#pragma unroll
+            for (int q = 0; q < NB; ++q) {
+                const uint4 v = gather4(pl_ptr[q], s * PW);
+                R[q][0] = v.x; R[q][1] = v.y; R[q][2] = v.z; R[q][3] = v.w;
+                if constexpr (PW == 8) {
+                    const uint4 u = gather4(pl_ptr[q], o2);
+                    R[q][4] = u.x; R[q][5] = u.y; R[q][6] = u.z; R[q][7] = u.w;
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int q = 0; q < NB; ++q) {
             const uint4 v = *reinterpret_cast<const uint4 *>(pl_ptr[q] + s * PW);
             R[q][0] = v.x; R[q][1] = v.y; R[q][2] = v.z; R[q][3] = v.w;
             if constexpr (PW == 8) {
-                // the second stage of the last period may not exist (the row ends with the first): stay inside the row
-                const int o = s * PW + 4 < p.Kd ? s * PW + 4 : p.Kd - 4;
-                const uint4 u = *reinterpret_cast<const uint4 *>(pl_ptr[q] + o);
+                const uint4 u = *reinterpret_cast<const uint4 *>(pl_ptr[q] + o2);
                 R[q][4] = u.x; R[q][5] = u.y; R[q][6] = u.z; R[q][7] = u.w;
             }
         }
@@ -335,26 +394,29 @@ OperandCoding coding_of(int bits, bs_format fmt, bool fp4)
 }
 
 template <bool FP4, int WTM, int WTN, int WGM, int WGN>
-bs_status launch_tile(PlanesParams &p, bool fuse, hipStream_t st)
+bs_status launch_tile(PlanesParams &p, bool fuse, bool conv, hipStream_t st)
 {
     constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN, NT = 64 * WGM * WGN;
     p.d.gx = (p.d.N + BN - 1) / BN;
     p.d.gy = (p.d.M + BM - 1) / BM;
     const long long blocks = (long long)p.d.gx * p.d.gy;
     if (blocks >= (1LL << 31)) return BS_ERR_UNSUPPORTED;
-    if (fuse) planes_mfma_kernel<FP4, WTM, WTN, WGM, WGN, true><<<dim3((unsigned)blocks), NT, 0, st>>>(p);
+    if (conv) {  // implicit lowering exists with the thresholding epilogue only
+        if (!fuse) return BS_ERR_UNSUPPORTED;
+        planes_mfma_kernel<FP4, WTM, WTN, WGM, WGN, true, true><<<dim3((unsigned)blocks), NT, 0, st>>>(p);
+    } else if (fuse) planes_mfma_kernel<FP4, WTM, WTN, WGM, WGN, true><<<dim3((unsigned)blocks), NT, 0, st>>>(p);
     else planes_mfma_kernel<FP4, WTM, WTN, WGM, WGN, false><<<dim3((unsigned)blocks), NT, 0, st>>>(p);
     return bs::after_launch();
 }
 
 template <bool FP4>
-bs_status launch_kind(PlanesParams &p, bool fuse, hipStream_t st)
+bs_status launch_kind(PlanesParams &p, bool fuse, bool conv, hipStream_t st)
 {
     // 256 x 256 tiles on eight wavefronts (one per compute unit) or 128 x 128 on four (two per compute unit).  A
     // 128 x 128 tile expands half the rows of a 256 x 256 one for a quarter of its products: the small tile is taken
     // when it needs fewer rounds over the chip (bs_planes_tile, which the engine choice's time model shares).
-    if (bs_planes_tile(p.d.M, p.d.N, nullptr, nullptr) == 256) return launch_tile<FP4, 4, 2, 2, 4>(p, fuse, st);
-    return launch_tile<FP4, 2, 2, 2, 2>(p, fuse, st);
+    if (bs_planes_tile(p.d.M, p.d.N, nullptr, nullptr) == 256) return launch_tile<FP4, 4, 2, 2, 4>(p, fuse, conv, st);
+    return launch_tile<FP4, 2, 2, 2, 2>(p, fuse, conv, st);
 }
 
 }  // namespace
@@ -392,7 +454,12 @@ bs_status launch_planes_mfma(const PlanesGemm &q, bool fp4, bool fuse, hipStream
     const int per_stage = fp4 ? 128 : 64;
     p.nst = (int)((q.K + per_stage - 1) / per_stage);
     p.nper = (p.nst + 1) / 2;
-    return fp4 ? launch_kind<true>(p, fuse, st) : launch_kind<false>(p, fuse, st);
+    if (q.conv) {
+        if (2 * (int64_t)q.Kd > 2 * kConvMaxLut) return BS_ERR_UNSUPPORTED;
+        p.cH = q.cH; p.cW = q.cW; p.cCd = q.cCd; p.cPix = q.cPix; p.cKW = q.cKW; p.cStride = q.cStride; p.cPad = q.cPad;
+        p.cOW = q.cOW; p.cOHW = q.cOHW; p.cB = q.cB; p.cKused = q.cKused;
+    }
+    return fp4 ? launch_kind<true>(p, fuse, q.conv != 0, st) : launch_kind<false>(p, fuse, q.conv != 0, st);
 }
 
 }  // namespace bs

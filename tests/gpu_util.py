@@ -87,6 +87,24 @@ def gemm_threshold_all_engines(Wp, wfmt, Ap, afmt, K, thr, obits, what="gemm_thr
     return first
 
 
+def conv_threshold_all_engines(xp, afmt, B, H, W, C, Fp, wfmt, k, stride, pad, thr, obits, what="conv_threshold"):
+    """bs_conv_threshold_batch on every engine that takes the layer (as a product F x Kl x B OH OW), into guarded
+    buffers prefilled with ones; returns the packed planes (numpy uint64) after checking that all engines agree."""
+    first = None
+    F = Fp.shape[1]
+    OH, OW = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    for eng in engines_for(Fp.shape[0], wfmt, xp.shape[0], afmt, bs.bs_lowered_depth(C, k, k)):
+        out = guarded_full((obits, B * OH * OW, bs.bs_words_per_row(F)), -1, torch.int64)
+        bs.bs_conv_threshold_batch(xp, afmt, B, H, W, C, Fp, wfmt, k, k, stride, pad, thr, obits, out=out, engine=eng)
+        got = planes_to_numpy(out)
+        check_guards()
+        if first is None:
+            first = got
+        else:
+            assert_equal(got, first, "%s: engine %s against engine auto" % (what, ENGINE_NAMES[eng]))
+    return first
+
+
 # ------------------------------------------------------------------ guard bands
 # Every output buffer of a test sits inside a larger allocation with sentinel words before and behind it; a
 # kernel that writes outside its output (a tile that ignores a ragged edge, a padding loop that runs too far)

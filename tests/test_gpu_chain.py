@@ -7,7 +7,7 @@ import torch
 import oracle
 import paper_1709_04060_amd as bs
 from paper_1709_04060_amd import workloads
-from gpu_util import FMT, assert_equal, dev, draw, planes_to_dev, planes_to_numpy, guarded_full
+from gpu_util import FMT, assert_equal, conv_threshold_all_engines, dev, draw, planes_to_dev, planes_to_numpy, guarded_full
 
 pytestmark = pytest.mark.gpu
 U, TC, BP = oracle.UNSIGNED, oracle.TWOS_COMPLEMENT, oracle.BIPOLAR
@@ -41,9 +41,8 @@ def test_conv_threshold(H, W, C, F, k, s, p, w, wf, a, af, obits):
     Cp = 32 * ((C + 31) // 32)
     xp = bs.bs_pack_planes(dev(x.reshape(H * W, C)), a, FMT[af])
     Fp = bs.bs_pack_planes(dev(pad_last(filt, Cp).reshape(F, -1)), w, FMT[wf])
-    out = guarded_full((obits, want.shape[1], bs.bs_words_per_row(F)), -1, torch.int64)
-    bs.bs_conv_threshold(xp, FMT[af], H, W, C, Fp, FMT[wf], k, k, s, p, dev(thr), obits, out=out)
-    assert_equal(planes_to_numpy(out), want, "conv_threshold")
+    got = conv_threshold_all_engines(xp, FMT[af], 1, H, W, C, Fp, FMT[wf], k, s, p, dev(thr), obits)
+    assert_equal(got, want, "conv_threshold")
     # and the two-call route gives the same planes
     low = bs.bs_im2col_interleaved(xp, H, W, C, k, k, s, p)
     two = bs.bs_gemm_threshold(Fp, FMT[wf], low, FMT[af], bs.bs_lowered_depth(C, k, k), dev(thr), obits)
@@ -60,8 +59,8 @@ def test_conv_threshold_large_grid():
     want, _ = conv_reference(x, filt, thr, 1, 1, 2)
     xp = bs.bs_pack_planes(dev(x.reshape(H * W, C)), 2, bs.BS_UNSIGNED)
     Fp = bs.bs_pack_planes(dev(filt.reshape(F, -1)), 1, bs.BS_BIPOLAR)
-    out = bs.bs_conv_threshold(xp, bs.BS_UNSIGNED, H, W, C, Fp, bs.BS_BIPOLAR, k, k, 1, 1, dev(thr), 2)
-    assert_equal(planes_to_numpy(out), want, "conv_threshold, 64x64 tiles")
+    got = conv_threshold_all_engines(xp, bs.BS_UNSIGNED, 1, H, W, C, Fp, bs.BS_BIPOLAR, k, 1, 1, dev(thr), 2)
+    assert_equal(got, want, "conv_threshold, 64x64 tiles")
 
 
 @pytest.mark.parametrize("H,W,C,k,s", [(27, 27, 256, 3, 2), (13, 13, 256, 3, 2), (8, 9, 40, 2, 2), (6, 6, 3, 3, 1), (5, 5, 130, 5, 1)])
@@ -128,9 +127,8 @@ def test_conv_and_pool_on_a_batch(B, H, W, C, F, k, s, p, w, wf, a, af, obits):
     Cp = 32 * ((C + 31) // 32)
     xp = bs.bs_pack_planes(dev(x.reshape(B * H * W, C)), a, FMT[af])
     Fp = bs.bs_pack_planes(dev(pad_last(filt, Cp).reshape(F, -1)), w, FMT[wf])
-    out = guarded_full((obits, B * OH * OW, bs.bs_words_per_row(F)), -1, torch.int64)
-    bs.bs_conv_threshold_batch(xp, FMT[af], B, H, W, C, Fp, FMT[wf], k, k, s, p, dev(thr), obits, out=out)
-    assert_equal(planes_to_numpy(out), want, "conv_threshold_batch")
+    got = conv_threshold_all_engines(xp, FMT[af], B, H, W, C, Fp, FMT[wf], k, s, p, dev(thr), obits)
+    assert_equal(got, want, "conv_threshold_batch")
     # the two-call route on the batch: lowered columns of all images side by side, then the plain GEMM
     low = bs.bs_im2col_interleaved_batch(xp, B, H, W, C, k, k, s, p)
     two = bs.bs_gemm_threshold(Fp, FMT[wf], low, FMT[af], bs.bs_lowered_depth(C, k, k), dev(thr), obits)
@@ -156,5 +154,5 @@ def test_conv_and_pool_on_a_batch(B, H, W, C, F, k, s, p, w, wf, a, af, obits):
     if min(OH, OW) >= 2:
         Y = [oracle.threshold(c.reshape(OH * OW, F).T.copy(), thr).T.reshape(OH, OW, F) for c in convs]
         wantp = np.concatenate([oracle.pack(oracle.maxpool(y, 2, 2).reshape(-1, F), obits, U) for y in Y], axis=1)
-        pooled = bs.bs_maxpool_packed_batch(out, B, OH, OW, F, 2, 2)
+        pooled = bs.bs_maxpool_packed_batch(two, B, OH, OW, F, 2, 2)
         assert_equal(planes_to_numpy(pooled), wantp, "maxpool_packed_batch")

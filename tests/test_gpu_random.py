@@ -7,7 +7,7 @@ import torch
 
 import oracle
 import paper_1709_04060_amd as bs
-from gpu_util import FMT, assert_equal, dev, draw, gemm_all_engines, gemm_threshold_all_engines, guarded_full, planes_to_numpy
+from gpu_util import FMT, assert_equal, conv_threshold_all_engines, dev, draw, gemm_all_engines, gemm_threshold_all_engines, guarded_full, planes_to_numpy
 
 pytestmark = pytest.mark.gpu
 U, TC, BP = oracle.UNSIGNED, oracle.TWOS_COMPLEMENT, oracle.BIPOLAR
@@ -103,9 +103,8 @@ def test_random_convolution_and_pooling(seed):
         fpad[..., C:] = -1                          # any value does: the activation pad bits are zero
     xp = bs.bs_pack_planes(dev(x.reshape(H * W, C)), a, FMT[af])
     Fp = bs.bs_pack_planes(dev(fpad.reshape(F, -1)), w, FMT[wf])
-    out = guarded_full((obits, OH * OW, bs.bs_words_per_row(F)), -1, torch.int64)
-    bs.bs_conv_threshold(xp, FMT[af], H, W, C, Fp, FMT[wf], k, k, s, p, dev(thr), obits, out=out)
-    assert_equal(planes_to_numpy(out), want, "bs_conv_threshold " + what)
+    got = conv_threshold_all_engines(xp, FMT[af], 1, H, W, C, Fp, FMT[wf], k, s, p, dev(thr), obits)
+    assert_equal(got, want, "bs_conv_threshold " + what)
     low = bs.bs_im2col_interleaved(xp, H, W, C, k, k, s, p)
     two = bs.bs_gemm_threshold(Fp, FMT[wf], low, FMT[af], bs.bs_lowered_depth(C, k, k), dev(thr), obits)
     assert_equal(planes_to_numpy(two), want, "bs_im2col_interleaved + bs_gemm_threshold " + what)
@@ -113,7 +112,7 @@ def test_random_convolution_and_pooling(seed):
     if pk <= min(OH, OW):
         ps = int(rng.integers(1, 3))
         Y = oracle.threshold(Cmat, thr).T.reshape(OH, OW, F)
-        pooled = bs.bs_maxpool_packed(out, OH, OW, F, pk, ps)
+        pooled = bs.bs_maxpool_packed(two, OH, OW, F, pk, ps)
         assert_equal(planes_to_numpy(pooled), oracle.pack(oracle.maxpool(Y, pk, ps).reshape(-1, F), obits, U), "bs_maxpool_packed " + what)
 
 
