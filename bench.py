@@ -535,20 +535,23 @@ def extras(bs, workloads, dev, timed):
         "us_per_layer_alone": per_layer,
         "context": "the same layers (lowering + GEMM rows of Table 2, bsgemm-intl column) sum to 55.1 ms on the "
                    "paper's Cortex-A57 core; synthetic weights here"}
-    # the same chain on a batch of images (columns = batch x pixels): throughput instead of latency
-    for Bn in (16, 64):
+    # the same chain on a batch of images (columns = batch x pixels): throughput instead of latency.  Once with the
+    # AND-popcount engine named for every layer, once as the library chooses per layer (Sec. 4.2: "choosing the execution
+    # method for each layer"); lowering happens inside the kernels on either engine.
+    names = {bs.BS_ENGINE_BITSERIAL: "bitserial", bs.BS_ENGINE_DENSE_I8: "dense_int8", bs.BS_ENGINE_DENSE_FP4: "dense_fp4"}
+    for Bn in (16, 64, 256):
         xb = torch.randint(0, 4, (Bn * H0 * W0, C0), dtype=torch.int8, device="cuda")
         xbp = bs.bs_pack_planes(xb, 2, U)
         bufs = {}
 
-        def frame_batch():
+        def frame_batch(engine):
             cur = xbp
             for L, Wp, th in prepared:
                 key = (L["name"], Bn)
                 if L["kind"] == "conv":
                     H, W, C, F, k, s, p = L["geom"]
                     OHW = ((H + 2 * p - k) // s + 1) ** 2
-                    cur = bs.bs_conv_threshold_batch(cur, U, Bn, H, W, C, Wp, BP, k, k, s, p, th, 2, out=bufs.setdefault(
+                    cur = bs.bs_conv_threshold_batch(cur, U, Bn, H, W, C, Wp, BP, k, k, s, p, th, 2, engine=engine, out=bufs.setdefault(
                         key, torch.empty((2, Bn * OHW, bs.bs_words_per_row(F)), dtype=torch.int64, device="cuda")))
                 elif L["kind"] == "pool":
                     H, W, C, k, s = L["geom"]
@@ -557,67 +560,25 @@ def extras(bs, workloads, dev, timed):
                         key, torch.empty((2, Bn * OHW, bs.bs_words_per_row(C)), dtype=torch.int64, device="cuda")))
                 else:
                     M, K = L["geom"]
-                    cur = bs.bs_gemm_threshold(Wp, BP, cur.reshape(2, Bn, -1), U, K, th, 2, out=bufs.setdefault(
+                    cur = bs.bs_gemm_threshold(Wp, BP, cur.reshape(2, Bn, -1), U, K, th, 2, engine=engine, out=bufs.setdefault(
                         key, torch.empty((2, Bn, bs.bs_words_per_row(M)), dtype=torch.int64, device="cuda")))
             return cur
-        msb = timed_graph([frame_batch], 10)
-        out["alexnet_W1A2_layers_conv2_to_fc7_chain_batch_%d" % Bn] = {
-            "us_per_batch": round(msb * 1e3, 2), "frames_per_s": round(Bn * 1e3 / msb, 1)}
-        # the paper's per-layer choice of the execution method (Sec. 4.2), made by bs_choose_engine: layers it
-        # gives to the fp4 matrix-core engine run as lowering -> planes to E2M1 codes -> dense GEMM + thresholds
-        picks, wd = {}, {}
+        want = frame_batch(BSER).clone()
+        same = bool((frame_batch(bs.BS_ENGINE_AUTO) == want).all())
+        msb = timed_graph([lambda: frame_batch(BSER)], 10)
+        msc = timed_graph([lambda: frame_batch(bs.BS_ENGINE_AUTO)], 10)
+        picks = {}
         for L, Wp, th in prepared:
-            if L["kind"] == "pool":
-                continue
             if L["kind"] == "conv":
                 H, W, C, F, k, s, p = L["geom"]
-                Mx, Nx, Kx = F, Bn * ((H + 2 * p - k) // s + 1) ** 2, bs.bs_lowered_depth(C, k, k)
-            else:
-                (Mx, Kx), Nx = L["geom"], Bn
-            picks[L["name"]] = bs.bs_choose_engine(1, BP, 2, U, Mx, Nx, Kx)
-            if picks[L["name"]] == bs.BS_ENGINE_DENSE_FP4:
-                wd[L["name"]] = bs.bs_unpack_planes_fp4(Wp, BP, Kx)
-        if any(v == bs.BS_ENGINE_DENSE_FP4 for v in picks.values()):
-            def frame_choice():
-                cur = xbp
-                for L, Wp, th in prepared:
-                    key = (L["name"], Bn)
-                    if L["kind"] == "pool":
-                        H, W, C, k, s = L["geom"]
-                        cur = bs.bs_maxpool_packed_batch(cur, Bn, H, W, C, k, s, out=bufs[key])
-                    elif picks[L["name"]] != bs.BS_ENGINE_DENSE_FP4:
-                        if L["kind"] == "conv":
-                            H, W, C, F, k, s, p = L["geom"]
-                            cur = bs.bs_conv_threshold_batch(cur, U, Bn, H, W, C, Wp, BP, k, k, s, p, th, 2, out=bufs[key])
-                        else:
-                            cur = bs.bs_gemm_threshold(Wp, BP, cur.reshape(2, Bn, -1), U, L["geom"][1], th, 2, out=bufs[key])
-                    else:
-                        if L["kind"] == "conv":
-                            # unpack first, lower second: the small feature map becomes E2M1 codes (16 bytes per 32
-                            # channels), and that map is lowered like a one-plane map of 4 C bit-channels, so the
-                            # large lowered matrix is written once, already as codes (channels are multiples of 32)
-                            H, W, C, F, k, s, p = L["geom"]
-                            Kx = bs.bs_lowered_depth(C, k, k)
-                            OHW = ((H + 2 * p - k) // s + 1) ** 2
-                            cmap = bs.bs_unpack_planes_fp4(cur, U, C, out=bufs.setdefault(
-                                key + ("map",), torch.empty((Bn * H * W, C // 2), dtype=torch.uint8, device="cuda")))
-                            codes = bs.bs_im2col_interleaved_batch(
-                                cmap.view(torch.int64).reshape(1, Bn * H * W, -1), Bn, H, W, 4 * C, k, k, s, p, out=bufs.setdefault(
-                                    key + ("fp4",), torch.empty((1, Bn * OHW, bs.bs_words_per_row(4 * Kx)), dtype=torch.int64, device="cuda"))
-                            ).view(torch.uint8).reshape(Bn * OHW, -1)
-                        else:
-                            Kx, cols = L["geom"][1], cur.reshape(2, Bn, -1)
-                            codes = bs.bs_unpack_planes_fp4(cols, U, Kx, out=bufs.setdefault(
-                                key + ("fp4",), torch.empty((Bn, 16 * ((Kx + 31) // 32)), dtype=torch.uint8, device="cuda")))
-                        cur = bs.bs_gemm_fp4_threshold(wd[L["name"]], codes, Kx, th, 2, out=bufs[key])
-                return cur
-            want = frame_batch().clone()
-            same = bool((frame_choice() == want).all())
-            msc = timed_graph([frame_choice], 10)
-            names = {bs.BS_ENGINE_BITSERIAL: "bitserial", bs.BS_ENGINE_DENSE_I8: "dense_int8", bs.BS_ENGINE_DENSE_FP4: "dense_fp4"}
-            out["alexnet_W1A2_layers_conv2_to_fc7_chain_batch_%d" % Bn]["with_engine_choice"] = {
-                "us_per_batch": round(msc * 1e3, 2), "frames_per_s": round(Bn * 1e3 / msc, 1),
-                "engine": {k: names[v] for k, v in picks.items()}, "same_output_as_bitserial_chain": same}
+                picks[L["name"]] = names[bs.bs_choose_engine(1, BP, 2, U, F, Bn * ((H + 2 * p - k) // s + 1) ** 2, bs.bs_lowered_depth(C, k, k))]
+            elif L["kind"] == "fc":
+                picks[L["name"]] = names[bs.bs_choose_engine(1, BP, 2, U, L["geom"][0], Bn, L["geom"][1])]
+        out["alexnet_W1A2_layers_conv2_to_fc7_chain_batch_%d" % Bn] = {
+            "bitserial_engine": {"us_per_batch": round(msb * 1e3, 2), "frames_per_s": round(Bn * 1e3 / msb, 1)},
+            "engine_chosen_per_layer": {"us_per_batch": round(msc * 1e3, 2), "frames_per_s": round(Bn * 1e3 / msc, 1),
+                                        "engine": picks, "same_output_as_bitserial_chain": same}}
+        del xb, xbp, bufs
     # the dense (int8 MFMA) engine on the compute-bound configurations, beside the bit-serial
     # numbers above: same logical product, operands unpacked to int8
     def dense(name, M, N, K, obits):
@@ -661,37 +622,6 @@ def extras(bs, workloads, dev, timed):
                                   "frac": round(tops / 10100.0, 4)}}
     dense_fp4("dense_fp4_engine_4096x4096x4096_int32_out", 4096, 4096, 4096, 0)
     dense_fp4("dense_fp4_engine_8192x8192x8192_fused_2bit_out", 8192, 8192, 8192, 2)
-    # per-layer engine choice (Sec. 4.1.1 / 4.2): the engines timed on the same fused product, the dense ones
-    # including the unpack of their activations, beside what bs_choose_engine picks
-    choice = {}
-    for (w_, a_, M_, N_, K_) in [(1, 2, 256, 729, 2400), (1, 2, 4096, 1024, 4096), (2, 2, 1024, 1024, 4096),
-                                 (4, 4, 8192, 64, 8192), (4, 4, 1024, 256, 1024)]:
-        wf_ = BP if w_ == 1 else TC
-        Wq, Aq = planes(w_, M_, K_), planes(a_, N_, K_)
-        th_ = thr_for(M_, a_)
-        Yq = torch.empty((a_, N_, bs.bs_words_per_row(M_)), dtype=torch.int64, device="cuda")
-        times = {"bitserial": timed_graph([lambda: bs.bs_gemm_threshold(Wq, wf_, Aq, U, K_, th_, a_, out=Yq)], 10)}
-        W8q = bs.bs_unpack_planes(Wq, wf_, K_)
-        A8q = torch.empty((N_, W8q.shape[1]), dtype=torch.int8, device="cuda")
-
-        def int8_route():
-            bs.bs_unpack_planes(Aq, U, K_, out=A8q)
-            bs.bs_gemm_i8_threshold(W8q, A8q, K_, th_, a_, out=Yq)
-        times["dense_int8"] = timed_graph([int8_route], 10)
-        if w_ <= 2 and a_ <= 2:
-            W4q = bs.bs_unpack_planes_fp4(Wq, wf_, K_)
-            A4q = torch.empty((N_, W4q.shape[1]), dtype=torch.uint8, device="cuda")
-
-            def fp4_route():
-                bs.bs_unpack_planes_fp4(Aq, U, K_, out=A4q)
-                bs.bs_gemm_fp4_threshold(W4q, A4q, K_, th_, a_, out=Yq)
-            times["dense_fp4"] = timed_graph([fp4_route], 10)
-        pick = bs.bs_choose_engine(w_, wf_, a_, U, M_, N_, K_)
-        row = {k + "_us": round(v * 1e3, 2) for k, v in times.items()}
-        row["chosen"] = ["bitserial", "dense_int8", "dense_fp4"][pick]
-        row["fastest"] = min(times, key=times.get)
-        choice["W%dA%d_%dx%dx%d" % (w_, a_, M_, K_, N_)] = row
-    out["engine_choice"] = choice
     # stand-alone thresholding of a large int32 result (the unfused route of S5)
     Cbig = torch.randint(-40000, -20000, (8192, 8192), dtype=torch.int32, device="cuda")
     thb = thr_for(8192, 4) - 30000
