@@ -530,9 +530,50 @@ def extras(bs, workloads, dev, timed):
     for L, Wp, th in prepared:
         per_layer[L["name"]] = round(timed_graph([one_layer(L, Wp, th, cur)], 20) * 1e3, 2)
         cur = L["_out"]
+    # the two pooling layers folded into their consumers' operand fetch: conv3 reads pool2's windows, fc6 (a convolution
+    # whose kernel is the whole pooled map) reads pool5's; six launches, same result
+    def frame_folded(alone=None):
+        cur, pool, calls = x0, None, []
+        for L, Wp, th in prepared:
+            if L["kind"] == "pool":
+                pool = L["geom"]
+                continue
+            if L["kind"] == "conv":
+                H, W, C, F, k, s, p = L["geom"]
+                if pool is not None:
+                    f = (lambda cur=cur, pool=pool, Wp=Wp, th=th, L=L, k=k, s=s, p=p:
+                         bs.bs_pool_conv_threshold_batch(cur, 1, pool[0], pool[1], pool[2], pool[3], pool[4], Wp, BP, k, k, s, p, th, 2, out=L["_out"]))
+                else:
+                    f = (lambda cur=cur, Wp=Wp, th=th, L=L, H=H, W=W, C=C, k=k, s=s, p=p:
+                         bs.bs_conv_threshold(cur, U, H, W, C, Wp, BP, k, k, s, p, th, 2, out=L["_out"]))
+            else:
+                M, K = L["geom"]
+                if pool is not None:
+                    PH = (pool[0] - pool[3]) // pool[4] + 1
+                    f = (lambda cur=cur, pool=pool, Wp=Wp, th=th, L=L, PH=PH:
+                         bs.bs_pool_conv_threshold_batch(cur, 1, pool[0], pool[1], pool[2], pool[3], pool[4], Wp, BP, PH, PH, 1, 0, th, 2, out=L["_out"]))
+                else:
+                    f = (lambda cur=cur, Wp=Wp, th=th, L=L, K=K:
+                         bs.bs_gemm_threshold(Wp, BP, cur.reshape(2, 1, -1), U, K, th, 2, out=L["_out"]))
+            calls.append((L["name"] + ("_reading_pooled_input" if pool is not None else ""), f))
+            cur, pool = L["_out"], None
+        return calls
+    want_last = frame().clone()
+    folded = frame_folded()
+    def run_folded():
+        for _, f in folded:
+            f()
+    run_folded()
+    torch.cuda.synchronize()
+    folded_same = bool(torch.equal(prepared[-1][0]["_out"], want_last))
+    ms_folded = timed_graph([run_folded], 20)
+    per_layer_folded = {name: round(timed_graph([f], 20) * 1e3, 2) for name, f in folded if name.endswith("pooled_input")}
     out["alexnet_W1A2_layers_conv2_to_fc7_chain"] = {
         "us_per_frame": round(ms * 1e3, 2), "frames_per_s": round(1e3 / ms, 1), "kernels_per_frame": len(prepared),
         "us_per_layer_alone": per_layer,
+        "pooling_folded_into_consumers": {"us_per_frame": round(ms_folded * 1e3, 2), "frames_per_s": round(1e3 / ms_folded, 1),
+                                          "kernels_per_frame": len(folded), "same_output": folded_same,
+                                          "us_per_fused_layer_alone": per_layer_folded},
         "context": "the same layers (lowering + GEMM rows of Table 2, bsgemm-intl column) sum to 55.1 ms on the "
                    "paper's Cortex-A57 core; synthetic weights here"}
     # the same chain on a batch of images (columns = batch x pixels): throughput instead of latency.  Once with the

@@ -235,6 +235,28 @@ bs_status bs_maxpool_packed_batch(const uint64_t *in, int bits, int B, int H, in
                                   uint64_t *out, void *stream);
 
 /*
+ * bs_conv_threshold_batch reading its input through a max pooling: the layer sequence pooling -> convolution ->
+ * thresholds (AlexNet's pool2 -> conv3 and pool5 -> fc6; Sec. 4.2 runs pooling as a separate layer) in one call.  The
+ * pooled map is never written: the kernel that gathers a lowered column (Sec. 3.2) forms every 32-channel word of it as
+ * the bit-sliced maximum over its pool_k x pool_k window of the map in memory.  The result equals
+ * bs_maxpool_packed_batch followed by bs_conv_threshold_batch bit for bit.
+ *   in   device uint64_t [abits][B][H][W][bs_words_per_row(C)], unsigned codes (H x W: the unpooled map)
+ *   pool_k, pool_stride  window (1..3) and stride of the pooling; the convolution sees a map of
+ *        PH x PW, PH = (H - pool_k) / pool_stride + 1
+ *   everything else as bs_conv_threshold_batch with H, W replaced by PH, PW.
+ * A kernel that covers the whole pooled map (kh = PH, kw = PW, pad = 0) is a fully connected layer on the flattened
+ * pooled map; with at most 4 images it runs on the few-column kernel, which streams the weights once.  All other cases
+ * run on the bit-serial kernel with narrow tiles, meant for the small batches where a launch saved matters; for
+ * large batches pooling and convolution as two calls are faster (the convolution then goes to the matrix cores).
+ * Errors: as bs_conv_threshold_batch; INVALID_ARG also for pool_k < 1 or a window larger than the map;
+ * UNSUPPORTED for pool_k > 3.
+ */
+bs_status bs_pool_conv_threshold_batch(const uint64_t *in, int abits, int B, int H, int W, int C, int pool_k,
+                                       int pool_stride, const uint64_t *Fp, int wbits, bs_format wfmt, int F, int kh,
+                                       int kw, int stride, int pad, const int32_t *thr, int obits, uint64_t *Yp,
+                                       void *stream);
+
+/*
  * Dense engine.  The paper configures each quantized layer to run on either its
  * bit-serial engine or an 8-bit engine (Sec. 4.2) and gives the break-even rule (Sec.
  * 4.1.1).  On this chip the 8-bit matrix cores win the large compute-bound shapes, so the

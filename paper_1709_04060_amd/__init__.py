@@ -26,7 +26,7 @@ BS_I8, BS_I32 = 0, 1
 BS_ENGINE_BITSERIAL, BS_ENGINE_DENSE_I8, BS_ENGINE_DENSE_FP4, BS_ENGINE_AUTO = 0, 1, 2, 3
 
 EXPORTS = ("bs_words_per_row", "bs_lowered_depth", "bs_pack_planes", "bs_gemm", "bs_gemm_topbits", "bs_threshold_activate",
-           "bs_gemm_threshold", "bs_gemm_on", "bs_gemm_threshold_on", "bs_im2col_interleaved", "bs_im2col_interleaved_batch", "bs_conv_threshold", "bs_conv_threshold_batch", "bs_conv_threshold_batch_on", "bs_maxpool_packed",
+           "bs_gemm_threshold", "bs_gemm_on", "bs_gemm_threshold_on", "bs_im2col_interleaved", "bs_im2col_interleaved_batch", "bs_conv_threshold", "bs_conv_threshold_batch", "bs_conv_threshold_batch_on", "bs_pool_conv_threshold_batch", "bs_maxpool_packed",
            "bs_maxpool_packed_batch",
            "bs_unpack_planes", "bs_gemm_i8", "bs_gemm_i8_threshold", "bs_unpack_planes_fp4", "bs_gemm_fp4",
            "bs_gemm_fp4_threshold", "bs_streamline_collapse",
@@ -73,6 +73,10 @@ def load_library() -> ctypes.CDLL:
     lib.bs_conv_threshold_batch.restype = i32
     lib.bs_conv_threshold_batch_on.argtypes = [i32] + lib.bs_conv_threshold_batch.argtypes
     lib.bs_conv_threshold_batch_on.restype = i32
+    # in, abits, B, H, W, C, pool_k, pool_stride, Fp, wbits, wfmt, F, kh, kw, stride, pad, thr, obits, Yp, stream
+    lib.bs_pool_conv_threshold_batch.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, i32, i32, i32, i32, i32, i32, i32,
+                                                 vp, i32, vp, vp]
+    lib.bs_pool_conv_threshold_batch.restype = i32
     lib.bs_maxpool_packed_batch.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.bs_maxpool_packed_batch.restype = i32
     lib.bs_maxpool_packed.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp]; lib.bs_maxpool_packed.restype = i32
@@ -342,6 +346,32 @@ def bs_conv_threshold_batch(x: torch.Tensor, afmt: int, B: int, H: int, W: int, 
                                                    wfmt, F, kh, kw, stride, pad, _dev(thr, "thr"), obits, _dev(out, "out"),
                                                    _stream())
     _check(st, "bs_conv_threshold_batch")
+    return out
+
+
+def bs_pool_conv_threshold_batch(x: torch.Tensor, B: int, H: int, W: int, C: int, pool_k: int, pool_stride: int,
+                                 Fp: torch.Tensor, wfmt: int, kh: int, kw: int, stride: int, pad: int,
+                                 thr: torch.Tensor, obits: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """bs_maxpool_packed_batch + bs_conv_threshold_batch in one call: x [abits][B*H*W][S_C] is the unpooled map
+    (unsigned codes); the convolution reads its pool_k x pool_k / pool_stride maximum."""
+    if min(B, H, W, C, pool_k, pool_stride) <= 0 or pool_k > H or pool_k > W:
+        raise ValueError("bad pooling geometry")
+    PH, PW = (H - pool_k) // pool_stride + 1, (W - pool_k) // pool_stride + 1
+    if min(kh, kw, stride) <= 0 or pad < 0 or PH + 2 * pad < kh or PW + 2 * pad < kw:
+        raise ValueError("bad convolution geometry")
+    _want_planes(x, "x", C, rows=B * H * W)
+    _want_planes(Fp, "Fp", bs_lowered_depth(C, kh, kw))
+    OH, OW = (PH + 2 * pad - kh) // stride + 1, (PW + 2 * pad - kw) // stride + 1
+    abits = x.shape[0]
+    wbits, F, _ = Fp.shape
+    _want_thr(thr, F, obits)
+    if out is None:
+        out = _planes(obits, B * OH * OW, F, x.device)
+    _want_planes(out, "out", F, bits=obits, rows=B * OH * OW)
+    st = load_library().bs_pool_conv_threshold_batch(_dev(x, "x"), abits, B, H, W, C, pool_k, pool_stride, _dev(Fp, "Fp"),
+                                                     wbits, wfmt, F, kh, kw, stride, pad, _dev(thr, "thr"), obits,
+                                                     _dev(out, "out"), _stream())
+    _check(st, "bs_pool_conv_threshold_batch")
     return out
 
 

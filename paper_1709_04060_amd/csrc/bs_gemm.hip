@@ -143,10 +143,13 @@ extern "C" bs_status bs_gemm_threshold(const uint64_t *Wp, int wbits, bs_format 
     return gemm_common(BS_ENGINE_AUTO, Wp, wbits, wfmt, Ap, abits, afmt, M, N, K, nullptr, 0, thr, obits, Yp, true, stream);
 }
 
-extern "C" bs_status bs_conv_threshold_batch_on(bs_engine engine, const uint64_t *in, int abits, bs_format afmt, int B, int H,
-                                                int W, int C, const uint64_t *Fp, int wbits, bs_format wfmt, int F, int kh,
-                                                int kw, int stride, int pad, const int32_t *thr, int obits, uint64_t *Yp,
-                                                void *stream)
+namespace {
+
+// Convolution by implicit lowering, optionally reading its input through a max pooling of pool_k x pool_k windows
+// (pool_k = 0: none): H x W is the map in memory, PH x PW the map the convolution sees.
+bs_status conv_common(bs_engine engine, const uint64_t *in, int abits, bs_format afmt, int B, int H, int W, int C, int pool_k,
+                      int pool_stride, const uint64_t *Fp, int wbits, bs_format wfmt, int F, int kh, int kw, int stride,
+                      int pad, const int32_t *thr, int obits, uint64_t *Yp, void *stream)
 {
     if (engine != BS_ENGINE_BITSERIAL && engine != BS_ENGINE_DENSE_I8 && engine != BS_ENGINE_DENSE_FP4 &&
         engine != BS_ENGINE_AUTO)
@@ -159,12 +162,21 @@ extern "C" bs_status bs_conv_threshold_batch_on(bs_engine engine, const uint64_t
     // spatial padding is written as zero words, which is the value 0 only for these formats
     if (afmt == BS_BIPOLAR) return BS_ERR_UNSUPPORTED;
     if (obits > bs::kMaxBits) return BS_ERR_UNSUPPORTED;
-    if (H + 2 * pad < kh || W + 2 * pad < kw) return BS_ERR_INVALID_ARG;
+    int PH = H, PW = W;
+    if (pool_k > 0) {
+        if (pool_stride <= 0 || pool_k > H || pool_k > W) return BS_ERR_INVALID_ARG;
+        // the maximum is taken on the codes, which is the maximum of the values for unsigned codes only; the kernels
+        // hold the taps of one window in registers, up to 3 x 3
+        if (afmt != BS_UNSIGNED || pool_k > 3) return BS_ERR_UNSUPPORTED;
+        PH = (H - pool_k) / pool_stride + 1;
+        PW = (W - pool_k) / pool_stride + 1;
+    }
+    if (PH + 2 * pad < kh || PW + 2 * pad < kw) return BS_ERR_INVALID_ARG;
     if (!bs::aligned(in, 16) || !bs::aligned(Fp, 16) || !bs::aligned(Yp, 16) || !bs::aligned(thr, 4))
         return BS_ERR_ALIGNMENT;
     const int64_t Kl = bs_lowered_depth(C, kh, kw);
     const int64_t S = bs_words_per_row(Kl);
-    const int OH = (H + 2 * pad - kh) / stride + 1, OW = (W + 2 * pad - kw) / stride + 1;
+    const int OH = (PH + 2 * pad - kh) / stride + 1, OW = (PW + 2 * pad - kw) / stride + 1;
     const int64_t N = (int64_t)B * OH * OW;
     if (2 * S > kConvMaxLut || kh > 127 || kw > 127) return BS_ERR_UNSUPPORTED;
     if (result_may_overflow(Kl, wbits, wfmt, abits, afmt, false)) return BS_ERR_OVERFLOW_RISK;
@@ -182,9 +194,24 @@ extern "C" bs_status bs_conv_threshold_batch_on(bs_engine engine, const uint64_t
     g.thr = thr; g.obits = obits; g.T = (1 << obits) - 1;
     g.Y = reinterpret_cast<uint32_t *>(Yp);
     g.Yd = (int)(2 * bs_words_per_row(F));
-    g.cH = H; g.cW = W; g.cCd = (C + 31) / 32; g.cPix = (int)pix; g.cKW = kw;
+    g.cH = PH; g.cW = PW; g.cCd = (C + 31) / 32; g.cPix = (int)pix; g.cKW = kw;
     g.cStride = stride; g.cPad = pad; g.cOW = OW; g.cOHW = OH * OW; g.cB = B; g.cKused = (int)(Kl / 32);
     g.cVec = (g.cCd % 4 == 0 && g.cPix % 4 == 0) ? 1 : 0;
+    g.pK = pool_k > 0 ? pool_k : 0; g.pS = pool_stride; g.pH = H; g.pW = W;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool corr = (wfmt == BS_BIPOLAR);
+    if (pool_k > 0) {
+        // A kernel that covers the whole pooled map is a fully connected layer on the flattened map: with few images
+        // the weights are streamed once by the few-column kernel, whose activation fill does the pooling.
+        if (N <= kGemvMaxCols && OH == 1 && OW == 1 && pad == 0 && kh == PH && kw == PW) {
+            const int nc = N == 1 ? 1 : (N == 2 ? 2 : 4);
+            if ((size_t)abits * nc * (g.Kd >> 2) * 16 <= kGemvMaxLds) {
+                finish_params(g);
+                return launch_gemv(g, wbits, abits, true, false, st);
+            }
+        }
+        return dispatch_wb(g, wbits, abits, true, corr, true, false, st);
+    }
     // Engine (Sec. 4.2): the layer is the product F x Kl x N; the matrix-core kernel gathers the lowered columns itself.
     if (engine != BS_ENGINE_BITSERIAL) {
         const bs_engine e = engine == BS_ENGINE_AUTO ? bs_choose_engine(wbits, wfmt, abits, afmt, F, N, Kl) : engine;
@@ -196,11 +223,30 @@ extern "C" bs_status bs_conv_threshold_batch_on(bs_engine engine, const uint64_t
             q.conv = 1;
             q.cH = H; q.cW = W; q.cCd = g.cCd; q.cPix = g.cPix; q.cKW = kw; q.cStride = stride; q.cPad = pad;
             q.cOW = OW; q.cOHW = OH * OW; q.cB = B; q.cKused = g.cKused;
-            return launch_planes_mfma(q, e == BS_ENGINE_DENSE_FP4, true, static_cast<hipStream_t>(stream));
+            return launch_planes_mfma(q, e == BS_ENGINE_DENSE_FP4, true, st);
         }
     }
-    const bool corr = (wfmt == BS_BIPOLAR);
-    return dispatch_wb(g, wbits, abits, true, corr, true, false, static_cast<hipStream_t>(stream));
+    return dispatch_wb(g, wbits, abits, true, corr, true, false, st);
+}
+
+}  // namespace
+
+extern "C" bs_status bs_conv_threshold_batch_on(bs_engine engine, const uint64_t *in, int abits, bs_format afmt, int B, int H,
+                                                int W, int C, const uint64_t *Fp, int wbits, bs_format wfmt, int F, int kh,
+                                                int kw, int stride, int pad, const int32_t *thr, int obits, uint64_t *Yp,
+                                                void *stream)
+{
+    return conv_common(engine, in, abits, afmt, B, H, W, C, 0, 0, Fp, wbits, wfmt, F, kh, kw, stride, pad, thr, obits, Yp, stream);
+}
+
+extern "C" bs_status bs_pool_conv_threshold_batch(const uint64_t *in, int abits, int B, int H, int W, int C, int pool_k,
+                                                  int pool_stride, const uint64_t *Fp, int wbits, bs_format wfmt, int F,
+                                                  int kh, int kw, int stride, int pad, const int32_t *thr, int obits,
+                                                  uint64_t *Yp, void *stream)
+{
+    if (pool_k <= 0) return BS_ERR_INVALID_ARG;
+    return conv_common(BS_ENGINE_BITSERIAL, in, abits, BS_UNSIGNED, B, H, W, C, pool_k, pool_stride, Fp, wbits, wfmt, F, kh, kw,
+                       stride, pad, thr, obits, Yp, stream);
 }
 
 extern "C" bs_status bs_conv_threshold_batch(const uint64_t *in, int abits, bs_format afmt, int B, int H, int W, int C,

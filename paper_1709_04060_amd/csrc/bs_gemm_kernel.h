@@ -94,6 +94,10 @@ struct GemmParams {
     int cB;             // images in the batch
     int cKused;         // dwords of a lowered column that carry data: kh * kw * cCd
     int cVec;           // 1 if cCd and cPix are multiples of 4: a 16-byte chunk never straddles two taps
+    // max pooling folded into the implicit lowering (pK > 0): A points at the UNPOOLED planes [abits][cB][pH][pW][cPix]
+    // and cH x cW is the pooled map the convolution reads, cH = (pH - pK) / pS + 1
+    int pK, pS;         // pooling window (at most 3) and stride
+    int pH, pW;         // size of the unpooled map
     // single-column kernel: read the weights with the non-temporal hint (set for large weight sets)
     int stream_weights;
     // divisors of the workgroups' set-up code (filled by finish_params)
@@ -156,6 +160,56 @@ __device__ __forceinline__ int bcnt_acc(uint32_t x, int acc)
     int r;
     asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(acc));
     return r;
+}
+
+// Max pooling inside an operand fetch.  Thresholding is monotone, so the maximum of the thresholded codes is the
+// thresholded maximum; codes are unsigned and held bit-sliced (one 32-channel word per plane), and the maximum of
+// two such numbers is a most-significant-plane-first comparison in bitwise logic.
+// pool_load: the channel word at dword offset `at` of the window's top-left pixel, all AB planes, for the 3 x 3 taps a
+// window can have.  Every load is unconditional and differs from its neighbours by a wavefront-uniform offset: taps
+// beyond a smaller window repeat tap (0, 0), which leaves a maximum unchanged, and an item that is to read as zero
+// (padding, past the depth) loads the first words of the map and is cleared by pool_max's `keep` mask.
+// V: uint32_t (one 32-channel word) or pool_v4 (a 16-byte chunk of four such words, where a chunk never straddles taps).
+typedef unsigned pool_v4 __attribute__((ext_vector_type(4)));
+template <int AB, typename V>
+__device__ __forceinline__ void pool_load(const uint32_t *src, int plane_stride, int at, int row_stride, int pix_stride,
+                                          int k, bool valid, V (&raw)[9][AB])
+{
+    if (__builtin_amdgcn_ballot_w64(valid) == 0) {  // nothing to read in this wavefront: no load instructions at all
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+            for (int j = 0; j < AB; ++j) raw[t][j] = V(0u);
+        return;
+    }
+    const unsigned lane_off = valid ? (unsigned)at : 0u;
+#pragma unroll
+    for (int a = 0; a < 3; ++a)
+#pragma unroll
+        for (int b = 0; b < 3; ++b) {
+            const int off = (a < k ? a : 0) * row_stride + (b < k ? b : 0) * pix_stride;  // uniform
+#pragma unroll
+            for (int j = 0; j < AB; ++j) raw[a * 3 + b][j] = *reinterpret_cast<const V *>(src + (j * plane_stride + off) + lane_off);
+        }
+}
+template <int AB, typename V>
+__device__ __forceinline__ void pool_max(const V (&raw)[9][AB], uint32_t keep, V (&best)[AB])
+{
+#pragma unroll
+    for (int j = 0; j < AB; ++j) best[j] = raw[0][j];
+#pragma unroll
+    for (int t = 1; t < 9; ++t) {
+        V gt = V(0u), eq = V(0xFFFFFFFFu);  // per channel: raw[t] > best, decided at the highest differing plane
+#pragma unroll
+        for (int j = AB - 1; j >= 0; --j) {
+            gt |= eq & raw[t][j] & ~best[j];
+            eq &= ~(raw[t][j] ^ best[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < AB; ++j) best[j] = (gt & raw[t][j]) | (~gt & best[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < AB; ++j) best[j] &= V(keep);
 }
 
 // Alg. 1's inner statement on one 16-byte chunk: acc += popcount(a & b) over 4 dwords.
@@ -262,13 +316,18 @@ __device__ __forceinline__ bool tile_of_block(const GemmParams &p, int bid, int 
 // XOR: both operands bipolar (W1A1): popcount(XOR) instead of popcount(AND), no correction terms.
 // KT: dwords of depth per packed row and stage (a multiple of 32; 32 everywhere except the
 // 32 x 32 tiles of more than four plane pairs, which take 64: see launch_planes).
+// POOL (with CONV): the image the columns are gathered from is the maximum over pK x pK windows of the map in
+// memory: every thread forms a few 32-channel words of the pooled, lowered tile per stage (all planes at once, the
+// comparison needs them all) instead of copying 16-byte chunks, so that a pooling layer between two convolutions
+// costs no launch and its output never exists in memory.
 template <int WB, int AB, int TM, int TN, int WM, int WN, int KS, int KT, bool FUSE, bool CORR, bool CONV = false,
-          bool XOR = false, bool IDLE = true>
+          bool XOR = false, bool IDLE = true, bool POOL = false>
 __global__ void __launch_bounds__(WM * WN * KS * 64)
 bs_gemm_kernel(const GemmParams p)
 {
     constexpr int KCH = KT / 4;  // 16-byte chunks per row and stage
     static_assert(!XOR || (WB == 1 && AB == 1 && !CORR), "the XOR form exists for one plane per operand only");
+    static_assert(!POOL || CONV, "pooling is part of the implicit lowering");
     constexpr int BM = 8 * TM * WM, BN = 8 * TN * WN, NT = 64 * WM * WN * KS;
     constexpr int WROWS = WB * BM, AROWS = AB * BN, ROWS = WROWS + AROWS;
     constexpr int CHUNKS = ROWS * KCH;
@@ -335,6 +394,55 @@ bs_gemm_kernel(const GemmParams p)
             }
         }
     }
+    // POOL: the words of the pooled activation tile this thread forms per stage (dword q of column r)
+    constexpr int PITEMS = BN * KT, PPT = POOL ? (PITEMS + NT - 1) / NT : 1;
+    int pl_src[PPT], pl_h[PPT], pl_w[PPT], pl_dst[PPT], pl_cnt[PPT];
+    uint32_t praw[PPT][9][AB], pkeep[PPT];
+    if constexpr (POOL) {
+#pragma unroll
+        for (int t = 0; t < PPT; ++t) {
+            const int u = tid + t * NT, r = u / KT, q = u % KT;
+            pl_src[t] = -1; pl_h[t] = 0; pl_w[t] = 0; pl_cnt[t] = 0;
+            pl_dst[t] = ((WROWS + r) * KCH + ((q >> 2) ^ ((r / TN) & 7))) * 4 + (q & 3);
+            if (u < PITEMS && n0 + r < p.N) {
+                const int b = fdiv(n0 + r, p.dOHW), opix = (n0 + r) - b * p.cOHW;
+                const int oh = fdiv(opix, p.dOW), ow = opix - oh * p.cOW;
+                pl_h[t] = oh * p.cStride - p.cPad;
+                pl_w[t] = ow * p.cStride - p.cPad;
+                pl_src[t] = b * p.pH * p.pW * p.cPix;  // image b in plane 0 of the unpooled map
+            }
+        }
+    }
+    // (Item u is word u % KT of column u / KT.  Columns fastest instead, so that in a partly filled last stage whole
+    // wavefronts have nothing to read and skip their loads, measured slower: conv3 behind pool2 8.0 instead of 7.2 us.)
+    auto pool_fetch = [&](int k0) {
+        const int plane_stride = p.cB * p.pH * p.pW * p.cPix;
+#pragma unroll
+        for (int t = 0; t < PPT; ++t) {
+            const int u = tid + t * NT, l = k0 + u % KT;
+            int tap = -1;
+            if (u < PITEMS && pl_src[t] >= 0 && l < p.Kd) tap = lut[l];
+            const int ih = pl_h[t] + (tap >> 24), iw = pl_w[t] + ((tap >> 16) & 0xFF);  // pixel of the pooled map
+            const bool ok = tap >= 0 && ih >= 0 && ih < p.cH && iw >= 0 && iw < p.cW;
+            const int at = pl_src[t] + (ih * p.pS * p.pW + iw * p.pS) * p.cPix + (tap & 0xFFFF);
+            pool_load<AB, uint32_t>(p.A, plane_stride, at, p.pW * p.cPix, p.cPix, p.pK, ok, praw[t]);
+            pkeep[t] = ok ? 0xFFFFFFFFu : 0u;
+        }
+    };
+    auto pool_write = [&]() {
+        uint32_t *ldsD = reinterpret_cast<uint32_t *>(lds);
+#pragma unroll
+        for (int t = 0; t < PPT; ++t) {
+            if (tid + t * NT >= PITEMS) continue;
+            uint32_t best[AB];
+            pool_max<AB, uint32_t>(praw[t], pkeep[t], best);
+#pragma unroll
+            for (int j = 0; j < AB; ++j) {
+                ldsD[pl_dst[t] + j * BN * KCH * 4] = best[j];
+                if (CORR) pl_cnt[t] += p.ccol[j] * __popc(best[j]);
+            }
+        }
+    };
     uint4 stage[CPT];
     // DO_W / DO_A: the weight slots, the activation slots or (in the depth loop) both
     auto fetch_part = [&](int k0, auto w_c, auto a_c) {
@@ -342,7 +450,8 @@ bs_gemm_kernel(const GemmParams p)
         // CONV: the table entries of all activation chunks first (one 16-byte LDS read each),
         // so that a single wait precedes the gathers instead of one per word
         int4 tap4[CONV ? CPT : 1];
-        if constexpr (CONV && DO_A) {
+        if constexpr (POOL && DO_A) pool_fetch(k0);
+        if constexpr (CONV && DO_A && !POOL) {
 #pragma unroll
             for (int s = 0; s < CPT; ++s) {
                 const int c = (tid + s * NT) % KCH;
@@ -354,7 +463,7 @@ bs_gemm_kernel(const GemmParams p)
 #pragma unroll
         for (int s = 0; s < CPT; ++s) {
             const int c = (tid + s * NT) % KCH;
-            if ((s * NT < WROWS * KCH) ? !DO_W : !DO_A) continue;  // resolved at compile time
+            if ((s * NT < WROWS * KCH) ? !DO_W : (!DO_A || POOL)) continue;  // resolved at compile time
             uint4 v = make_uint4(0, 0, 0, 0);
             if (s * NT < WROWS * KCH) {
                 if (goff[s] >= 0 && k0 + c * 4 < p.Kd)
@@ -437,9 +546,11 @@ bs_gemm_kernel(const GemmParams p)
         __syncthreads();  // everyone is done reading the previous stage
 #pragma unroll
         for (int s = 0; s < CPT; ++s) {
+            if (POOL && s * NT >= WROWS * KCH) continue;  // the activation tile comes from pool_write
             if (tid + s * NT < CHUNKS) lds[loff[s]] = stage[s];
             if (CORR) cnt[s] += popc4(stage[s]);
         }
+        if constexpr (POOL) pool_write();
         __syncthreads();
         if (FULL && k0 + KT < p.Kd) fetch(k0 + KT);
 
@@ -515,8 +626,13 @@ bs_gemm_kernel(const GemmParams p)
             if (id < CHUNKS && cweight[s] != 0) {
                 const int srow = id / KCH;
                 if (srow < WROWS) atomicAdd(&corr_row[srow % BM], cweight[s] * cnt[s]);
-                else atomicAdd(&corr_col[(srow - WROWS) % BN], cweight[s] * cnt[s]);
+                else if (!POOL) atomicAdd(&corr_col[(srow - WROWS) % BN], cweight[s] * cnt[s]);
             }
+        }
+        if constexpr (POOL) {
+#pragma unroll
+            for (int t = 0; t < PPT; ++t)
+                if (tid + t * NT < PITEMS && pl_cnt[t] != 0) atomicAdd(&corr_col[(tid + t * NT) / KT], pl_cnt[t]);
         }
     }
     __syncthreads();  // also: all LDS tile reads are finished, the tile space may be reused
@@ -714,6 +830,15 @@ bs_status launch_variant(const GemmParams &g, dim3 grid, bool fuse, bool corr, b
     }
     if (conv) {  // implicit lowering exists with the thresholding epilogue only
         if (!fuse) return BS_ERR_UNSUPPORTED;
+        if (g.pK > 0) {  // pooled fetch: instantiated for the narrow tiles only (launch_planes takes no other for it)
+            if constexpr (KS == 4 && TN <= 2) {
+                if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, CAN_CORR, true, false, IDLE, true><<<grid, block, 0, st>>>(g);
+                else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, false, true, false, IDLE, true><<<grid, block, 0, st>>>(g);
+                return bs::after_launch();
+            } else {
+                return BS_ERR_UNSUPPORTED;
+            }
+        }
         if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, CAN_CORR, true, false, IDLE><<<grid, block, 0, st>>>(g);
         else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, false, true, false, IDLE><<<grid, block, 0, st>>>(g);
     } else if (fuse) {
@@ -773,7 +898,9 @@ bs_status launch_planes(const GemmParams &g, bool fuse, bool corr, bool conv, bo
     }
     // just above the tiny grids 32 x 16 tiles still pay: twice the workgroups, so that two wavefronts share a SIMD
     // (4096 x 9216 x 64 W1A2: 18.7 -> 15.5 us; W4A4 4096 x 4096 x 64: 49.9 -> 41.5 us; a tie from 512 tiles on)
-    if (tiles32 <= kHalfWidthMaxTiles32) return launch_cfg<WB, AB, 4, 2, 1, 1, 4, KT_DEEP>(g, fuse, corr, conv, xr, st);
+    // (also for every larger grid with a pooled fetch, whose kernels exist for the narrow tiles only: a thread of
+    // a wider tile would have to hold the window taps of eight and more words per stage)
+    if (tiles32 <= kHalfWidthMaxTiles32 || (conv && g.pK > 0)) return launch_cfg<WB, AB, 4, 2, 1, 1, 4, KT_DEEP>(g, fuse, corr, conv, xr, st);
     if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4, KT_DEEP>(g, fuse, corr, conv, xr, st);
     return launch_cfg<WB, AB, 4, 4, 2, 2, 1, kStageDwords>(g, fuse, corr, conv, xr, st);
 }

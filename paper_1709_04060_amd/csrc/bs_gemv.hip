@@ -23,8 +23,59 @@ constexpr int LANES_PER_ROW = 32;
 constexpr int GEMV_THREADS = ROWS_PER_BLOCK * LANES_PER_ROW;
 constexpr int UNROLL = 4;           // chunks per lane and plane fetched in one go
 
+// Pooled activation fill: item id = n * (Kd / VW) + u is unit u (VW = 1 or 4 words) of column n, i.e. words
+// q = u * VW .. of the flattened pooled map of image n0 + n; issue() requests the window taps of all planes, store()
+// takes their bit-sliced maximum, writes it to the planes in LDS ([AB][NC][Kd] words) and counts its bits.
+template <int AB, int NC, typename V>
+struct PoolFill {
+    static constexpr int VW = sizeof(V) / 4;
+    V raw[9][AB];
+    uint32_t keep;
+    __device__ __forceinline__ void locate(const GemmParams &p, int id, int &n, int &q) const
+    {
+        const int units = p.Kd / VW;
+        n = 0;
+#pragma unroll
+        for (int z = 0; z < NC; ++z)
+            if (id >= units) { id -= units; ++n; }
+        q = id * VW;
+    }
+    __device__ __forceinline__ void issue(const GemmParams &p, int id, int n0)
+    {
+        int n, q;
+        locate(p, id, n, q);
+        const bool ok = n < NC && q < p.cKused && n0 + n < p.N;
+        const int tap = fdiv(q, p.dCd), cd = q - tap * p.cCd;
+        const int fr = fdiv(tap, p.dKW), fs = tap - fr * p.cKW;  // pixel of the pooled map
+        const int at = ((n0 + n) * p.pH * p.pW + fr * p.pS * p.pW + fs * p.pS) * p.cPix + cd;
+        pool_load<AB, V>(p.A, p.cB * p.pH * p.pW * p.cPix, at, p.pW * p.cPix, p.cPix, p.pK, ok, raw);
+        keep = ok ? 0xFFFFFFFFu : 0u;
+    }
+    __device__ __forceinline__ void store(const GemmParams &p, int id, uint32_t *lds_words, int (&colsum)[NC]) const
+    {
+        int n, q;
+        locate(p, id, n, q);
+        if (n >= NC) return;
+        V best[AB];
+        pool_max<AB, V>(raw, keep, best);
+#pragma unroll
+        for (int j = 0; j < AB; ++j) {
+            *reinterpret_cast<V *>(lds_words + (j * NC + n) * p.Kd + q) = best[j];
+            int pc;
+            if constexpr (VW == 1) pc = __popc(best[j]);
+            else pc = __popc(best[j].x) + __popc(best[j].y) + __popc(best[j].z) + __popc(best[j].w);
+            pc *= p.ccol[j];
+#pragma unroll
+            for (int nn = 0; nn < NC; ++nn) colsum[nn] += (nn == n) ? pc : 0;
+        }
+    }
+};
+
 // NT: read the weights with the non-temporal hint (large weight sets, single column).
-template <int WB, int AB, int NC, bool FUSE, bool XOR = false, bool NT = false>
+// POOL: a column is not a packed row in memory but the flattened maximum over pK x pK windows of image n of an
+// unpooled map (a fully connected layer behind a pooling layer, i.e. a convolution whose kernel covers the whole
+// pooled map): the fill of the activation planes forms each 32-channel word from its window, all planes at once.
+template <int WB, int AB, int NC, bool FUSE, bool XOR = false, bool NT = false, bool POOL = false>
 __global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams p)
 {
     bs::prefetch_kernel_arguments<(int)sizeof(GemmParams)>();
@@ -64,6 +115,15 @@ __global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams 
             }
         }
     };
+    // POOL: the activation fill forms pooled words instead of copying.  The first items' window loads are requested even
+    // before the weights: they return first, and the comparisons run while the weight stream is on its way.
+    // One 32-channel word per item, two items per thread and trip.  (16-byte items, a quarter of the load instructions,
+    // measured slower: fc6 behind pool5 6.2 instead of 5.3 us; the comparisons of four words then sit in one wavefront.)
+    PoolFill<AB, NC, uint32_t> fill[2];
+    if constexpr (POOL) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) fill[h].issue(p, tid + h * GEMV_THREADS, n0);
+    }
     fetch_w(g);  // the weight stream starts first; the activation fill below overlaps with it
     // Row leaders fetch their thresholds now as well, so that the epilogue does not wait
     // for a second round trip to memory.
@@ -84,7 +144,17 @@ __global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams 
 #pragma unroll
         for (int n = 0; n < NC; ++n) colsum[n] = 0;
         const uint4 *Ag = reinterpret_cast<const uint4 *>(p.A);
-        const int total = AB * NC * nch;
+        const int total = POOL ? 0 : AB * NC * nch;
+        if constexpr (POOL) {
+            uint32_t *ldsD = reinterpret_cast<uint32_t *>(ldsA);
+            for (int id = tid; id < NC * p.Kd; id += 2 * GEMV_THREADS) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    if (id != tid) fill[h].issue(p, id + h * GEMV_THREADS, n0);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) fill[h].store(p, id + h * GEMV_THREADS, ldsD, colsum);
+            }
+        }
         for (int id = tid; id < total; id += GEMV_THREADS) {
             const int c = id % nch, jn = id / nch;
             const int n = jn % NC, j = jn / NC;
@@ -205,6 +275,11 @@ bs_status launch_gemv_nc(const GemmParams &g, bool fuse, bool xr, size_t lds_byt
         } else {
             return BS_ERR_INVALID_ARG;
         }
+    }
+    if (g.pK > 0) {  // pooled columns: with the thresholding epilogue only
+        if (!fuse) return BS_ERR_UNSUPPORTED;
+        bs_gemv_kernel<WB, AB, NC, true, false, false, true><<<grid, GEMV_THREADS, lds_bytes, st>>>(g);
+        return after_launch();
     }
     if constexpr (NC == 1) {
         if (g.stream_weights) {

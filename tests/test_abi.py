@@ -82,6 +82,15 @@ def test_argument_errors_of_the_later_entry_points():
     # pooling window larger than the map
     assert lib.bs_maxpool_packed(p, 2, 2, 2, 32, 3, 2, p, None) == bs.BS_ERR_INVALID_ARG
     assert lib.bs_maxpool_packed(p, 5, 8, 8, 32, 3, 2, p, None) == bs.BS_ERR_UNSUPPORTED
+    # convolution behind a pooling: window of 1..3 inside the map, a kernel that fits the POOLED map
+    pc = lib.bs_pool_conv_threshold_batch   # in, abits, B, H, W, C, pool_k, pool_stride, Fp, wbits, wfmt, F, kh, kw, stride, pad, thr, obits, Yp, stream
+    assert pc(p, 2, 1, 13, 13, 64, 0, 2, p, 1, BP, 16, 3, 3, 1, 1, p, 2, p, None) == bs.BS_ERR_INVALID_ARG
+    assert pc(p, 2, 1, 13, 13, 64, 3, 0, p, 1, BP, 16, 3, 3, 1, 1, p, 2, p, None) == bs.BS_ERR_INVALID_ARG
+    assert pc(p, 2, 1, 2, 2, 64, 3, 2, p, 1, BP, 16, 1, 1, 1, 0, p, 2, p, None) == bs.BS_ERR_INVALID_ARG
+    assert pc(p, 2, 1, 13, 13, 64, 4, 2, p, 1, BP, 16, 3, 3, 1, 1, p, 2, p, None) == bs.BS_ERR_UNSUPPORTED
+    assert pc(p, 2, 1, 13, 13, 64, 3, 2, p, 1, BP, 16, 7, 7, 1, 0, p, 2, p, None) == bs.BS_ERR_INVALID_ARG      # pooled map is 6 x 6
+    assert pc(p, 2, 1, 13, 13, 64, 3, 2, None, 1, BP, 16, 3, 3, 1, 1, p, 2, p, None) == bs.BS_ERR_INVALID_ARG
+    assert pc(p, 2, 1, 13, 13, 64, 3, 2, p, 1, BP, 16, 3, 3, 1, 1, p, 2, p + 8, None) == bs.BS_ERR_ALIGNMENT
     # dense engine: leading dimensions must be multiples of 16 and >= K; depth bound
     assert lib.bs_gemm_i8(p, 24, p, 32, 4, 4, 20, p, 4, None) == bs.BS_ERR_ALIGNMENT
     assert lib.bs_gemm_i8(p, 16, p, 32, 4, 4, 20, p, 4, None) == bs.BS_ERR_INVALID_ARG

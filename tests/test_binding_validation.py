@@ -115,6 +115,17 @@ def test_convolution_and_pooling_geometry():
         bs.bs_im2col_interleaved(x, 5, 5, 32, 3, 3, 1, 1, out=planes(2, 9, 288))
     with pytest.raises(ValueError, match="geometry"):
         bs.bs_maxpool_packed(x, 5, 5, 32, 6, 2)
+    # convolution behind a pooling: 5 x 5 map, 2 x 2 / 1 windows -> 4 x 4 pooled map
+    with pytest.raises(ValueError, match="GPU tensor"):
+        bs.bs_pool_conv_threshold_batch(x, 1, 5, 5, 32, 2, 1, Fp, BP, 3, 3, 1, 1, t, 2)
+    with pytest.raises(ValueError, match="pooling geometry"):
+        bs.bs_pool_conv_threshold_batch(x, 1, 5, 5, 32, 6, 1, Fp, BP, 3, 3, 1, 1, t, 2)
+    with pytest.raises(ValueError, match="convolution geometry"):
+        bs.bs_pool_conv_threshold_batch(x, 1, 5, 5, 32, 2, 1, planes(1, 16, 800), BP, 5, 5, 1, 0, t, 2)   # 5 x 5 kernel on the 4 x 4 map
+    with pytest.raises(ValueError, match="must hold 36 rows"):
+        bs.bs_pool_conv_threshold_batch(x, 1, 6, 6, 32, 2, 1, Fp, BP, 3, 3, 1, 1, t, 2)
+    with pytest.raises(ValueError, match="must hold 16 rows"):
+        bs.bs_pool_conv_threshold_batch(x, 1, 5, 5, 32, 2, 1, Fp, BP, 3, 3, 1, 1, t, 2, out=planes(2, 25, 16))
     with pytest.raises(ValueError, match="must hold 36 rows"):
         bs.bs_maxpool_packed(x, 6, 6, 32, 3, 2)
 

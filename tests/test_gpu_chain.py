@@ -156,3 +156,85 @@ def test_conv_and_pool_on_a_batch(B, H, W, C, F, k, s, p, w, wf, a, af, obits):
         wantp = np.concatenate([oracle.pack(oracle.maxpool(y, 2, 2).reshape(-1, F), obits, U) for y in Y], axis=1)
         pooled = bs.bs_maxpool_packed_batch(two, B, OH, OW, F, 2, 2)
         assert_equal(planes_to_numpy(pooled), wantp, "maxpool_packed_batch")
+
+
+# (B, H, W, C, pool window, pool stride, F, kernel, stride, pad): ragged channel counts (words of 32 and of 64 channels,
+# 16-byte chunks inside one tap or across taps), every tile width the pooled fetch runs on (8 columns up to 200 tiles,
+# 16 beyond), windows of 1, 2 and 3, kernels that cover the whole pooled map (the fully connected case: few-column
+# kernel up to 4 images, tiled beyond), spatial padding.
+POOL_CONV_CASES = [(1, 27, 27, 256, 3, 2, 384, 3, 1, 1), (1, 13, 13, 256, 3, 2, 512, 6, 1, 0), (3, 13, 13, 256, 3, 2, 100, 6, 1, 0),
+                   (7, 13, 13, 128, 3, 2, 96, 6, 1, 0), (2, 9, 8, 40, 2, 2, 33, 3, 1, 1), (5, 11, 11, 96, 3, 1, 70, 5, 2, 2),
+                   (1, 7, 7, 3, 2, 1, 5, 1, 1, 0), (24, 12, 12, 64, 2, 2, 64, 3, 1, 1), (4, 6, 6, 130, 1, 1, 40, 6, 1, 0),
+                   (2, 10, 10, 32, 3, 3, 48, 2, 1, 0), (8, 27, 27, 64, 3, 2, 384, 3, 1, 1)]
+
+
+@pytest.mark.parametrize("B,H,W,C,pk,ps,F,k,s,p", POOL_CONV_CASES)
+@pytest.mark.parametrize("w,wf,a,obits", [(1, BP, 2, 2), (2, TC, 2, 2), (4, TC, 4, 4), (1, U, 3, 1), (3, U, 1, 3)])
+def test_pool_conv_threshold(B, H, W, C, pk, ps, F, k, s, p, w, wf, a, obits):
+    """Pooling folded into the convolution's operand fetch: equal to the oracle's max pooling followed by its direct
+    convolution and thresholds, image by image, and to the library's two-call route."""
+    rng = np.random.default_rng(B * 7919 + H * W + C + F + w + a + pk)
+    x = draw(rng, (B, H, W, C), a, U)
+    filt = draw(rng, (F, k, k, C), w, wf)
+    pooled = [oracle.maxpool(x[b], pk, ps) for b in range(B)]
+    convs = [oracle.conv_direct(pm, filt, s, p) for pm in pooled]
+    lo, hi = min(int(c.min()) for c in convs), max(int(c.max()) for c in convs)
+    T = (1 << obits) - 1
+    thr = np.sort(rng.integers(lo - 2, hi + 3, size=(F, T)), axis=1).astype(np.int32)
+    OH, OW, _ = convs[0].shape
+    want = np.concatenate([oracle.threshold_pack(c.reshape(OH * OW, F).T.copy(), thr, obits) for c in convs], axis=1)
+    Cp = 32 * ((C + 31) // 32)
+    xp = bs.bs_pack_planes(dev(x.reshape(B * H * W, C)), a, bs.BS_UNSIGNED)
+    Fp = bs.bs_pack_planes(dev(pad_last(filt, Cp).reshape(F, -1)), w, FMT[wf])
+    got = bs.bs_pool_conv_threshold_batch(xp, B, H, W, C, pk, ps, Fp, FMT[wf], k, k, s, p, dev(thr), obits)
+    assert_equal(planes_to_numpy(got), want, "pool_conv_threshold_batch")
+    PH, PW = (H - pk) // ps + 1, (W - pk) // ps + 1
+    two = bs.bs_conv_threshold_batch(bs.bs_maxpool_packed_batch(xp, B, H, W, C, pk, ps), bs.BS_UNSIGNED, B, PH, PW, C, Fp,
+                                     FMT[wf], k, k, s, p, dev(thr), obits)
+    assert_equal(planes_to_numpy(two), want, "maxpool_packed_batch + conv_threshold_batch")
+
+
+@pytest.mark.parametrize("scale", [2, 1])
+def test_alexnet_inner_chain_six_launches(scale):
+    """The chain with both pooling layers folded into their consumers (conv3 reads pool2's windows, fc6 reads pool5's
+    as a convolution over the whole pooled map): six launches, every map after a fused layer equal to the oracle's."""
+    x, layers = workloads.alexnet_inner(scale)
+    H, W, C = x.shape
+    cur = bs.bs_pack_planes(dev(x.reshape(H * W, C)), 2, bs.BS_UNSIGNED)
+    ref = x
+    pool = None        # geometry of a pooling layer waiting for its consumer
+    launches = 0
+    for L in layers:
+        if L["kind"] == "pool":
+            pool = L["geom"]
+            ref = oracle.maxpool(ref, pool[3], pool[4])
+            continue
+        if L["kind"] == "conv":
+            H, W, C, F, k, s, p = L["geom"]
+            Cp = 32 * ((C + 31) // 32)
+            Fp = bs.bs_pack_planes(dev(pad_last(L["filt"], Cp).reshape(F, -1)), 1, bs.BS_BIPOLAR)
+            if pool is not None:
+                cur = bs.bs_pool_conv_threshold_batch(cur, 1, pool[0], pool[1], pool[2], pool[3], pool[4], Fp, bs.BS_BIPOLAR,
+                                                      k, k, s, p, dev(L["thr"]), 2)
+            else:
+                cur = bs.bs_conv_threshold(cur, bs.BS_UNSIGNED, H, W, C, Fp, bs.BS_BIPOLAR, k, k, s, p, dev(L["thr"]), 2)
+            want, ref = conv_reference(ref, L["filt"], L["thr"], s, p, 2)
+            ref = ref.astype(np.int8)
+        else:
+            M, K = L["geom"]
+            Wp = bs.bs_pack_planes(dev(L["W"]), 1, bs.BS_BIPOLAR)
+            if pool is not None:                                 # fc6: a convolution whose kernel is the whole pooled map
+                PH, PW = ref.shape[0], ref.shape[1]
+                assert PH * PW * pool[2] == K and pool[2] % 64 == 0
+                cur = bs.bs_pool_conv_threshold_batch(cur, 1, pool[0], pool[1], pool[2], pool[3], pool[4], Wp, bs.BS_BIPOLAR,
+                                                      PH, PW, 1, 0, dev(L["thr"]), 2)
+                ref = ref.reshape(K, 1)
+            else:
+                cur = bs.bs_gemm_threshold(Wp, bs.BS_BIPOLAR, cur, bs.BS_UNSIGNED, K, dev(L["thr"]), 2)
+            Cmat = oracle.gemm(L["W"], ref.astype(np.int8))
+            want = oracle.threshold_pack(Cmat, L["thr"], 2)
+            ref = oracle.threshold(Cmat, L["thr"]).astype(np.int8)
+        pool = None
+        launches += 1
+        assert_equal(planes_to_numpy(cur), want, "six-launch chain after %s" % L["name"])
+    assert launches == 6
