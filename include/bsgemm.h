@@ -343,10 +343,15 @@ bs_status bs_streamline_thresholds(const double *t, int T, const double *a, cons
  *               min(3.88 + G (0.69 + 0.2 p + 0.031 p k), 3.64 + R p (0.253 k + 0.21))   (5 <= N <= 16), with
  *               G = ceil(N / 4) M / 4096 (streaming kernel, groups of four columns), R = 1 + max(0, B - 256) / 900,
  *               B = ceil(M / 32) ceil(N / 8) (tiled kernel, 32 x 8 tiles); bs_gemm itself picks between these two
- *   dense fp4   5.5 + ceil(K / 256) r c + 0.22 abits MN / 1e6     r = rounds of tiles over the chip (bs_planes_tile),
- *   dense int8  6.0 + ceil(K / 128) r c + 0.29 abits MN / 1e6     c = microseconds per period of the kernel's pipeline:
- *               fp4 1.96 (256 x 256 tiles) or 0.92 + 0.24 f (128 x 128), int8 2.28 max(f, 0.85) or 1.10 + 0.25 f,
- *               f = the part of the chip's tile slots that is filled
+ *   dense       F + ceil(K / d) r c + E abits MN / 1e6, with d = 256 depth indices per period of the kernel's pipeline
+ *               as fp4 codes, 128 as int8 codes; r = rounds of tiles over the chip (bs_planes_tile); and the time of a
+ *               period c = c1 + c2 P + f (c3 + c4 P) + c5 max(0, f - 1/2), P = wbits + abits planes to request and merge,
+ *               f = the part of the chip's tile slots that is filled (two small tiles share a compute unit beyond 1/2):
+ *                                    F      c1     c2      c3      c4      c5     E
+ *                 int8, 128 x 128    6.32   0.809  0.0635  0.0328  0.0822  0.567  0.218
+ *                 int8, 256 x 256   12.15   1.262  0.1438  0.1413  0.0830  0      0.117
+ *                 fp4,  128 x 128    5.58   0.694  0.0760  0.0752  0.0619  0.612  0.218
+ *                 fp4,  256 x 256   10.67   1.008  0.1714  0       0.1319  0      0.0708
  * N <= 4 is always bit-serial (weights are read once, wbits/8 byte per weight, and nothing is expanded).
  * Invalid arguments (bits outside 1..4, bipolar with bits != 1, non-positive sizes) return BS_ENGINE_BITSERIAL.
  */

@@ -451,9 +451,12 @@ def bs_choose_engine(wbits: int, wfmt: int, abits: int, afmt: int, M: int, N: in
     return load_library().bs_choose_engine(wbits, wfmt, abits, afmt, M, N, K)
 
 
-def bs_planes_tile(M: int, N: int) -> int:
-    """Host-only: tile edge (256 or 128) of the matrix-core kernel on packed planes for an M x N output."""
-    return int(load_library().bs_planes_tile(int(M), int(N), None, None))
+def bs_planes_tile(M: int, N: int) -> tuple[int, int, int]:
+    """Host-only: (tile edge 256 or 128, rounds over the chip, tiles) of the matrix-core kernel on packed planes for
+    an M x N output."""
+    rounds, tiles = ctypes.c_longlong(0), ctypes.c_longlong(0)
+    tile = load_library().bs_planes_tile(int(M), int(N), ctypes.byref(rounds), ctypes.byref(tiles))
+    return int(tile), int(rounds.value), int(tiles.value)
 
 
 def bs_probe_popcount_rate(sink: torch.Tensor, passes: int) -> int:

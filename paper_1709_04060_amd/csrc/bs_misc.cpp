@@ -19,8 +19,9 @@ extern "C" int bs_version(void) { return 100; }
 // Per-layer engine choice (Sec. 4.1.1 / 4.2): the fastest of the engines under time models fitted to measurements on
 // MI355X over M in {256, 1024, 4096}, N in {17 .. 4096}, K in {512 .. 8192} and W1A1, W1A2, W2A2, W3A3, W4A4, all from
 // packed planes with the fused thresholding epilogue (375 shapes; non-negative least squares on the relative error).
-// Over those shapes the choice costs 0.9 % on average and 33 % at worst against always taking the fastest engine, where
-// always bit-serial costs 80 % on average (17 x at worst) and always matrix cores 92 % (5.9 x).  Microseconds.
+// Over those shapes the choice costs 0.3 % on average and 27 % at worst against always taking the fastest engine (three
+// shapes above 15 %), where always bit-serial costs 80 % on average (17 x at worst) and always matrix cores 92 % (5.9 x).
+// Microseconds.
 namespace {
 
 // The dense engines as the library runs them on packed planes: 4-bit floating-point codes for operands of at most two
@@ -31,19 +32,26 @@ bool fp4_usable(int wbits, int abits, int64_t K)
 }
 
 // The matrix-core kernel on packed planes: a 256 x 256 tile per compute unit or two 128 x 128 tiles (bs_planes_tile
-// makes the same choice for the launch), `per` depth indices per period of the kernel's pipeline.
-double t_planes(double M, double N, double K, int abits, bool fp4)
+// makes the same choice for the launch).  Time = fixed + periods x rounds x (time of a period) + epilogue, where a
+// period (128 depth indices as int8 codes, 256 as fp4 codes) costs more with the planes P = wbits + abits the loader
+// has to request and merge, with the share `fill` of the chip's tile slots in use (the requests meet in L2), and, for
+// the small tile, once two workgroups share a compute unit (fill > 1/2).
+double t_planes(double M, double N, double K, int wbits, int abits, bool fp4)
 {
     long long rounds, tiles;
     const int tile = bs_planes_tile((int64_t)M, (int64_t)N, &rounds, &tiles);
     const double nper = (double)(((int64_t)K + (fp4 ? 255 : 127)) / (fp4 ? 256 : 128));
-    double per;
-    if (fp4) per = tile == 256 ? 1.96 : 0.92 + 0.24 * (double)(tiles < 512 ? tiles : 512) / 512.0;
-    else {
-        const double fill = (double)(tiles < 256 ? tiles : 256) / 256.0;
-        per = tile == 256 ? 2.28 * (fill > 0.85 ? fill : 0.85) : 1.10 + 0.25 * (double)(tiles < 512 ? tiles : 512) / 512.0;
-    }
-    return (fp4 ? 5.5 : 6.0) + nper * (double)rounds * per + (fp4 ? 0.22 : 0.29) * abits * M * N / 1e6;
+    const double cap = tile == 256 ? 256.0 : 512.0;
+    const double fill = ((double)tiles < cap ? (double)tiles : cap) / cap, P = wbits + abits;
+    const double shared = fill > 0.5 ? fill - 0.5 : 0.0;
+    // fixed, per period: 1, P, fill, P fill, shared; epilogue per abits M N / 1e6
+    static const double c[2][2][7] = {{{6.32, 0.809, 0.0635, 0.0328, 0.0822, 0.567, 0.218},      // int8, 128 x 128
+                                       {12.15, 1.262, 0.1438, 0.1413, 0.0830, 0.0, 0.117}},      // int8, 256 x 256
+                                      {{5.58, 0.694, 0.0760, 0.0752, 0.0619, 0.612, 0.218},      // fp4, 128 x 128
+                                       {10.67, 1.008, 0.1714, 0.0, 0.1319, 0.0, 0.0708}}};       // fp4, 256 x 256
+    const double *q = c[fp4 ? 1 : 0][tile == 256 ? 1 : 0];
+    const double per = q[1] + q[2] * P + fill * (q[3] + q[4] * P) + shared * q[5];
+    return q[0] + nper * (double)rounds * per + q[6] * abits * M * N / 1e6;
 }
 
 }  // namespace
@@ -81,7 +89,7 @@ extern "C" bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_f
         t_bitserial = t_stream < t_tiled ? t_stream : t_tiled;
     }
     const bool fp4 = fp4_usable(wbits, abits, K);
-    const double t_dense = t_planes((double)M, (double)N, (double)K, abits, fp4);
+    const double t_dense = t_planes((double)M, (double)N, (double)K, wbits, abits, fp4);
     if (t_dense < t_bitserial) return fp4 ? BS_ENGINE_DENSE_FP4 : BS_ENGINE_DENSE_I8;
     return BS_ENGINE_BITSERIAL;
 }
