@@ -116,6 +116,43 @@ def test_random_convolution_and_pooling(seed):
         assert_equal(planes_to_numpy(pooled), oracle.pack(oracle.maxpool(Y, pk, ps).reshape(-1, F), obits, U), "bs_maxpool_packed " + what)
 
 
+@pytest.mark.parametrize("seed", range(400, 460))
+def test_random_pooled_convolution(seed):
+    """Random batches, maps, pooling windows and kernels for the convolution that reads its input through a max pooling
+    (including kernels that cover the whole pooled map, the fully connected case), against the oracle's pooling followed
+    by its direct convolution."""
+    rng = np.random.default_rng([20240611, seed])
+    w, wf = draw_operand(rng)
+    a, obits = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+    B = int(rng.choice([1, 1, 2, 3, 4, 5, 9]))
+    pk, ps = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+    H, W = int(rng.integers(pk + 1, 20)), int(rng.integers(pk + 1, 20))
+    PH, PW = (H - pk) // ps + 1, (W - pk) // ps + 1
+    whole = rng.random() < 0.35 and PH == PW
+    p = 0 if whole else int(rng.integers(0, 3))
+    k = PH if whole else int(rng.choice([q for q in (1, 2, 3, 5) if q <= min(PH, PW) + 2 * p]))
+    s = 1 if whole else int(rng.integers(1, 3))
+    C = int(rng.choice([1, 3, 32, 33, 64, 96, 128, 130, 256])) if rng.random() < 0.7 else int(rng.integers(1, 140))
+    F = draw_size(rng, 300)
+    x, filt = draw(rng, (B, H, W, C), a, U), draw(rng, (F, k, k, C), w, wf)
+    convs = [oracle.conv_direct(oracle.maxpool(x[b], pk, ps), filt, s, p) for b in range(B)]
+    lo, hi = min(int(c.min()) for c in convs), max(int(c.max()) for c in convs)
+    T = (1 << obits) - 1
+    thr = np.sort(rng.integers(lo - 2, hi + 3, size=(F, T)), axis=1).astype(np.int32)
+    OH, OW, _ = convs[0].shape
+    want = np.concatenate([oracle.threshold_pack(c.reshape(OH * OW, F).T.copy(), thr, obits) for c in convs], axis=1)
+    what = "seed %d W%d(%d)A%d B=%d %dx%dx%d pool %d/%d F=%d k=%d s=%d p=%d o=%d" % (seed, w, wf, a, B, H, W, C, pk, ps, F, k, s, p, obits)
+    Cp = 32 * ((C + 31) // 32)
+    fpad = np.zeros((F, k, k, Cp), dtype=filt.dtype)
+    fpad[..., :C] = filt
+    if wf == BP:
+        fpad[..., C:] = -1
+    xp = bs.bs_pack_planes(dev(x.reshape(B * H * W, C)), a, bs.BS_UNSIGNED)
+    Fp = bs.bs_pack_planes(dev(fpad.reshape(F, -1)), w, FMT[wf])
+    got = bs.bs_pool_conv_threshold_batch(xp, B, H, W, C, pk, ps, Fp, FMT[wf], k, k, s, p, dev(thr), obits)
+    assert_equal(planes_to_numpy(got), want, "bs_pool_conv_threshold_batch " + what)
+
+
 @pytest.mark.parametrize("seed", range(300, 364))
 def test_random_large_shapes(seed):
     """Shapes beyond the sweep above, so that every tile configuration and both few-column kernels are drawn: mid-sized
