@@ -171,6 +171,7 @@ __device__ __forceinline__ int bcnt_acc(uint32_t x, int acc)
 // (padding, past the depth) loads the first words of the map and is cleared by pool_max's `keep` mask.
 // V: uint32_t (one 32-channel word) or pool_v4 (a 16-byte chunk of four such words, where a chunk never straddles taps).
 typedef unsigned pool_v4 __attribute__((ext_vector_type(4)));
+typedef unsigned pool_v2 __attribute__((ext_vector_type(2)));
 template <int AB, typename V>
 __device__ __forceinline__ void pool_load(const uint32_t *src, int plane_stride, int at, int row_stride, int pix_stride,
                                           int k, bool valid, V (&raw)[9][AB])

@@ -63,6 +63,7 @@ struct PoolFill {
             *reinterpret_cast<V *>(lds_words + (j * NC + n) * p.Kd + q) = best[j];
             int pc;
             if constexpr (VW == 1) pc = __popc(best[j]);
+            else if constexpr (VW == 2) pc = __popc(best[j].x) + __popc(best[j].y);
             else pc = __popc(best[j].x) + __popc(best[j].y) + __popc(best[j].z) + __popc(best[j].w);
             pc *= p.ccol[j];
 #pragma unroll
@@ -117,8 +118,9 @@ __global__ void __launch_bounds__(GEMV_THREADS) bs_gemv_kernel(const GemmParams 
     };
     // POOL: the activation fill forms pooled words instead of copying.  The first items' window loads are requested even
     // before the weights: they return first, and the comparisons run while the weight stream is on its way.
-    // One 32-channel word per item, two items per thread and trip.  (16-byte items, a quarter of the load instructions,
-    // measured slower: fc6 behind pool5 6.2 instead of 5.3 us; the comparisons of four words then sit in one wavefront.)
+    // One 32-channel word per item, two items per thread and trip.  (Wider items, i.e. fewer and wider loads, measured
+    // slower: fc6 behind pool5 takes 5.1 us with one word per item, 5.7 with two, 6.2 with four; the comparisons then
+    // sit in fewer wavefronts.)
     PoolFill<AB, NC, uint32_t> fill[2];
     if constexpr (POOL) {
 #pragma unroll
