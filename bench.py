@@ -50,10 +50,11 @@ def main() -> int:
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line, run the W1A1 size sweep of Sec. 4.1.2 (every dimension "
                          "from 2^6 to 2^12) and print one JSON line per (M, K, N)")
-    ap.add_argument("--only", choices=["gemv", "dense", "planes"], default=None,
+    ap.add_argument("--only", choices=["gemv", "dense", "planes", "chain"], default=None,
                     help="run one kernel family only, with plain launches and a short JSON line: the few-column "
-                         "(batch-1) kernels, the matrix-core kernels on unpacked operands, or the matrix-core "
-                         "kernels on packed planes; meant to be run under rocprofv3")
+                         "(batch-1) kernels, the matrix-core kernels on unpacked operands, the matrix-core "
+                         "kernels on packed planes, or the batch-1 layer chain conv2..fc7 as eight and as six "
+                         "launches; meant to be run under rocprofv3")
     ap.add_argument("--case", default=None, help="with --only: run this one case (see the names in the printed line)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run plain 256 MiB device copies, so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
@@ -316,6 +317,31 @@ def only(which, case, bs, torch, timed):
             for _ in range(30):
                 f()                        # clocks
             run(name, [f], 20)
+    elif which == "chain":
+        # the W1A2 layers of Table 2 at batch 1 on random planes of their shapes: conv2, pool2, conv3, conv4, conv5, pool5,
+        # fc6, fc7 as eight launches, then with the pooling layers folded into conv3 and fc6 (six launches)
+        def conv_args(C, F, k):
+            return planes(1, F, bs.bs_lowered_depth(C, k, k)), thr_for(F, 2)
+        x2 = planes(2, 27 * 27, 96)
+        (F2, t2), (F3, t3), (F4, t4), (F5, t5) = conv_args(96, 256, 5), conv_args(256, 384, 3), conv_args(384, 384, 3), conv_args(384, 256, 3)
+        W6, t6, W7, t7 = planes(1, 4096, 9216), thr_for(4096, 2), planes(1, 4096, 4096), thr_for(4096, 2)
+        y2, p2, y3, y4 = planes(2, 729, 256), planes(2, 169, 256), planes(2, 169, 384), planes(2, 169, 384)
+        y5, p5, y6, y7 = planes(2, 169, 256), planes(2, 36, 256), planes(2, 1, 4096), planes(2, 1, 4096)
+        eight = [lambda: bs.bs_conv_threshold(x2, U, 27, 27, 96, F2, BP, 5, 5, 1, 2, t2, 2, out=y2),
+                 lambda: bs.bs_maxpool_packed(y2, 27, 27, 256, 3, 2, out=p2),
+                 lambda: bs.bs_conv_threshold(p2, U, 13, 13, 256, F3, BP, 3, 3, 1, 1, t3, 2, out=y3),
+                 lambda: bs.bs_conv_threshold(y3, U, 13, 13, 384, F4, BP, 3, 3, 1, 1, t4, 2, out=y4),
+                 lambda: bs.bs_conv_threshold(y4, U, 13, 13, 384, F5, BP, 3, 3, 1, 1, t5, 2, out=y5),
+                 lambda: bs.bs_maxpool_packed(y5, 13, 13, 256, 3, 2, out=p5),
+                 lambda: bs.bs_gemm_threshold(W6, BP, p5.reshape(2, 1, -1), U, 9216, t6, 2, out=y6),
+                 lambda: bs.bs_gemm_threshold(W7, BP, y6, U, 4096, t7, 2, out=y7)]
+        six = [eight[0],
+               lambda: bs.bs_pool_conv_threshold_batch(y2, 1, 27, 27, 256, 3, 2, F3, BP, 3, 3, 1, 1, t3, 2, out=y3),
+               eight[3], eight[4],
+               lambda: bs.bs_pool_conv_threshold_batch(y5, 1, 13, 13, 256, 3, 2, W6, BP, 6, 6, 1, 0, t6, 2, out=y6),
+               eight[7]]
+        run("chain_eight_launches", eight, 200)
+        run("chain_six_launches", six, 200)
     else:
         for (name, e, w, a, M, N, K, ob) in [("planes_fp4_W2A2_4096", bs.BS_ENGINE_DENSE_FP4, 2, 2, 4096, 4096, 4096, 0),
                                              ("planes_fp4_W1A2_4096_fused2", bs.BS_ENGINE_DENSE_FP4, 1, 2, 4096, 4096, 4096, 2),

@@ -12,7 +12,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbsgemm.so")
 
-SOURCES = ["bs_pack.hip", "bs_gemm.hip", "bs_gemm_w1.hip", "bs_gemm_w2.hip", "bs_gemm_w3.hip", "bs_gemm_w4.hip", "bs_gemv.hip", "bs_planes_mfma.hip",
+SOURCES = ["bs_pack.hip", "bs_gemm.hip", "bs_gemm_w1.hip", "bs_gemm_w2.hip", "bs_gemm_w3.hip", "bs_gemm_w4.hip", "bs_gemv.hip", "bs_gemv_w1.hip", "bs_gemv_w2.hip", "bs_gemv_w3.hip", "bs_gemv_w4.hip", "bs_planes_mfma.hip",
            "bs_threshold.hip", "bs_im2col.hip", "bs_pool.hip", "bs_dense.hip", "bs_probe.hip", "bs_streamline.cpp", "bs_misc.cpp"]
 
 # -packed-fp32-ops is switched off on purpose: this code has no float math, and the

@@ -1,0 +1,6 @@
+// Instantiates the few-column kernels for 4 weight plane(s).
+#include "bs_gemv_kernel.h"
+
+namespace bs {
+template bs_status launch_gemv_wb<4>(const GemmParams &, int, bool, bool, hipStream_t);
+}
