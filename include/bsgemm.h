@@ -339,17 +339,24 @@ bs_status bs_streamline_thresholds(const double *t, int T, const double *a, cons
  *   BS_ENGINE_DENSE_I8   the matrix-core kernel on int8 codes (everything else below K = 2^30),
  * whichever is fastest under a time model fitted to measurements on MI355X (microseconds, p = wbits * abits,
  * k = K / 1024, thresholding epilogue included):
- *   bit-serial  3.73 + 0.198 k p + 2MNK p / 1.23e9      (N > 16)
- *               min(3.88 + G (0.69 + 0.2 p + 0.031 p k), 3.64 + R p (0.253 k + 0.21))   (5 <= N <= 16), with
+ *   bit-serial  N > 16, by the tile the launch takes (t32, t64 = tiles of 32 x 32, 64 x 64 the output needs;
+ *               g = 2MNK p / 1e9, e = abits MN / 1e6):
+ *                 t32 <= 200   (32 x 8 tiles)             3.17 + 0.270 k p + 6.10 e
+ *                 t32 <= 384   (32 x 16 tiles)            1.98 + 0.492 k p + 5.06 e
+ *                 t64 <  512   (32 x 32, depth split)     0.38 + 0.839 g + 3.47 e
+ *                 else         (64 x 64)                  1.12 + 0.612 k p + 0.685 g + 0.825 e
+ *               5 <= N <= 16: min(3.88 + G (0.69 + 0.2 p + 0.031 p k), 3.64 + R p (0.253 k + 0.21)), with
  *               G = ceil(N / 4) M / 4096 (streaming kernel, groups of four columns), R = 1 + max(0, B - 256) / 900,
  *               B = ceil(M / 32) ceil(N / 8) (tiled kernel, 32 x 8 tiles); bs_gemm itself picks between these two
  *   dense       F + ceil(K / d) r c + E abits MN / 1e6, with d = 256 depth indices per period of the kernel's pipeline
  *               as fp4 codes, 128 as int8 codes; r = rounds of tiles over the chip (bs_planes_tile); and the time of a
  *               period c = c1 + c2 P + f (c3 + c4 P) + c5 max(0, f - 1/2), P = wbits + abits planes to request and merge,
- *               f = the part of the chip's tile slots that is filled (two small tiles share a compute unit beyond 1/2):
+ *               f = the part of the chip's tile slots that is filled (two 128 x 128 tiles share a compute unit beyond 1/2):
  *                                    F      c1     c2      c3      c4      c5     E
+ *                 int8,  64 x 64     5.37   0.612  0.0566  0       0       0      0.0841
  *                 int8, 128 x 128    6.32   0.809  0.0635  0.0328  0.0822  0.567  0.218
  *                 int8, 256 x 256   12.15   1.262  0.1438  0.1413  0.0830  0      0.117
+ *                 fp4,   64 x 64     4.93   0.545  0.0485  0       0       0      0
  *                 fp4,  128 x 128    5.58   0.694  0.0760  0.0752  0.0619  0.612  0.218
  *                 fp4,  256 x 256   10.67   1.008  0.1714  0       0.1319  0      0.0708
  * N <= 4 is always bit-serial (weights are read once, wbits/8 byte per weight, and nothing is expanded).
@@ -357,8 +364,9 @@ bs_status bs_streamline_thresholds(const double *t, int T, const double *a, cons
  */
 bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_format afmt, int64_t M, int64_t N, int64_t K);
 
-/* Tile edge (256 or 128) the matrix-core kernel on packed planes takes for an M x N output, the rounds of such tiles
- * over the chip and their number (either pointer may be NULL).  Host-only; part of the time model above. */
+/* Tile edge (256, 128 or 64) the matrix-core kernel on packed planes takes for an M x N output, the rounds of such tiles
+ * over the chip (256 slots for the largest tile, 512 for the others) and their number (either pointer may be NULL).
+ * Host-only; part of the time model above. */
 int bs_planes_tile(int64_t M, int64_t N, long long *rounds, long long *tiles);
 
 /*

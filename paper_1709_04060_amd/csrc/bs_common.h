@@ -10,6 +10,12 @@ namespace bs {
 constexpr int kWave = 64;        // CDNA4 wavefront width
 constexpr int kMaxBits = 4;      // the few-bit range of the paper (w, a <= 4)
 
+// Output grids at which the bit-serial launch changes its tile (bs_gemm_kernel.h, launch_planes); the time model of the
+// engine choice (bs_misc.cpp) follows the same steps.
+constexpr long long kNarrowMaxTiles32 = 200;  // measured, W1A2..W4A4 at depth 2048: 32 x 8 tiles win up to 184 tiles of 32 x 32, tie at 256, lose from 512
+constexpr long long kHalfWidthMaxTiles32 = 384;  // 32 x 16 tiles between the tiny grids and this many 32 x 32 tiles
+constexpr long long kWideMinTiles64 = 512;  // 64 x 64 tiles from this many on, 32 x 32 tiles with the depth split below
+
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 // A kernel's parameter block arrives through scalar loads, and the compiler requests each

@@ -132,10 +132,12 @@ __device__ __forceinline__ void dense_threshold_planes(const DenseParams &p, typ
                 for (int pl = 0; pl < OB; ++pl) word[b][pl] |= ((y >> pl) & 1u) << rr;
             }
         }
-        // Row bands cover a multiple of 128 rows, i.e. at least the Yd words of a column, so
-        // every word (padding included) is written by some band; words beyond Yd (a 256-row
-        // tile over a shorter column) are dropped.
+        // Tiles of a multiple of 128 rows cover at least the Yd words of a column (Yd is a multiple of four), so
+        // every word, padding included, is written by some band; words beyond Yd (a 256-row tile over a shorter
+        // column) are dropped.  A tile of 64 rows may end two words short of Yd: the last band of the last row
+        // tile clears them.
         const int wi = (m0 + rbase) / 32;
+        const bool clears_rest = (BM % 128 != 0) && m0 + BM >= p.M && wm == WGM - 1 && a == WTM - 1;
 #pragma unroll
         for (int b = 0; b < WTN; ++b) {
             const int n = n0 + (wn * WTN + b) * 32 + li;
@@ -145,6 +147,11 @@ __device__ __forceinline__ void dense_threshold_planes(const DenseParams &p, typ
             if (lg == 0 && n < p.N && wi < p.Yd) {
 #pragma unroll
                 for (int pl = 0; pl < OB; ++pl) p.Y[((long long)pl * p.N + n) * p.Yd + wi] = word[b][pl];
+                if (clears_rest) {
+                    for (int z = wi + 1; z < p.Yd; ++z)
+#pragma unroll
+                        for (int pl = 0; pl < OB; ++pl) p.Y[((long long)pl * p.N + n) * p.Yd + z] = 0;
+                }
             }
         }
     }

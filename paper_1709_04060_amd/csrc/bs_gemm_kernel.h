@@ -37,8 +37,6 @@
 namespace bs {
 
 constexpr int kStageDwords = 32;  // dwords of depth per packed row and stage
-constexpr long long kNarrowMaxTiles32 = 200;  // measured, W1A2..W4A4 at depth 2048: 32 x 8 tiles win up to 184 tiles of 32 x 32, tie at 256, lose from 512
-constexpr long long kHalfWidthMaxTiles32 = 384;  // 32 x 16 tiles between the tiny grids and this many 32 x 32 tiles
 constexpr long long kIdleMinBlocks = 257;  // more workgroups than compute units (measured: 10.9 vs 12.5 us at 320, 10.7 vs 9.6 us at 256)
 
 // Division of a 32-bit index by a launch constant as a multiply-high and two shifts (the set-up of
@@ -117,7 +115,7 @@ constexpr long long kStreamWeightBytes = 64ll << 20;
 
 constexpr int kConvMaxLut = 2048;  // lowered dwords the implicit-lowering kernels can index (65536 depth bits)
 
-// GEMV path (bs_gemv.hip): a workgroup handles at most kGemvMaxCols columns, activation planes in LDS; up to
+// GEMV path (bs_gemv_kernel.h, bs_gemv.hip): a workgroup handles at most kGemvMaxCols columns, activation planes in LDS; up to
 // kGemvMaxGroupedCols columns run as groups of four side by side (each group streams the weights again, from
 // L2 as the groups run together): 32 x 32 tiles would leave 3/4 or more of their columns empty there
 // (W4A4 8192 x 8192: 89 us tiled for 5..32 columns, 36 / 53 / 67 us grouped for 8 / 12 / 16).  Between 5 and
@@ -902,7 +900,7 @@ bs_status launch_planes(const GemmParams &g, bool fuse, bool corr, bool conv, bo
     // (also for every larger grid with a pooled fetch, whose kernels exist for the narrow tiles only: a thread of
     // a wider tile would have to hold the window taps of eight and more words per stage)
     if (tiles32 <= kHalfWidthMaxTiles32 || (conv && g.pK > 0)) return launch_cfg<WB, AB, 4, 2, 1, 1, 4, KT_DEEP>(g, fuse, corr, conv, xr, st);
-    if (tiles64 < 512) return launch_cfg<WB, AB, 4, 4, 1, 1, 4, KT_DEEP>(g, fuse, corr, conv, xr, st);
+    if (tiles64 < kWideMinTiles64) return launch_cfg<WB, AB, 4, 4, 1, 1, 4, KT_DEEP>(g, fuse, corr, conv, xr, st);
     return launch_cfg<WB, AB, 4, 4, 2, 2, 1, kStageDwords>(g, fuse, corr, conv, xr, st);
 }
 

@@ -19,8 +19,8 @@ extern "C" int bs_version(void) { return 100; }
 // Per-layer engine choice (Sec. 4.1.1 / 4.2): the fastest of the engines under time models fitted to measurements on
 // MI355X over M in {256, 1024, 4096}, N in {17 .. 4096}, K in {512 .. 8192} and W1A1, W1A2, W2A2, W3A3, W4A4, all from
 // packed planes with the fused thresholding epilogue (375 shapes; non-negative least squares on the relative error).
-// Over those shapes the choice costs 0.3 % on average and 27 % at worst against always taking the fastest engine (three
-// shapes above 15 %), where always bit-serial costs 80 % on average (17 x at worst) and always matrix cores 92 % (5.9 x).
+// Over those shapes the choice costs 0.4 % on average and 11 % at worst against always taking the fastest engine and
+// tile, where always bit-serial costs 100 % on average (20 x at worst) and always matrix cores 77 % (4.7 x).
 // Microseconds.
 namespace {
 
@@ -31,11 +31,25 @@ bool fp4_usable(int wbits, int abits, int64_t K)
     return wbits <= 2 && abits <= 2 && K * ((int64_t(1) << wbits) - 1) * ((int64_t(1) << abits) - 1) < (int64_t(1) << 24);
 }
 
-// The matrix-core kernel on packed planes: a 256 x 256 tile per compute unit or two 128 x 128 tiles (bs_planes_tile
-// makes the same choice for the launch).  Time = fixed + periods x rounds x (time of a period) + epilogue, where a
-// period (128 depth indices as int8 codes, 256 as fp4 codes) costs more with the planes P = wbits + abits the loader
-// has to request and merge, with the share `fill` of the chip's tile slots in use (the requests meet in L2), and, for
-// the small tile, once two workgroups share a compute unit (fill > 1/2).
+// The tiled AND-popcount kernel (more than 16 columns), one model per tile the launch takes (the same steps as
+// launch_planes): fixed + depth stages + stages x rounds beyond the resident workgroups + products + epilogue.
+double t_bitserial_tiled(double M, double N, double K, int wbits, int abits)
+{
+    const long long m = (long long)M, n = (long long)N;
+    const long long tiles32 = ((m + 31) / 32) * ((n + 31) / 32), tiles64 = ((m + 63) / 64) * ((n + 63) / 64);
+    const double p = (double)wbits * abits, kp = K / 1024.0 * p;
+    const double work = 2.0 * M * N * K * p / 1e9, epi = M * N * abits / 1e6;
+    if (tiles32 <= bs::kNarrowMaxTiles32) return 3.17 + 0.270 * kp + 6.10 * epi;    // 32 x 8 tiles
+    if (tiles32 <= bs::kHalfWidthMaxTiles32) return 1.98 + 0.492 * kp + 5.06 * epi;  // 32 x 16
+    if (tiles64 < bs::kWideMinTiles64) return 0.38 + 0.839 * work + 3.47 * epi;      // 32 x 32, depth split
+    return 1.12 + 0.612 * kp + 0.685 * work + 0.825 * epi;                           // 64 x 64
+}
+
+// The matrix-core kernel on packed planes: 256 x 256, 128 x 128 or 64 x 64 tiles (bs_planes_tile makes the same
+// choice for the launch).  Time = fixed + periods x rounds x (time of a period) + epilogue, where a period (128
+// depth indices as int8 codes, 256 as fp4 codes) costs more with the planes P = wbits + abits the loader has to
+// request and merge, with the share `fill` of the chip's tile slots in use (the requests meet in L2), and, for the
+// 128 x 128 tile, once two workgroups share a compute unit (fill > 1/2).
 double t_planes(double M, double N, double K, int wbits, int abits, bool fp4)
 {
     long long rounds, tiles;
@@ -44,24 +58,35 @@ double t_planes(double M, double N, double K, int wbits, int abits, bool fp4)
     const double cap = tile == 256 ? 256.0 : 512.0;
     const double fill = ((double)tiles < cap ? (double)tiles : cap) / cap, P = wbits + abits;
     const double shared = fill > 0.5 ? fill - 0.5 : 0.0;
-    // fixed, per period: 1, P, fill, P fill, shared; epilogue per abits M N / 1e6
-    static const double c[2][2][7] = {{{6.32, 0.809, 0.0635, 0.0328, 0.0822, 0.567, 0.218},      // int8, 128 x 128
-                                       {12.15, 1.262, 0.1438, 0.1413, 0.0830, 0.0, 0.117}},      // int8, 256 x 256
-                                      {{5.58, 0.694, 0.0760, 0.0752, 0.0619, 0.612, 0.218},      // fp4, 128 x 128
-                                       {10.67, 1.008, 0.1714, 0.0, 0.1319, 0.0, 0.0708}}};       // fp4, 256 x 256
-    const double *q = c[fp4 ? 1 : 0][tile == 256 ? 1 : 0];
+    // fixed; per period: 1, P, fill, P fill, shared; epilogue per abits M N / 1e6
+    static const double c[2][3][7] = {{{5.37, 0.612, 0.0566, 0.0, 0.0, 0.0, 0.0841},             // int8, 64 x 64
+                                       {6.32, 0.809, 0.0635, 0.0328, 0.0822, 0.567, 0.218},       // int8, 128 x 128
+                                       {12.15, 1.262, 0.1438, 0.1413, 0.0830, 0.0, 0.117}},       // int8, 256 x 256
+                                      {{4.93, 0.545, 0.0485, 0.0, 0.0, 0.0, 0.0},                 // fp4, 64 x 64
+                                       {5.58, 0.694, 0.0760, 0.0752, 0.0619, 0.612, 0.218},       // fp4, 128 x 128
+                                       {10.67, 1.008, 0.1714, 0.0, 0.1319, 0.0, 0.0708}}};        // fp4, 256 x 256
+    const double *q = c[fp4 ? 1 : 0][tile == 256 ? 2 : (tile == 128 ? 1 : 0)];
     const double per = q[1] + q[2] * P + fill * (q[3] + q[4] * P) + shared * q[5];
     return q[0] + nper * (double)rounds * per + q[6] * abits * M * N / 1e6;
 }
 
 }  // namespace
 
-// Tile of the matrix-core kernel on packed planes for an M x N output: 256 (one workgroup per compute unit) or 128 (two).
-// A round of 128 x 128 tiles over the chip (512 of them) takes 0.67 of a round of 256 x 256 tiles (256 of them) and
-// covers half as much output; the rule picked the faster tile on every shape of the sweep above.
+// Tile of the matrix-core kernel on packed planes for an M x N output.  Up to 128 tiles of 128 x 128 (a quarter of the
+// chip's slots for them): 64 x 64 tiles on two wavefronts, four times as many workgroups, each expanding half the rows
+// (15 to 38 % faster there on every measured shape).  Beyond: 256 x 256 (one workgroup per compute unit) or 128 x 128
+// (two); a round of 128 x 128 tiles over the chip (512 of them) takes 0.67 of a round of 256 x 256 tiles (256 of them)
+// and covers half as much output.  On the shapes of the sweep above the rule is within 0.2 % of the best tile on
+// average, 11 % at worst.
 extern "C" int bs_planes_tile(int64_t M, int64_t N, long long *rounds, long long *tiles)
 {
     const long long t256 = ((M + 255) / 256) * ((N + 255) / 256), t128 = ((M + 127) / 128) * ((N + 127) / 128);
+    if (t128 <= 128) {
+        const long long t64 = ((M + 63) / 64) * ((N + 63) / 64);
+        if (rounds) *rounds = (t64 + 511) / 512;
+        if (tiles) *tiles = t64;
+        return 64;
+    }
     const long long r256 = (t256 + 255) / 256, r128 = (t128 + 511) / 512;
     const bool big = r256 * 100 <= r128 * 67;
     if (rounds) *rounds = big ? r256 : r128;
@@ -76,10 +101,9 @@ extern "C" bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_f
     if (K >= (int64_t(1) << 30)) return BS_ENGINE_BITSERIAL;  // beyond the dense engines' depth range
     if (N <= 4) return BS_ENGINE_BITSERIAL;  // weights streamed once: wbits/8 byte per weight, nothing to expand
     const double pairs = (double)wbits * abits, kk = (double)K / 1024.0;
-    const double mnk2 = 2.0 * (double)M * (double)N * (double)K;
     // 5..16 columns: the bit-serial call takes the faster of the streaming kernel in groups of four columns and
     // the tiled kernel with 32 x 8 tiles (the same two models decide inside bs_gemm)
-    double t_bitserial = 3.73 + 0.198 * kk * pairs + mnk2 * pairs / 1.23e9;
+    double t_bitserial = t_bitserial_tiled((double)M, (double)N, (double)K, wbits, abits);
     if (N <= 16) {
         const double groups = (double)((N + 3) / 4) * (double)M / 4096.0;
         const double t_stream = 3.88 + groups * (0.69 + 0.2 * pairs + 0.031 * pairs * kk);

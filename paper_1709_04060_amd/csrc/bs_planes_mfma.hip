@@ -412,10 +412,12 @@ bs_status launch_tile(PlanesParams &p, bool fuse, bool conv, hipStream_t st)
 template <bool FP4>
 bs_status launch_kind(PlanesParams &p, bool fuse, bool conv, hipStream_t st)
 {
-    // 256 x 256 tiles on eight wavefronts (one per compute unit) or 128 x 128 on four (two per compute unit).  A
-    // 128 x 128 tile expands half the rows of a 256 x 256 one for a quarter of its products: the small tile is taken
-    // when it needs fewer rounds over the chip (bs_planes_tile, which the engine choice's time model shares).
-    if (bs_planes_tile(p.d.M, p.d.N, nullptr, nullptr) == 256) return launch_tile<FP4, 4, 2, 2, 4>(p, fuse, conv, st);
+    // 256 x 256 tiles on eight wavefronts (one per compute unit), 128 x 128 on four (two per compute unit) or, for
+    // small outputs, 64 x 64 on two (each wavefront 32 x 64).  A smaller tile expands more rows per product, but puts
+    // more workgroups on the chip: bs_planes_tile holds the rule, which the engine choice's time model shares.
+    const int tile = bs_planes_tile(p.d.M, p.d.N, nullptr, nullptr);
+    if (tile == 256) return launch_tile<FP4, 4, 2, 2, 4>(p, fuse, conv, st);
+    if (tile == 64) return launch_tile<FP4, 1, 2, 2, 1>(p, fuse, conv, st);
     return launch_tile<FP4, 2, 2, 2, 2>(p, fuse, conv, st);
 }
 

@@ -22,9 +22,9 @@ def load():
             continue
         f = line.split()
         w, a, M, N, K = (int(x) for x in f[:5])
-        t = {"bitserial": float(f[5]), "i8_256": float(f[6]), "i8_128": float(f[7])}
-        if f[8] != "-":
-            t["fp4_256"], t["fp4_128"] = float(f[8]), float(f[9])
+        t = {"bitserial": float(f[5]), "i8_256": float(f[6]), "i8_128": float(f[7]), "i8_64": float(f[8])}
+        if f[9] != "-":
+            t["fp4_256"], t["fp4_128"], t["fp4_64"] = float(f[9]), float(f[10]), float(f[11])
         rows.append((w, a, M, N, K, t))
     return rows
 
@@ -48,11 +48,10 @@ def test_fixture_covers_the_fitted_range():
 
 def test_choice_is_close_to_the_fastest_engine_on_the_recorded_shapes():
     regret = np.array([chosen_time(*r) / min(r[5].values()) - 1.0 for r in load()])
-    # as fitted: 0.3 % on average, 27 % at worst, three shapes above 15 %; the bounds leave room for a refit, not for a
-    # wrong boundary
+    # as fitted: 0.4 % on average, 11 % at worst; the bounds leave room for a refit, not for a wrong boundary
     assert regret.mean() < 0.01, regret.mean()
-    assert regret.max() < 0.35, regret.max()
-    assert (regret > 0.15).sum() <= 6, (regret > 0.15).sum()
+    assert regret.max() < 0.20, regret.max()
+    assert (regret > 0.10).sum() <= 8, (regret > 0.10).sum()
 
 
 def test_a_single_engine_everywhere_is_far_worse():
@@ -61,24 +60,25 @@ def test_a_single_engine_everywhere_is_far_worse():
     always_bs = np.array([r[5]["bitserial"] / min(r[5].values()) - 1.0 for r in rows])
     always_mc = np.array([min(v for k, v in r[5].items() if k != "bitserial") / min(r[5].values()) - 1.0 for r in rows])
     assert always_bs.mean() > 0.5 and always_bs.max() > 10
-    assert always_mc.mean() > 0.5 and always_mc.max() > 4
+    assert always_mc.mean() > 0.5 and always_mc.max() > 3
 
 
 def test_tile_rule_picks_the_faster_tile():
-    """bs_planes_tile against the measured pair of tiles, per engine kind: within 10 % of the faster tile on every
-    recorded shape but a handful, never worse than 35 %."""
+    """bs_planes_tile against the three measured tiles, per engine kind: within 10 % of the fastest tile on every
+    recorded shape but a handful, never worse than 15 %."""
     loss = []
     for w, a, M, N, K, t in load():
         tile = bs.bs_planes_tile(M, N)[0]
         for kind in ("i8", "fp4"):
             if kind + "_256" in t:
-                loss.append(t["%s_%d" % (kind, tile)] / min(t[kind + "_256"], t[kind + "_128"]) - 1.0)
+                loss.append(t["%s_%d" % (kind, tile)] / min(t[kind + "_256"], t[kind + "_128"], t[kind + "_64"]) - 1.0)
     loss = np.array(loss)
-    assert loss.max() < 0.35, loss.max()
-    assert (loss > 0.10).mean() < 0.05, (loss > 0.10).mean()
+    assert loss.max() < 0.15, loss.max()
+    assert (loss > 0.10).mean() < 0.02, (loss > 0.10).mean()
 
 
-@pytest.mark.parametrize("M,N,want", [(4096, 4096, 256), (256, 256, 128), (1024, 1024, 128), (384, 10816, 128), (8192, 8192, 256)])
+@pytest.mark.parametrize("M,N,want", [(4096, 4096, 256), (256, 256, 64), (1024, 1024, 64), (1024, 2048, 64), (1024, 2176, 128),
+                                      (384, 10816, 128), (8192, 8192, 256)])
 def test_tile_rule_examples(M, N, want):
     tile, rounds, tiles = bs.bs_planes_tile(M, N)
     assert tile == want
