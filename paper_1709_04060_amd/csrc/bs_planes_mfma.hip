@@ -119,8 +119,9 @@ struct PlanesResult {
 // threads as the stacked tile has rows (one row per thread).
 // CONV: the activation operand is not a packed matrix but packed HWC image planes; the rows of the A part of the tile
 // (columns of the lowered matrix of Sec. 3.2) are gathered from the image, zero words for taps outside of it, so
-// the lowered matrix never exists in memory.
-template <bool FP4, int WTM, int WTN, int WGM, int WGN, bool FUSE, bool CONV = false>
+// the lowered matrix never exists in memory.  VEC: a pixel's channel run is a whole number of 16-byte chunks, so that
+// four consecutive lowered dwords lie inside one tap of one pixel and are gathered with one load.
+template <bool FP4, int WTM, int WTN, int WGM, int WGN, bool FUSE, bool CONV = false, bool VEC = false>
 __global__ void __launch_bounds__(64 * WGM * WGN)
 planes_mfma_kernel(const PlanesParams p)
 {
@@ -193,38 +194,44 @@ planes_mfma_kernel(const PlanesParams p)
     // stages (int8 kind), two where they hold one (fp4 kind).  Every lane of a request reads another row, i.e. another
     // cache line, and those line look-ups are what bounds the loader: the fewer requests the better.
     uint32_t R[NB][PW];
-    // four lowered dwords starting at dword q0 (a multiple of 4) of this row's column, gathered from image plane `img`
-    auto gather4 = [&](const uint32_t *img, int q0) -> uint4 {
+    // CONV, A rows: where the four lowered dwords from dword q0 (a multiple of 4) of this row's column lie in an image
+    // plane, and which of them exist (taps outside the image and words past the lowered depth read as zero).  The loads
+    // themselves are unconditional, from offset 0 where there is nothing to read, and the words are cleared when they
+    // are expanded: a load inside a branch would cut the period's instruction stream into pieces and make every wait a
+    // wait for all loads.
+    int okbits = -1;                             // bit t: word t of R[.] holds data
+    auto locate4 = [&](int q0, int (&off)[4]) -> int {
         const int4 l4 = *reinterpret_cast<const int4 *>(&lut[q0]);
         const int l[4] = {l4.x, l4.y, l4.z, l4.w};
-        if ((p.cCd & 3) == 0 && (p.cPix & 3) == 0) {
-            // the four dwords lie inside one tap of one pixel: one test, one 16-byte load
-            const int ih = pix_h + (l[0] >> 24), iw = pix_w + ((l[0] >> 16) & 0xFF);
-            if (l[0] >= 0 && ih >= 0 && ih < p.cH && iw >= 0 && iw < p.cW)
-                return *reinterpret_cast<const uint4 *>(img + (size_t)(ih * p.cW + iw) * p.cPix + (l[0] & 0xFFFF));
-            return make_uint4(0, 0, 0, 0);
-        }
-        uint32_t e[4];
+        int bits = 0;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            e[t] = 0;
+        for (int t = 0; t < (VEC ? 1 : 4); ++t) {
             const int ih = pix_h + (l[t] >> 24), iw = pix_w + ((l[t] >> 16) & 0xFF);
-            if (l[t] >= 0 && ih >= 0 && ih < p.cH && iw >= 0 && iw < p.cW) e[t] = img[(size_t)(ih * p.cW + iw) * p.cPix + (l[t] & 0xFFFF)];
+            const bool ok = l[t] >= 0 && ih >= 0 && ih < p.cH && iw >= 0 && iw < p.cW;
+            off[t] = ok ? (ih * p.cW + iw) * p.cPix + (l[t] & 0xFFFF) : 0;
+            bits |= ok ? (1 << t) : 0;
         }
-        return make_uint4(e[0], e[1], e[2], e[3]);
+        if (VEC) bits = (bits & 1) ? 15 : 0;
+        return bits;
+    };
+    auto gather4 = [&](const uint32_t *img, const int (&off)[4]) -> uint4 {
+        if constexpr (VEC) return *reinterpret_cast<const uint4 *>(img + (unsigned)off[0]);
+        return make_uint4(img[(unsigned)off[0]], img[(unsigned)off[1]], img[(unsigned)off[2]], img[(unsigned)off[3]]);
     };
     auto fetch = [&](int period) {
         const int s = period < p.nper ? period : p.nper - 1;  // past the depth: any valid address; the words are zeroed on use
         // the second stage of the last period may not exist (the row ends with the first): stay inside the row
         const int o2 = s * PW + 4 < p.Kd ? s * PW + 4 : p.Kd - 4;
         if (CONV && !isW) {                      // uniform for the wavefront
+            okbits = 0;
 #pragma unroll
-            for (int q = 0; q < NB; ++q) {
-                const uint4 v = gather4(pl_ptr[q], s * PW);
-                R[q][0] = v.x; R[q][1] = v.y; R[q][2] = v.z; R[q][3] = v.w;
-                if constexpr (PW == 8) {
-                    const uint4 u = gather4(pl_ptr[q], o2);
-                    R[q][4] = u.x; R[q][5] = u.y; R[q][6] = u.z; R[q][7] = u.w;
+            for (int g = 0; g < PW / 4; ++g) {   // one gather per 16 bytes of the period's plane words; few offsets live at a time
+                int off[4];
+                okbits |= locate4(g == 0 ? s * PW : o2, off) << (4 * g);
+#pragma unroll
+                for (int q = 0; q < NB; ++q) {
+                    const uint4 v = gather4(pl_ptr[q], off);
+                    R[q][4 * g] = v.x; R[q][4 * g + 1] = v.y; R[q][4 * g + 2] = v.z; R[q][4 * g + 3] = v.w;
                 }
             }
             return;
@@ -257,7 +264,8 @@ planes_mfma_kernel(const PlanesParams p)
             uint32_t x[NB];
 #pragma unroll
             for (int q = 0; q < NB; ++q) {
-                const uint32_t r = R[q][h * DW + d];
+                uint32_t r = R[q][h * DW + d];
+                if constexpr (CONV) r &= (uint32_t)__builtin_amdgcn_sbfe(okbits, h * DW + d, 1);  // all ones or zero
                 x[q] = TAIL ? (((r & plain[q]) | (~r & flipped[q] & vm)) & live) : ((r & plain[q]) | (~r & flipped[q]));
                 popc[q] += __builtin_popcount(x[q]);
             }
@@ -403,7 +411,8 @@ bs_status launch_tile(PlanesParams &p, bool fuse, bool conv, hipStream_t st)
     if (blocks >= (1LL << 31)) return BS_ERR_UNSUPPORTED;
     if (conv) {  // implicit lowering exists with the thresholding epilogue only
         if (!fuse) return BS_ERR_UNSUPPORTED;
-        planes_mfma_kernel<FP4, WTM, WTN, WGM, WGN, true, true><<<dim3((unsigned)blocks), NT, 0, st>>>(p);
+        if (p.cCd % 4 == 0 && p.cPix % 4 == 0) planes_mfma_kernel<FP4, WTM, WTN, WGM, WGN, true, true, true><<<dim3((unsigned)blocks), NT, 0, st>>>(p);
+        else planes_mfma_kernel<FP4, WTM, WTN, WGM, WGN, true, true, false><<<dim3((unsigned)blocks), NT, 0, st>>>(p);
     } else if (fuse) planes_mfma_kernel<FP4, WTM, WTN, WGM, WGN, true><<<dim3((unsigned)blocks), NT, 0, st>>>(p);
     else planes_mfma_kernel<FP4, WTM, WTN, WGM, WGN, false><<<dim3((unsigned)blocks), NT, 0, st>>>(p);
     return bs::after_launch();
