@@ -92,8 +92,8 @@ bs_status bs_pack_planes(const void *src, bs_dtype dtype, int64_t rows, int64_t 
  *   Ap  device, planes [abits][N][S]
  *   C   device int32 [M][ldc], ldc >= N, OVERWRITTEN (not accumulated into)
  * Errors: INVALID_ARG; UNSUPPORTED (bits > 4); ALIGNMENT (planes 16 B, C 4 B);
- * OVERFLOW_RISK if K * max|w| * max|a| >= 2^31 (max|v| of a format: unsigned 2^bits - 1, two's
- * complement 2^(bits-1), bipolar 1: no result can then leave the int32 range; partial sums are
+ * OVERFLOW_RISK if K * max|w| * max|a| >= 2^31 - 1 (max|v| of a format: unsigned 2^bits - 1, two's
+ * complement 2^(bits-1), bipolar 1: otherwise every result lies inside the int32 range and below INT_MAX, the threshold given to rows past M; partial sums are
  * taken modulo 2^32, which does not change an in-range result) or an operand exceeds 2^31 32-bit
  * words; LAUNCH.
  *

@@ -44,7 +44,8 @@ bool result_may_overflow(int64_t K, int wbits, bs_format wfmt, int abits, bs_for
     const int64_t mw = subset_of_pairs ? (int64_t(1) << wbits) - 1 : bs::max_abs(wbits, wfmt);
     const int64_t ma = subset_of_pairs ? (int64_t(1) << abits) - 1 : bs::max_abs(abits, afmt);
     const int64_t lim = int64_t(1) << 31;
-    return K >= lim || K * mw * ma >= lim;
+    // (lim - 1: no result reaches INT_MAX, the threshold that rows past M are given)
+    return K >= lim || K * mw * ma >= lim - 1;
 }
 
 bs_status gemm_common(bs_engine engine, const uint64_t *Wp, int wbits, bs_format wfmt, const uint64_t *Ap, int abits,

@@ -464,12 +464,17 @@ bs_gemm_kernel(const GemmParams p)
             const int c = (tid + s * NT) % KCH;
             if ((s * NT < WROWS * KCH) ? !DO_W : (!DO_A || POOL)) continue;  // resolved at compile time
             uint4 v = make_uint4(0, 0, 0, 0);
+            // Rows of a packed matrix are loaded without a branch: a row past the operand or a chunk past the depth reads
+            // the operand's first words instead.  Such rows only feed outputs that are never stored, such chunks are
+            // never multiplied (the last, partial stage stops at the depth) and are left out of the popcounts below.
+            const bool in_range = goff[s] >= 0 && k0 + c * 4 < p.Kd;
             if (s * NT < WROWS * KCH) {
-                if (goff[s] >= 0 && k0 + c * 4 < p.Kd)
-                    v = *reinterpret_cast<const uint4 *>(p.W + (size_t)(unsigned)goff[s] + k0);
+                // (the kernels that gather lowered columns keep the branch for the weights as well: their small grids
+                // measured 0.2 us slower per layer without it, the large plain products 1 to 2 % faster)
+                if constexpr (!CONV) v = *reinterpret_cast<const uint4 *>(p.W + (size_t)(unsigned)(in_range ? goff[s] + k0 : 0));
+                else if (in_range) v = *reinterpret_cast<const uint4 *>(p.W + (size_t)(unsigned)goff[s] + k0);
             } else if constexpr (!CONV) {
-                if (goff[s] >= 0 && k0 + c * 4 < p.Kd)
-                    v = *reinterpret_cast<const uint4 *>(p.A + (size_t)(unsigned)goff[s] + k0);
+                v = *reinterpret_cast<const uint4 *>(p.A + (size_t)(unsigned)(in_range ? goff[s] + k0 : 0));
             } else {
                 if (p.cVec) {
                     // the chunk lies inside one tap of one pixel: one test, one 16-byte load
@@ -547,7 +552,8 @@ bs_gemm_kernel(const GemmParams p)
         for (int s = 0; s < CPT; ++s) {
             if (POOL && s * NT >= WROWS * KCH) continue;  // the activation tile comes from pool_write
             if (tid + s * NT < CHUNKS) lds[loff[s]] = stage[s];
-            if (CORR) cnt[s] += popc4(stage[s]);
+            if constexpr (CORR && CONV) cnt[s] += popc4(stage[s]);  // loaded under a branch: zero where there is nothing
+            else if constexpr (CORR) cnt[s] += (goff[s] >= 0 && k0 + ((tid + s * NT) % KCH) * 4 < p.Kd) ? popc4(stage[s]) : 0;
         }
         if constexpr (POOL) pool_write();
         __syncthreads();
@@ -741,6 +747,8 @@ bs_gemm_kernel(const GemmParams p)
                         uint32_t y = 0;
 #pragma unroll
                         for (int t = 0; t < T; ++t) y += (val[r][c] >= tv[t]) ? 1u : 0u;
+                        // (a row past M holds whatever the unconditional loads brought: its thresholds are INT_MAX, which no
+                        // sum within the overflow bound reaches)
 #pragma unroll
                         for (int pl = 0; pl < 4; ++pl) word[c][pl] |= ((y >> pl) & 1u) << (4 * ly + r);
                     }

@@ -53,6 +53,7 @@ def test_argument_errors_are_rejected_on_the_host():
     assert lib.bs_gemm(p, 2, 1, p, 2, 0, 4, 4, 357913942, p, 4, None) == bs.BS_ERR_OVERFLOW_RISK         # 2 * 3 * K
     assert lib.bs_gemm(p, 1, 2, p, 2, 0, 4, 4, 715827883, p, 4, None) == bs.BS_ERR_OVERFLOW_RISK         # 1 * 3 * K
     assert lib.bs_gemm(p, 1, 2, p, 1, 2, 4, 4, 1 << 31, p, 4, None) == bs.BS_ERR_OVERFLOW_RISK
+    assert lib.bs_gemm(p, 1, 0, p, 1, 0, 4, 4, (1 << 31) - 1, p, 4, None) == bs.BS_ERR_OVERFLOW_RISK    # a result could be INT_MAX
     # the approximate mode sums a subset of the plane pairs: bounded by the unsigned ranges, 15 * 15 * K
     assert lib.bs_gemm_topbits(p, 4, 1, p, 4, 0, 4, 4, 9544372, 3, p, 4, None) == bs.BS_ERR_OVERFLOW_RISK
     # engines: unknown value; the fp4 matrix-core kernel takes operands of at most two bits and 9 K < 2^24 for two planes each
