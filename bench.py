@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per bs_gemm launch on the W2A2 4096^3 workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE scaled by a 256 MiB copy (profiles/bench_w2a2_4096_trace_and_counters.md): 24.5 MiB + 64 MiB.  A counter run
 # cannot be made from inside this script; the figure is the one of the committed profile and is labelled as such.
-GEMM_TRAFFIC_BYTES = 92_952_618
+GEMM_TRAFFIC_BYTES = 92_953_222
 GEMM_TRAFFIC_SOURCE = "profiles/bench_w2a2_4096_trace_and_counters.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE of an earlier run of this command; not re-measured in this run)"
 # untimed GEMM launches before the warm-up steps (see main)
 CLOCK_WARMUP_LAUNCHES = 100
