@@ -107,7 +107,8 @@ struct PlanesResult {
     const int *row_term, *col_term;  // LDS, indexed by the row / column inside the tile
     __device__ __forceinline__ int operator()(float a, int row, int col) const
     {
-        return wrap_add(wrap_mul(mul, (int)(a * acc_scale)), wrap_add(row_term[row], col_term[col]));
+        // one multiplication: mul is 1, 2 or 4 and the scaled sum an integer below 2^24, so the product is exact in fp32
+        return wrap_add((int)(a * (acc_scale * (float)mul)), wrap_add(row_term[row], col_term[col]));
     }
     __device__ __forceinline__ int operator()(int a, int row, int col) const
     {
