@@ -168,16 +168,28 @@ __device__ __forceinline__ void dense_epilogue(const DenseParams &p, typename Ac
     const int li = lane & 31, lg = lane >> 5;
     (void)tile_m;
     if constexpr (!FUSE) {
+        constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
+        // a tile that lies wholly inside C stores without a test (and without a branch) per element
+        const bool inside = m0 + BM <= p.M && n0 + BN <= p.N;  // uniform
 #pragma unroll
         for (int a = 0; a < WTM; ++a)
 #pragma unroll
             for (int b = 0; b < WTN; ++b) {
                 const int n = n0 + (wn * WTN + b) * 32 + li;
+                const int mr = (wm * WTM + a) * 32 + 4 * lg;   // this lane's first row of the 32-row band, within the tile
+                int32_t *cp = p.C + (long long)(m0 + mr) * p.ldc + n;
+                if (inside) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = m0 + (wm * WTM + a) * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-                    if (m < p.M && n < p.N)
-                        p.C[(long long)m * p.ldc + n] = result(acc[a][b][v], m - m0, n - n0);
+                    for (int v = 0; v < 16; ++v) {
+                        const int dr = 8 * (v >> 2) + (v & 3);
+                        cp[(long long)dr * p.ldc] = result(acc[a][b][v], mr + dr, n - n0);
+                    }
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int dr = 8 * (v >> 2) + (v & 3);
+                        if (m0 + mr + dr < p.M && n < p.N) cp[(long long)dr * p.ldc] = result(acc[a][b][v], mr + dr, n - n0);
+                    }
                 }
             }
     } else {
