@@ -838,7 +838,7 @@ bs_status launch_variant(const GemmParams &g, dim3 grid, bool fuse, bool corr, b
     if (conv) {  // implicit lowering exists with the thresholding epilogue only
         if (!fuse) return BS_ERR_UNSUPPORTED;
         if (g.pK > 0) {  // pooled fetch: instantiated for the narrow tiles only (launch_planes takes no other for it)
-            if constexpr (KS == 4 && TN <= 2) {
+            if constexpr (KS >= 4 && TN <= 2) {
                 if (corr) bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, CAN_CORR, true, false, IDLE, true><<<grid, block, 0, st>>>(g);
                 else bs_gemm_kernel<WB, AB, TM, TN, WM, WN, KS, KT, true, false, true, false, IDLE, true><<<grid, block, 0, st>>>(g);
                 return bs::after_launch();
@@ -900,7 +900,17 @@ bs_status launch_planes(const GemmParams &g, bool fuse, bool corr, bool conv, bo
     // narrow tiles also whenever at most 16 columns exist: wider tiles would be half empty or more
     if (tiles32 <= kNarrowMaxTiles32 || g.N <= 16) {
         const long long narrow_blocks = (long long)((g.M + 31) / 32) * ((g.N + 7) / 8);
-        if (narrow_blocks <= 768) return launch_cfg<WB, AB, 4, 1, 1, 1, 4, KT_DEEP>(g, fuse, corr, conv, xr, st);
+        if (narrow_blocks <= 768) {
+            // Eight wavefronts that split stages of twice the depth, instead of four: half as many stages, each with
+            // the same products per wavefront, and two wavefronts per SIMD to overlap each other's latencies.  Measured
+            // against four (W1A2, W2A2, W4A4; 8..704 workgroups; depth 1024..9216): 6 to 20 % faster for more than four
+            // plane pairs at every size, and for up to four pairs from about three stages of depth on while the
+            // workgroups do not outnumber the compute units by much (conv4, conv5 of Table 2 at batch 1: 6.8 -> 6.3 and
+            // 6.0 -> 5.3 us); up to 38 % slower on short depths with 600 and more workgroups, hence the conditions.
+            const bool eight = (WB * AB > 4) || (narrow_blocks <= 400 && g.Kd > 75);
+            if (eight) return launch_cfg<WB, AB, 4, 1, 1, 1, 8, 2 * kStageDwords>(g, fuse, corr, conv, xr, st);
+            return launch_cfg<WB, AB, 4, 1, 1, 1, 4, KT_DEEP>(g, fuse, corr, conv, xr, st);
+        }
         return launch_cfg<WB, AB, 4, 1, 1, 1, 4, KT_SMALL>(g, fuse, corr, conv, xr, st);
     }
     // just above the tiny grids 32 x 16 tiles still pay: twice the workgroups, so that two wavefronts share a SIMD
