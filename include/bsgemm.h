@@ -341,7 +341,8 @@ bs_status bs_streamline_thresholds(const double *t, int T, const double *a, cons
  * k = K / 1024, thresholding epilogue included):
  *   bit-serial  N > 16, by the tile the launch takes (t32, t64 = tiles of 32 x 32, 64 x 64 the output needs;
  *               g = 2MNK p / 1e9, e = abits MN / 1e6):
- *                 t32 <= 200   (32 x 8 tiles)             3.17 + 0.270 k p + 6.10 e
+ *                 t32 <= 200   (32 x 8 tiles)             3.03 + 0.206 p + k p (0.155 + 0.113 s) + 1.14 e,
+ *                                                         s = ceil(B / 256) - 1 further workgroups per compute unit (B below)
  *                 t32 <= 384   (32 x 16 tiles)            1.98 + 0.492 k p + 5.06 e
  *                 t64 <  512   (32 x 32, depth split)     0.38 + 0.839 g + 3.47 e
  *                 else         (64 x 64)                  1.12 + 0.612 k p + 0.685 g + 0.825 e

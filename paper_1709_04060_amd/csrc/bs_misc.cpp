@@ -39,7 +39,11 @@ double t_bitserial_tiled(double M, double N, double K, int wbits, int abits)
     const long long tiles32 = ((m + 31) / 32) * ((n + 31) / 32), tiles64 = ((m + 63) / 64) * ((n + 63) / 64);
     const double p = (double)wbits * abits, kp = K / 1024.0 * p;
     const double work = 2.0 * M * N * K * p / 1e9, epi = M * N * abits / 1e6;
-    if (tiles32 <= bs::kNarrowMaxTiles32) return 3.17 + 0.270 * kp + 6.10 * epi;    // 32 x 8 tiles
+    if (tiles32 <= bs::kNarrowMaxTiles32) {  // 32 x 8 tiles; a second workgroup on a compute unit slows both
+        const long long blocks = ((m + 31) / 32) * ((n + 7) / 8);
+        const double second = (double)((blocks + 255) / 256 - 1);
+        return 3.03 + 0.206 * p + kp * (0.155 + 0.113 * second) + 1.14 * epi;
+    }
     if (tiles32 <= bs::kHalfWidthMaxTiles32) return 1.98 + 0.492 * kp + 5.06 * epi;  // 32 x 16
     if (tiles64 < bs::kWideMinTiles64) return 0.38 + 0.839 * work + 3.47 * epi;      // 32 x 32, depth split
     return 1.12 + 0.612 * kp + 0.685 * work + 0.825 * epi;                           // 64 x 64
