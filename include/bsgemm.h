@@ -351,22 +351,23 @@ bs_status bs_streamline_thresholds(const double *t, int T, const double *a, cons
  *               B = ceil(M / 32) ceil(N / 8) (tiled kernel, 32 x 8 tiles); bs_gemm itself picks between these two
  *   dense       F + ceil(K / d) r c + E abits MN / 1e6, with d = 256 depth indices per period of the kernel's pipeline
  *               as fp4 codes, 128 as int8 codes; r = rounds of tiles over the chip (bs_planes_tile); and the time of a
- *               period c = c1 + c2 P + f (c3 + c4 P) + c5 max(0, f - 1/2), P = wbits + abits planes to request and merge,
- *               f = the part of the chip's tile slots that is filled (two 128 x 128 tiles share a compute unit beyond 1/2):
+ *               period c = c1 + c2 P + f (c3 + c4 P) + c5 max(0, f - h), P = wbits + abits planes to request and merge,
+ *               f = the part of the chip's tile slots that is filled (256, 512, 1024 slots for the three tiles), h = 1/2
+ *               (1/4 for the 64 x 64 tile): beyond it workgroups share a compute unit; c5 applies to max(0, f - h):
  *                                    F      c1     c2      c3      c4      c5     E
- *                 int8,  64 x 64     5.37   0.612  0.0566  0       0       0      0.0841
- *                 int8, 128 x 128    6.32   0.809  0.0635  0.0328  0.0822  0.567  0.218
- *                 int8, 256 x 256   12.15   1.262  0.1438  0.1413  0.0830  0      0.117
- *                 fp4,   64 x 64     4.93   0.545  0.0485  0       0       0      0
- *                 fp4,  128 x 128    5.58   0.694  0.0760  0.0752  0.0619  0.612  0.218
- *                 fp4,  256 x 256   10.67   1.008  0.1714  0       0.1319  0      0.0708
+ *                 int8,  64 x 64     4.87   0.623  0.0377       0  0.0177  0.387  0.319
+ *                 int8, 128 x 128    6.17   0.783  0.0609  0.2404  0.0062  0.351  0.303
+ *                 int8, 256 x 256   11.63   1.232  0.1467       0  0.0617      0  0.198
+ *                 fp4,   64 x 64     4.69   0.505  0.0417       0  0.0411  0.297  0.205
+ *                 fp4,  128 x 128    5.57   0.615  0.0789  0.0182  0.0557  0.510  0.283
+ *                 fp4,  256 x 256   10.11   0.947  0.1680       0  0.1317      0  0.133
  * N <= 4 is always bit-serial (weights are read once, wbits/8 byte per weight, and nothing is expanded).
  * Invalid arguments (bits outside 1..4, bipolar with bits != 1, non-positive sizes) return BS_ENGINE_BITSERIAL.
  */
 bs_engine bs_choose_engine(int wbits, bs_format wfmt, int abits, bs_format afmt, int64_t M, int64_t N, int64_t K);
 
 /* Tile edge (256, 128 or 64) the matrix-core kernel on packed planes takes for an M x N output, the rounds of such tiles
- * over the chip (256 slots for the largest tile, 512 for the others) and their number (either pointer may be NULL).
+ * over the chip (256 slots for the largest tile, 512 and 1024 for the smaller ones) and their number (either pointer may be NULL).
  * Host-only; part of the time model above. */
 int bs_planes_tile(int64_t M, int64_t N, long long *rounds, long long *tiles);
 

@@ -59,16 +59,17 @@ double t_planes(double M, double N, double K, int wbits, int abits, bool fp4)
     long long rounds, tiles;
     const int tile = bs_planes_tile((int64_t)M, (int64_t)N, &rounds, &tiles);
     const double nper = (double)(((int64_t)K + (fp4 ? 255 : 127)) / (fp4 ? 256 : 128));
-    const double cap = tile == 256 ? 256.0 : 512.0;
+    const double cap = tile == 256 ? 256.0 : (tile == 128 ? 512.0 : 1024.0);  // workgroups the chip holds at a time
     const double fill = ((double)tiles < cap ? (double)tiles : cap) / cap, P = wbits + abits;
-    const double shared = fill > 0.5 ? fill - 0.5 : 0.0;
+    const double alone = tile == 64 ? 0.25 : 0.5;  // up to here every workgroup has a compute unit to itself
+    const double shared = fill > alone ? fill - alone : 0.0;
     // fixed; per period: 1, P, fill, P fill, shared; epilogue per abits M N / 1e6
-    static const double c[2][3][7] = {{{5.37, 0.612, 0.0566, 0.0, 0.0, 0.0, 0.0841},             // int8, 64 x 64
-                                       {6.32, 0.809, 0.0635, 0.0328, 0.0822, 0.567, 0.218},       // int8, 128 x 128
-                                       {12.15, 1.262, 0.1438, 0.1413, 0.0830, 0.0, 0.117}},       // int8, 256 x 256
-                                      {{4.93, 0.545, 0.0485, 0.0, 0.0, 0.0, 0.0},                 // fp4, 64 x 64
-                                       {5.58, 0.694, 0.0760, 0.0752, 0.0619, 0.612, 0.218},       // fp4, 128 x 128
-                                       {10.67, 1.008, 0.1714, 0.0, 0.1319, 0.0, 0.0708}}};        // fp4, 256 x 256
+    static const double c[2][3][7] = {{{4.87, 0.623, 0.0377, 0.0000, 0.0177, 0.387, 0.319},    // int8, 64 x 64
+                                       {6.17, 0.783, 0.0609, 0.2404, 0.0062, 0.351, 0.303},    // int8, 128 x 128
+                                       {11.63, 1.232, 0.1467, 0.0000, 0.0617, 0.000, 0.198}},  // int8, 256 x 256
+                                      {{4.69, 0.505, 0.0417, 0.0000, 0.0411, 0.297, 0.205},    // fp4, 64 x 64
+                                       {5.57, 0.615, 0.0789, 0.0182, 0.0557, 0.510, 0.283},    // fp4, 128 x 128
+                                       {10.11, 0.947, 0.1680, 0.0000, 0.1317, 0.000, 0.133}}}; // fp4, 256 x 256
     const double *q = c[fp4 ? 1 : 0][tile == 256 ? 2 : (tile == 128 ? 1 : 0)];
     const double per = q[1] + q[2] * P + fill * (q[3] + q[4] * P) + shared * q[5];
     return q[0] + nper * (double)rounds * per + q[6] * abits * M * N / 1e6;
@@ -76,18 +77,18 @@ double t_planes(double M, double N, double K, int wbits, int abits, bool fp4)
 
 }  // namespace
 
-// Tile of the matrix-core kernel on packed planes for an M x N output.  Up to 128 tiles of 128 x 128 (a quarter of the
-// chip's slots for them): 64 x 64 tiles on two wavefronts, four times as many workgroups, each expanding half the rows
-// (15 to 38 % faster there on every measured shape).  Beyond: 256 x 256 (one workgroup per compute unit) or 128 x 128
-// (two); a round of 128 x 128 tiles over the chip (512 of them) takes 0.67 of a round of 256 x 256 tiles (256 of them)
-// and covers half as much output.  On the shapes of the sweep above the rule is within 0.2 % of the best tile on
-// average, 11 % at worst.
+// Tile of the matrix-core kernel on packed planes for an M x N output.  Up to 256 tiles of 128 x 128: 64 x 64 tiles on
+// two wavefronts, four times as many workgroups (the chip holds 1024 of them at a time, four per compute unit), each
+// expanding half the rows: up to 17 % faster than 128 x 128 tiles up to that size, within 3 % of them where it is not;
+// from 320 tiles of 128 x 128 on it is 20 to 50 % slower.  Beyond: 256 x 256 (one workgroup per compute unit) or
+// 128 x 128 (two); a round of 128 x 128 tiles over the chip (512 of them) takes 0.67 of a round of 256 x 256 tiles (256
+// of them) and covers half as much output.
 extern "C" int bs_planes_tile(int64_t M, int64_t N, long long *rounds, long long *tiles)
 {
     const long long t256 = ((M + 255) / 256) * ((N + 255) / 256), t128 = ((M + 127) / 128) * ((N + 127) / 128);
-    if (t128 <= 128) {
+    if (t128 <= 256) {
         const long long t64 = ((M + 63) / 64) * ((N + 63) / 64);
-        if (rounds) *rounds = (t64 + 511) / 512;
+        if (rounds) *rounds = (t64 + 1023) / 1024;
         if (tiles) *tiles = t64;
         return 64;
     }

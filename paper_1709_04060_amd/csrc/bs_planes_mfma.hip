@@ -36,6 +36,8 @@
 // Plane words are requested a period ahead, 16 bytes per row and plane: every lane of such a request touches
 // another cache line, and those look-ups bound the loader (with all lanes on one row the W4A4 8192^3 product took
 // 555 instead of 1105 us), hence as few and as wide requests as the registers allow.
+#include <algorithm>
+#include <vector>
 #include "bs_dense_common.h"
 #include "bs_gemm_kernel.h"
 
@@ -43,6 +45,7 @@ namespace bs {
 namespace {
 
 using namespace bs::dense;
+typedef __attribute__((address_space(3))) void lds_void;
 
 struct OperandCoding {
     int bits;
@@ -64,6 +67,10 @@ struct PlanesParams {
     float acc_scale;
     // implicit lowering (CONV kernels): Ap points at packed HWC image planes; see PlanesGemm
     int cH, cW, cCd, cPix, cKW, cStride, cPad, cOW, cOHW, cB, cKused;
+    // tile order (plan_order): 0 = workgroup i takes tile i of the row-major order; 1, 2 = the workgroups of an XCD
+    // (workgroup index mod 8) take a run of consecutive tiles, xcd_base (+ 1 for the first xcd_rem XCDs) of them, in
+    // row-major (1) or column-major (2) order of the tile grid
+    int order, xcd_base, xcd_rem;
 };
 
 // (a & m) | (b & ~m): one v_bfi_b32
@@ -82,6 +89,7 @@ __device__ __forceinline__ uint4 expand32_fp4(uint32_t lo, uint32_t hi)
 {
     uint32_t e, o;
     merge_pair(lo, hi, e, o);
+    asm("" : "+v"(e), "+v"(o));  // used as they are: see expand32_i8
     return make_uint4(e & 0x33333333u, (e >> 2) & 0x33333333u, o & 0x33333333u, (o >> 2) & 0x33333333u);
 }
 
@@ -96,6 +104,9 @@ __device__ __forceinline__ void expand32_i8(const uint32_t (&x)[4], uint4 &out0,
     n[1] = bitsel(0x33333333u, e01 >> 2, e23);
     n[2] = bitsel(0x33333333u, o01, o23 << 2);
     n[3] = bitsel(0x33333333u, o01 >> 2, o23);
+    // The outputs below take the n[] as they are.  Left transparent, each masked output is rebuilt from the planes'
+    // words through a chain of its own that keeps only the bits it needs (52 instead of 36 instructions per 32 codes).
+    asm("" : "+v"(n[0]), "+v"(n[1]), "+v"(n[2]), "+v"(n[3]));
     out0 = make_uint4(n[0] & 0x0F0F0F0Fu, (n[0] >> 4) & 0x0F0F0F0Fu, n[1] & 0x0F0F0F0Fu, (n[1] >> 4) & 0x0F0F0F0Fu);
     out1 = make_uint4(n[2] & 0x0F0F0F0Fu, (n[2] >> 4) & 0x0F0F0F0Fu, n[3] & 0x0F0F0F0Fu, (n[3] >> 4) & 0x0F0F0F0Fu);
 }
@@ -134,7 +145,15 @@ planes_mfma_kernel(const PlanesParams p)
     static_assert(BM % 64 == 0, "a wavefront's rows belong to one operand");
     constexpr int TILE = NT * DK;                // bytes per stage buffer
     __shared__ __attribute__((aligned(16))) unsigned char lds[4 * TILE];  // two stages being multiplied, two being written
-    __shared__ int terms[NT];                    // per-row terms of the result: W rows, then A rows (columns of C)
+    // STASH (int8 kind, packed-matrix operands): plane words are requested for two periods at a time, 32 adjacent bytes
+    // per row and plane; the first period's words go to registers, the second one's straight into this thread's 16-byte
+    // places of `raw` (global_load_lds_dwordx4: the 64 lanes' chunks land side by side) and are picked up a period
+    // later.  A third fewer requests reach L2; 3 to 9 % faster on four-plane operands, slower for the fp4 kind, whose
+    // period already takes 32 adjacent bytes.
+    constexpr bool STASH = !CONV && !FP4;
+    constexpr int RAWCH = NB * (PW / 4);         // 16-byte chunks per row and period
+    __shared__ __attribute__((aligned(16))) unsigned char raw[STASH ? NT * RAWCH * 16 : NT * 4];
+    int *const terms = reinterpret_cast<int *>(raw);  // per-row terms of the result (after the loop): W rows, then A rows
     // lowered dword -> (kernel row << 24 | kernel column << 16 | channel word), -1 past the data
     __shared__ __attribute__((aligned(16))) int lut[CONV ? kConvMaxLut + 8 : 4];
 
@@ -142,7 +161,13 @@ planes_mfma_kernel(const PlanesParams p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
     const int li = lane & 31, lg = lane >> 5;
-    const int tile_m = blockIdx.x / p.d.gx, tile_n = blockIdx.x % p.d.gx;
+    int tile_m, tile_n;
+    {
+        const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+        const int lin = p.order == 0 ? (int)blockIdx.x : xcd * p.xcd_base + (xcd < p.xcd_rem ? xcd : p.xcd_rem) + local;
+        if (p.order == 2) { tile_n = lin / p.d.gy; tile_m = lin - tile_n * p.d.gy; }
+        else { tile_m = lin / p.d.gx; tile_n = lin - tile_m * p.d.gx; }
+    }
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     // ---- this thread's row: operand, the plane each code-bit slot takes, masks ----
@@ -247,6 +272,37 @@ planes_mfma_kernel(const PlanesParams p)
             }
         }
     };
+    // STASH: period -> R as above, period + 1 -> raw (requested next to each other: the two lie in the same 64 bytes
+    // of memory, so the second request finds the first one's line on its way)
+    lds_void *const raw_wave = (lds_void *)(raw + wave * RAWCH * 1024);
+    const unsigned char *const raw_mine = raw + wave * RAWCH * 1024 + lane * 16;
+    auto fetch_pair = [&](int period) {
+        const int s = period < p.nper ? period : p.nper - 1, s1 = period + 1 < p.nper ? period + 1 : p.nper - 1;
+        const int o2 = s * PW + 4 < p.Kd ? s * PW + 4 : p.Kd - 4, o3 = s1 * PW + 4 < p.Kd ? s1 * PW + 4 : p.Kd - 4;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(pl_ptr[q] + s * PW);
+            R[q][0] = v.x; R[q][1] = v.y; R[q][2] = v.z; R[q][3] = v.w;
+            if constexpr (PW == 8) {
+                const uint4 u = *reinterpret_cast<const uint4 *>(pl_ptr[q] + o2);
+                R[q][4] = u.x; R[q][5] = u.y; R[q][6] = u.z; R[q][7] = u.w;
+            }
+            __builtin_amdgcn_global_load_lds((const void *)(pl_ptr[q] + s1 * PW), (lds_void *)((unsigned char __attribute__((address_space(3))) *)raw_wave + q * (PW / 4) * 1024), 16, 0, 0);
+            if constexpr (PW == 8)
+                __builtin_amdgcn_global_load_lds((const void *)(pl_ptr[q] + o3), (lds_void *)((unsigned char __attribute__((address_space(3))) *)raw_wave + (q * 2 + 1) * 1024), 16, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    auto unstash = [&]() {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int q = 0; q < NB; ++q)
+#pragma unroll
+            for (int h = 0; h < PW / 4; ++h) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(raw_mine + (q * (PW / 4) + h) * 1024);
+                R[q][4 * h] = v.x; R[q][4 * h + 1] = v.y; R[q][4 * h + 2] = v.z; R[q][4 * h + 3] = v.w;
+            }
+    };
     // Expands stage `stage` (half `h` of the period in R) and writes its four chunks into stage buffer `buf`.
     // TAIL: the stage may be the last one (an inverted top plane is cut off at the depth) or lie past the depth (the
     // pipeline touches up to three such stages at its end; they become zero codes and stay out of the row sums).
@@ -268,6 +324,9 @@ planes_mfma_kernel(const PlanesParams p)
                 uint32_t r = R[q][h * DW + d];
                 if constexpr (CONV) r &= (uint32_t)__builtin_amdgcn_sbfe(okbits, h * DW + d, 1);  // all ones or zero
                 x[q] = TAIL ? (((r & plain[q]) | (~r & flipped[q] & vm)) & live) : ((r & plain[q]) | (~r & flipped[q]));
+                // one value from here on: left transparent, the two terms are carried through the merges below separately
+                // (shifts and masks distribute over the OR) and joined at the end, at 1.6 times the instructions
+                asm("" : "+v"(x[q]));
                 popc[q] += __builtin_popcount(x[q]);
             }
             if constexpr (FP4) {
@@ -318,7 +377,7 @@ planes_mfma_kernel(const PlanesParams p)
         }
     };
     constexpr std::integral_constant<int, 0> kNoValu{};
-    constexpr std::integral_constant<int, (FP4 ? 80 : 110) / (WTM * WTN) + 1> kExpandValu{};
+    constexpr std::integral_constant<int, (FP4 ? 60 : 84) / (WTM * WTN) + 1> kExpandValu{};
 
     // One period = two stages = four depth steps ("quarters").  PP: parity of the period; its stages sit in LDS
     // buffers 2 PP and 2 PP + 1, the next period's stages are written into the other two.  The fragments of a quarter
@@ -346,7 +405,9 @@ planes_mfma_kernel(const PlanesParams p)
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
-        fetch(P + 2);
+        if constexpr (!STASH) fetch(P + 2);
+        else if constexpr (PP == 0) fetch_pair(P + 2);
+        else unstash();
         load_frags(0, N0, 0);
         mfmas(1);
         interleave(kNoValu);
@@ -402,6 +463,43 @@ OperandCoding coding_of(int bits, bs_format fmt, bool fp4)
     return c;
 }
 
+// Which tiles the workgroups of one XCD take.  Workgroups are dealt round-robin to the 8 XCDs, each with its own 4 MiB
+// L2, so workgroup i of the plain order lands on XCD i mod 8: with a tile grid whose width is a multiple of 8 an XCD
+// then owns a few tile columns and walks down all tile rows (good: its activation panels stay in L2), but with an odd
+// width, or few tile rows or columns, every XCD touches nearly every panel of the larger operand (384 x 10816 in 64 x 64
+// tiles: 127 of the 169 column panels per XCD, where a run of consecutive tiles in column-major order needs 22).  The
+// three orders are compared by walking XCD 0's tiles in launch order, `resident` at a time (what the XCD's compute
+// units hold): every panel (a tile's rows of all planes of one operand) that was not touched by the previous group
+// costs its planes; if a group's panels exceed the L2, nothing is kept.  Ties keep the plain order.
+void plan_order(PlanesParams &p, int tile, int resident)
+{
+    const long long blocks = (long long)p.d.gx * p.d.gy;
+    p.order = 0; p.xcd_base = (int)(blocks / 8); p.xcd_rem = (int)(blocks % 8);
+    if (blocks < 16 || blocks > 65536) return;
+    const int gx = p.d.gx, gy = p.d.gy, n0 = (int)((blocks + 7) / 8);
+    const long long panel = (long long)tile * p.Kd * 4;   // bytes of a panel's plane
+    long long best = -1;
+    std::vector<int> seen_row(gy), seen_col(gx);
+    for (int order = 0; order < 3; ++order) {
+        std::fill(seen_row.begin(), seen_row.end(), -2);
+        std::fill(seen_col.begin(), seen_col.end(), -2);
+        long long cost = 0;
+        for (int g0 = 0, g = 0; g0 < n0; g0 += resident, ++g) {
+            const int g1 = std::min(n0, g0 + resident);
+            long long fresh = 0, all = 0;
+            for (int local = g0; local < g1; ++local) {
+                const long long lin = order == 0 ? 8LL * local : local;
+                if (lin >= blocks) break;
+                const int tm = order == 2 ? (int)(lin % gy) : (int)(lin / gx), tn = order == 2 ? (int)(lin / gy) : (int)(lin % gx);
+                if (seen_row[tm] != g) { all += p.cw.bits; if (seen_row[tm] != g - 1) fresh += p.cw.bits; seen_row[tm] = g; }
+                if (seen_col[tn] != g) { all += p.ca.bits; if (seen_col[tn] != g - 1) fresh += p.ca.bits; seen_col[tn] = g; }
+            }
+            cost += all * panel <= (3LL << 20) ? fresh : all;
+        }
+        if (best < 0 || cost < best) { best = cost; p.order = order; }
+    }
+}
+
 template <bool FP4, int WTM, int WTN, int WGM, int WGN>
 bs_status launch_tile(PlanesParams &p, bool fuse, bool conv, hipStream_t st)
 {
@@ -410,6 +508,7 @@ bs_status launch_tile(PlanesParams &p, bool fuse, bool conv, hipStream_t st)
     p.d.gy = (p.d.M + BM - 1) / BM;
     const long long blocks = (long long)p.d.gx * p.d.gy;
     if (blocks >= (1LL << 31)) return BS_ERR_UNSUPPORTED;
+    plan_order(p, BM, (int)(NT == 512 ? 32 : NT == 256 ? 64 : 128));
     if (conv) {  // implicit lowering exists with the thresholding epilogue only
         if (!fuse) return BS_ERR_UNSUPPORTED;
         if (p.cCd % 4 == 0 && p.cPix % 4 == 0) planes_mfma_kernel<FP4, WTM, WTN, WGM, WGN, true, true, true><<<dim3((unsigned)blocks), NT, 0, st>>>(p);
@@ -425,7 +524,11 @@ bs_status launch_kind(PlanesParams &p, bool fuse, bool conv, hipStream_t st)
     // 256 x 256 tiles on eight wavefronts (one per compute unit), 128 x 128 on four (two per compute unit) or, for
     // small outputs, 64 x 64 on two (each wavefront 32 x 64).  A smaller tile expands more rows per product, but puts
     // more workgroups on the chip: bs_planes_tile holds the rule, which the engine choice's time model shares.
-    const int tile = bs_planes_tile(p.d.M, p.d.N, nullptr, nullptr);
+    int tile = bs_planes_tile(p.d.M, p.d.N, nullptr, nullptr);
+    // The implicit-lowering kernels keep their look-up table in LDS as well, so that a compute unit holds three
+    // workgroups of the 64 x 64 tile instead of four: beyond 768 tiles these take the larger tile (conv3 of Table 2 at
+    // batch 64, 1014 tiles: 27 us instead of 15.6).
+    if (conv && tile == 64 && ((p.d.M + 63) / 64) * (long long)((p.d.N + 63) / 64) > 768) tile = 128;
     if (tile == 256) return launch_tile<FP4, 4, 2, 2, 4>(p, fuse, conv, st);
     if (tile == 64) return launch_tile<FP4, 1, 2, 2, 1>(p, fuse, conv, st);
     return launch_tile<FP4, 2, 2, 2, 2>(p, fuse, conv, st);
