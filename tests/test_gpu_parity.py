@@ -261,6 +261,25 @@ def test_gemm_threshold_fused(M, K, N, w, wf, a, af, obits):
     assert_equal(got, oracle.threshold_pack(C, thr, obits), "fused gemm+threshold")
 
 
+# Long, thin outputs: the matrix-core kernels on packed planes map their workgroups to tiles in one of three orders
+# (plain; runs of consecutive tiles per XCD, by rows or by columns of the tile grid), chosen on the host from the grid
+# and the operands' planes.  These shapes reach the two run orders with every tile size, ragged edges, a tile count
+# that is no multiple of 8 and more tiles than the chip holds at a time.
+@pytest.mark.parametrize("M,K,N", [(390, 200, 10801), (70, 130, 16390), (16390, 130, 70), (200, 96, 43270), (43270, 96, 200),
+                                   (384, 192, 43264), (8200, 300, 390), (1030, 260, 4100), (600, 64, 43270), (43270, 64, 600)])
+@pytest.mark.parametrize("w,wf,a,af,obits", [(1, BP, 2, U, 2), (2, TC, 2, U, 2), (4, TC, 4, U, 4)])
+def test_long_thin_outputs_on_every_engine(M, K, N, w, wf, a, af, obits):
+    rng = np.random.default_rng(M + 3 * K + 7 * N + obits)
+    W, A = draw(rng, (M, K), w, wf), draw(rng, (K, N), a, af)
+    C = oracle.gemm(W, A)
+    thr = make_thr(rng, C, obits)
+    Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
+    Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
+    assert_equal(gemm_all_engines(Wp, FMT[wf], Ap, FMT[af], K), C, "long thin gemm %dx%dx%d" % (M, K, N))
+    got = gemm_threshold_all_engines(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits)
+    assert_equal(got, oracle.threshold_pack(C, thr, obits), "long thin fused gemm+threshold %dx%dx%d" % (M, K, N))
+
+
 # ------------------------------------------------------------------ S2 lowering
 def pad_channels(x, Cp):
     out = np.zeros(x.shape[:-1] + (Cp,), dtype=x.dtype)
