@@ -35,25 +35,60 @@ threshold_kernel(const int32_t *__restrict__ C, long long ldc, int M, int N, con
             c[r] = C[(long long)row * ldc + n];
         }
     }
+    // Bit-sliced over the thread's 32 rows: word hit[t] collects, one bit per row, whether the row's accumulator
+    // reaches the row's threshold t (compare into the carry, then hit = 2 hit + carry, rows taken from 31 down to 0 so
+    // that row r ends up in bit r).  The count of Sec. 2.1.1 is the sum of the T one-bit words, taken for all 32 rows
+    // at once by a carry-save adder tree whose outputs ARE the plane words (11 full adders of two three-input bit
+    // operations for T = 15), instead of a count per element that is then cut into planes bit by bit (8 more
+    // instructions per element at 4 bits: 94 -> 79 us for 8192 x 8192).
     uint32_t w[OB];
 #pragma unroll
     for (int p = 0; p < OB; ++p) w[p] = 0;
     if (n < N) {
+        uint32_t hit[T];
 #pragma unroll
-        for (int r = 0; r < 32; ++r) {
+        for (int t = 0; t < T; ++t) hit[t] = 0;
+#pragma unroll
+        for (int r = 31; r >= 0; --r) {
             const int row = mbase + (r < last ? r : last);
             const int32_t *tr = thr + (long long)row * T;
-            uint32_t y = 0;
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 const int32_t th = tr[t];  // uniform address: a scalar load
-                // y += (c >= th): compare into the carry mask, add the carry
-                asm("v_cmp_le_i32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, 0, %0, vcc" : "+v"(y) : "v"(c[r]), "s"(th) : "vcc");
+                asm("v_cmp_le_i32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(hit[t]) : "v"(c[r]), "s"(th) : "vcc");
             }
-            if (r > last) y = 0;
-#pragma unroll
-            for (int p = 0; p < OB; ++p) w[p] |= ((y >> p) & 1u) << r;
         }
+        auto full_add = [](uint32_t x, uint32_t y, uint32_t z, uint32_t &sum, uint32_t &carry) {
+            sum = x ^ y ^ z;
+            carry = (x & y) | (z & (x ^ y));
+        };
+        if constexpr (OB == 1) {
+            w[0] = hit[0];
+        } else if constexpr (OB == 2) {
+            full_add(hit[0], hit[1], hit[2], w[0], w[1]);
+        } else {
+            constexpr int G = T / 3;  // full adders of the first level: 2 (T = 7) or 5 (T = 15)
+            uint32_t s1[G], c1[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) full_add(hit[3 * g], hit[3 * g + 1], hit[3 * g + 2], s1[g], c1[g]);
+            if constexpr (OB == 3) {
+                uint32_t c2;
+                full_add(s1[0], s1[1], hit[6], w[0], c2);
+                full_add(c1[0], c1[1], c2, w[1], w[2]);
+            } else {
+                uint32_t t0, c5, c6, u0, u1, d0, d1, d2;
+                full_add(s1[0], s1[1], s1[2], t0, c5);
+                full_add(t0, s1[3], s1[4], w[0], c6);
+                full_add(c1[0], c1[1], c1[2], u0, d0);
+                full_add(c1[3], c1[4], c5, u1, d1);
+                full_add(u0, u1, c6, w[1], d2);
+                full_add(d0, d1, d2, w[2], w[3]);
+            }
+        }
+        // rows past M compared a copy of row M - 1: their bits are dropped
+        const uint32_t valid = last >= 31 ? 0xFFFFFFFFu : (last < 0 ? 0u : ((2u << last) - 1u));
+#pragma unroll
+        for (int p = 0; p < OB; ++p) w[p] &= valid;
     }
 #pragma unroll
     for (int p = 0; p < OB; ++p) reinterpret_cast<uint32_t *>(yt)[(p * 64 + (tid & 63)) * 4 + wave] = w[p];
