@@ -34,6 +34,43 @@ __device__ __forceinline__ void prefetch_kernel_arguments()
     asm volatile("" ::"s"(sink));  // keeps the loads; nothing is done with the value
 }
 
+// Sum of T = 2^OB - 1 one-bit inputs, bit-sliced: bit i of hit[t] says whether element i reached threshold t; plane
+// word w[p] gets bit p of every element's count (Sec. 2.1.1: the activation is the number of thresholds reached).  A
+// carry-save adder tree of full adders (two three-input bit operations each): 1, 4 or 11 of them for 32 elements.
+__device__ __forceinline__ void full_add(uint32_t x, uint32_t y, uint32_t z, uint32_t &sum, uint32_t &carry)
+{
+    sum = x ^ y ^ z;
+    carry = (x & y) | (z & (x ^ y));
+}
+
+template <int OB>
+__device__ __forceinline__ void count_planes(const uint32_t (&hit)[(1 << OB) - 1], uint32_t (&w)[OB])
+{
+    if constexpr (OB == 1) {
+        w[0] = hit[0];
+    } else if constexpr (OB == 2) {
+        full_add(hit[0], hit[1], hit[2], w[0], w[1]);
+    } else {
+        constexpr int G = ((1 << OB) - 1) / 3;  // full adders of the first level: 2 (7 inputs) or 5 (15 inputs)
+        uint32_t s1[G], c1[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) full_add(hit[3 * g], hit[3 * g + 1], hit[3 * g + 2], s1[g], c1[g]);
+        if constexpr (OB == 3) {
+            uint32_t c2;
+            full_add(s1[0], s1[1], hit[6], w[0], c2);
+            full_add(c1[0], c1[1], c2, w[1], w[2]);
+        } else {
+            uint32_t t0, c5, c6, u0, u1, d0, d1, d2;
+            full_add(s1[0], s1[1], s1[2], t0, c5);
+            full_add(t0, s1[3], s1[4], w[0], c6);
+            full_add(c1[0], c1[1], c1[2], u0, d0);
+            full_add(c1[3], c1[4], c5, u1, d1);
+            full_add(u0, u1, c6, w[1], d2);
+            full_add(d0, d1, d2, w[2], w[3]);
+        }
+    }
+}
+
 inline bs_status after_launch() { return hipGetLastError() == hipSuccess ? BS_OK : BS_ERR_LAUNCH; }
 
 inline bs_status check_bits_fmt(int bits, bs_format fmt)

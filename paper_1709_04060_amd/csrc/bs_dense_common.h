@@ -102,13 +102,17 @@ __device__ __forceinline__ void dense_threshold_planes(const DenseParams &p, typ
 #pragma unroll
     for (int a = 0; a < WTM; ++a) {
         const int rbase = (wm * WTM + a) * 32;  // first row of this 32-row band within the block tile
-        uint32_t word[WTN][OB];
+        // Bit-sliced over the lane's 16 rows of the band: hit[b][t] collects one bit per row (compare into the carry,
+        // hit = 2 hit + carry, rows taken from the last down so that accumulator v ends up in bit v), a carry-save
+        // adder tree turns the T words into the OB plane words of the 16 rows at once, and the 16 bits are spread to
+        // the rows' places in the 32-row word: v -> 8 (v / 4) + 4 lg + v % 4.
+        uint32_t hit[WTN][T];
 #pragma unroll
         for (int b = 0; b < WTN; ++b)
 #pragma unroll
-            for (int pl = 0; pl < OB; ++pl) word[b][pl] = 0;
+            for (int t = 0; t < T; ++t) hit[b][t] = 0;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
+        for (int v = 15; v >= 0; --v) {
             const int rr = 8 * (v >> 2) + 4 * lg + (v & 3);
             // one row's thresholds serve the WTN column tiles this lane holds
             int th[TS];
@@ -124,12 +128,21 @@ __device__ __forceinline__ void dense_threshold_planes(const DenseParams &p, typ
 #pragma unroll
             for (int b = 0; b < WTN; ++b) {
                 const int c = result(acc[a][b][v], rbase + rr, (wn * WTN + b) * 32 + li);
-                uint32_t y = 0;
 #pragma unroll
-                for (int e = 0; e < T; ++e)  // y += (c >= t): compare into the carry mask, add the carry
-                    asm("v_cmp_le_i32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, 0, %0, vcc" : "+v"(y) : "v"(c), "v"(th[e]) : "vcc");
+                for (int e = 0; e < T; ++e)
+                    asm("v_cmp_le_i32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(hit[b][e]) : "v"(c), "v"(th[e]) : "vcc");
+            }
+        }
+        uint32_t word[WTN][OB];
 #pragma unroll
-                for (int pl = 0; pl < OB; ++pl) word[b][pl] |= ((y >> pl) & 1u) << rr;
+        for (int b = 0; b < WTN; ++b) {
+            count_planes<OB>(hit[b], word[b]);
+#pragma unroll
+            for (int pl = 0; pl < OB; ++pl) {
+                uint32_t x = word[b][pl];                    // 16 bits: nibble g holds rows 8 g + 4 lg .. + 3
+                x = (x | (x << 8)) & 0x00FF00FFu;
+                x = (x | (x << 4)) & 0x0F0F0F0Fu;
+                word[b][pl] = x << (4 * lg);
             }
         }
         // Tiles of a multiple of 128 rows cover at least the Yd words of a column (Yd is a multiple of four), so

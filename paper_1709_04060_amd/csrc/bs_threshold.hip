@@ -58,33 +58,7 @@ threshold_kernel(const int32_t *__restrict__ C, long long ldc, int M, int N, con
                 asm("v_cmp_le_i32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(hit[t]) : "v"(c[r]), "s"(th) : "vcc");
             }
         }
-        auto full_add = [](uint32_t x, uint32_t y, uint32_t z, uint32_t &sum, uint32_t &carry) {
-            sum = x ^ y ^ z;
-            carry = (x & y) | (z & (x ^ y));
-        };
-        if constexpr (OB == 1) {
-            w[0] = hit[0];
-        } else if constexpr (OB == 2) {
-            full_add(hit[0], hit[1], hit[2], w[0], w[1]);
-        } else {
-            constexpr int G = T / 3;  // full adders of the first level: 2 (T = 7) or 5 (T = 15)
-            uint32_t s1[G], c1[G];
-#pragma unroll
-            for (int g = 0; g < G; ++g) full_add(hit[3 * g], hit[3 * g + 1], hit[3 * g + 2], s1[g], c1[g]);
-            if constexpr (OB == 3) {
-                uint32_t c2;
-                full_add(s1[0], s1[1], hit[6], w[0], c2);
-                full_add(c1[0], c1[1], c2, w[1], w[2]);
-            } else {
-                uint32_t t0, c5, c6, u0, u1, d0, d1, d2;
-                full_add(s1[0], s1[1], s1[2], t0, c5);
-                full_add(t0, s1[3], s1[4], w[0], c6);
-                full_add(c1[0], c1[1], c1[2], u0, d0);
-                full_add(c1[3], c1[4], c5, u1, d1);
-                full_add(u0, u1, c6, w[1], d2);
-                full_add(d0, d1, d2, w[2], w[3]);
-            }
-        }
+        bs::count_planes<OB>(hit, w);
         // rows past M compared a copy of row M - 1: their bits are dropped
         const uint32_t valid = last >= 31 ? 0xFFFFFFFFu : (last < 0 ? 0u : ((2u << last) - 1u));
 #pragma unroll
