@@ -475,7 +475,7 @@ void plan_order(PlanesParams &p, int tile, int resident)
 {
     const long long blocks = (long long)p.d.gx * p.d.gy;
     p.order = 0; p.xcd_base = (int)(blocks / 8); p.xcd_rem = (int)(blocks % 8);
-    if (blocks < 16 || blocks > 65536) return;
+    if (blocks < 16 || blocks > 8192) return;  // small grids have nothing to order; the walk below stays a few microseconds of host time
     const int gx = p.d.gx, gy = p.d.gy, n0 = (int)((blocks + 7) / 8);
     const long long panel = (long long)tile * p.Kd * 4;   // bytes of a panel's plane
     long long best = -1;
