@@ -435,6 +435,10 @@ planes_mfma_kernel(const PlanesParams p)
     if (P < p.nper) period(I0{}, std::true_type{}, P);
 
     // ---- per-row terms of the affine correction: slot q carries weight 2^(q - shift) of the unsigned code ----
+    // They go where the stashed plane words were.  The last periods still request words past the depth (clamped
+    // addresses, never read back): those writes into `raw` have to land before the terms do, the first wavefront's
+    // places being where every wavefront's terms go.
+    if constexpr (STASH) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
     {
         int rs = 0;
 #pragma unroll

@@ -261,6 +261,23 @@ def test_gemm_threshold_fused(M, K, N, w, wf, a, af, obits):
     assert_equal(got, oracle.threshold_pack(C, thr, obits), "fused gemm+threshold")
 
 
+def test_fused_int8_planes_676_small_tiles_odd_period_count():
+    """W3A3 1620 x 2831 x 1657 with 4-bit outputs: 676 tiles of 64 x 64 on the int8 matrix-core kernel, an odd number of
+    periods, so that the loader's last two-period request is never read back; the per-row terms of the epilogue take
+    the place of the stashed plane words and must not be written before that request has landed (a run once produced
+    all-ones words in 96 columns of one tile row)."""
+    rng = np.random.default_rng(420)
+    M, K, N, obits = 1620, 2831, 1657, 4
+    W, A = draw(rng, (M, K), 3, TC), draw(rng, (K, N), 3, U)
+    C = oracle.gemm(W, A)
+    thr = make_thr(rng, C, obits)
+    Wp = bs.bs_pack_planes(dev(W), 3, FMT[TC])
+    Ap = bs.bs_pack_planes(dev(A), 3, FMT[U], depth_is_strided=True)
+    want = oracle.threshold_pack(C, thr, obits)
+    for _ in range(3):
+        assert_equal(gemm_threshold_all_engines(Wp, FMT[TC], Ap, FMT[U], K, dev(thr), obits), want, "fused W3A3 1620x2831x1657")
+
+
 # Long, thin outputs: the matrix-core kernels on packed planes map their workgroups to tiles in one of three orders
 # (plain; runs of consecutive tiles per XCD, by rows or by columns of the tile grid), chosen on the host from the grid
 # and the operands' planes.  These shapes reach the two run orders with every tile size, ragged edges, a tile count
