@@ -355,12 +355,12 @@ bs_status bs_streamline_thresholds(const double *t, int T, const double *a, cons
  *               f = the part of the chip's tile slots that is filled (256, 512, 1024 slots for the three tiles), h = 1/2
  *               (1/4 for the 64 x 64 tile): beyond it workgroups share a compute unit; c5 applies to max(0, f - h):
  *                                    F      c1     c2      c3      c4      c5     E
- *                 int8,  64 x 64     4.87   0.623  0.0377       0  0.0177  0.387  0.319
- *                 int8, 128 x 128    6.17   0.783  0.0609  0.2404  0.0062  0.351  0.303
- *                 int8, 256 x 256   11.63   1.232  0.1467       0  0.0617      0  0.198
- *                 fp4,   64 x 64     4.69   0.505  0.0417       0  0.0411  0.297  0.205
- *                 fp4,  128 x 128    5.57   0.615  0.0789  0.0182  0.0557  0.510  0.283
- *                 fp4,  256 x 256   10.11   0.947  0.1680       0  0.1317      0  0.133
+ *                 int8,  64 x 64     4.63   0.632  0.0351       0  0.0202  0.373  0.318
+ *                 int8, 128 x 128    5.79   0.783  0.0602  0.2501  0.0080  0.284  0.296
+ *                 int8, 256 x 256   10.08   1.260  0.1380       0  0.0678      0  0.183
+ *                 fp4,   64 x 64     4.45   0.511  0.0389       0  0.0461  0.288  0.204
+ *                 fp4,  128 x 128    5.24   0.682  0.0648  0.1107       0  0.387  0.248
+ *                 fp4,  256 x 256    8.82   1.034  0.1443  0.0806  0.0428      0  0.119
  * N <= 4 is always bit-serial (weights are read once, wbits/8 byte per weight, and nothing is expanded).
  * Invalid arguments (bits outside 1..4, bipolar with bits != 1, non-positive sizes) return BS_ENGINE_BITSERIAL.
  */

@@ -48,7 +48,7 @@ def test_fixture_covers_the_fitted_range():
 
 def test_choice_is_close_to_the_fastest_engine_on_the_recorded_shapes():
     regret = np.array([chosen_time(*r) / min(r[5].values()) - 1.0 for r in load()])
-    # as fitted: 0.04 % on average, 16 % at worst (one shape); the bounds leave room for a refit, not for a wrong boundary
+    # as fitted: 0.07 % on average, 14 % at worst (one shape); the bounds leave room for a refit, not for a wrong boundary
     assert regret.mean() < 0.01, regret.mean()
     assert regret.max() < 0.20, regret.max()
     assert (regret > 0.10).sum() <= 8, (regret > 0.10).sum()
