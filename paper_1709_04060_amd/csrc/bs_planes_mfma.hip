@@ -394,7 +394,7 @@ planes_mfma_kernel(const PlanesParams p)
         }
     };
     constexpr std::integral_constant<int, 0> kNoValu{};
-    constexpr std::integral_constant<int, (FP4 ? 60 : 84) / (WTM * WTN) + 1> kExpandValu{};
+    constexpr std::integral_constant<int, (FP4 ? 60 : 100) / (WTM * WTN) + 1> kExpandValu{};
 
     // One period = two stages = four depth steps ("quarters").  PP: parity of the period; its stages sit in LDS
     // buffers 2 PP and 2 PP + 1, the next period's stages are written into the other two.  The fragments of a quarter

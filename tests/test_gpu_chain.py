@@ -111,12 +111,14 @@ def test_alexnet_inner_chain(scale):
 
 @pytest.mark.parametrize("B,H,W,C,F,k,s,p", [(3, 9, 9, 32, 70, 3, 1, 1), (5, 13, 13, 40, 33, 3, 2, 0), (2, 27, 27, 96, 256, 5, 1, 2),
                                              (40, 8, 7, 130, 64, 1, 1, 0), (64, 13, 13, 64, 96, 3, 1, 1),
-                                             (64, 13, 13, 32, 384, 3, 1, 1), (70, 13, 13, 40, 300, 3, 1, 1)])
+                                             (64, 13, 13, 32, 384, 3, 1, 1), (70, 13, 13, 40, 300, 3, 1, 1),
+                                             (64, 27, 27, 96, 256, 5, 1, 2), (66, 27, 27, 128, 250, 3, 1, 1)])
 @pytest.mark.parametrize("w,wf,a,af,obits", [(1, BP, 2, U, 2), (2, TC, 2, U, 2), (4, TC, 3, TC, 4)])
 def test_conv_and_pool_on_a_batch(B, H, W, C, F, k, s, p, w, wf, a, af, obits):
     """B images side by side in the column dimension: every image's output equals the oracle's direct convolution of
     that image, and pooling the batch equals pooling each map.  (64, 13, 13) gives enough columns for 64 x 64 tiles; with 384 or 300 filters the matrix-core kernels take
-    128 x 128 tiles in column-major runs per XCD."""
+    128 x 128 tiles in column-major runs per XCD; the two (27, 27) cases take 256 x 256 tiles, with the word-wise (96
+    channels) and the 16-byte (128 channels) gather."""
     rng = np.random.default_rng(B * 1000 + H * W + C + F + w + a)
     x = draw(rng, (B, H, W, C), a, af)
     filt = draw(rng, (F, k, k, C), w, wf)
