@@ -196,3 +196,24 @@ def test_random_large_shapes(seed):
         out.fill_(-1)
         bs.bs_gemm_fp4_threshold(W4, A4, K, dev(thr), obits, out=out)
         assert_equal(planes_to_numpy(out), want, "bs_gemm_fp4_threshold " + what)
+
+
+@pytest.mark.parametrize("seed", range(500, 650))
+def test_random_middle_shapes_on_every_engine(seed):
+    """Up to 1700 rows and columns at any depth up to 3000: the matrix-core kernels' 64 x 64 and 128 x 128 tiles with
+    up to several hundred workgroups, even and odd numbers of pipeline periods, every precision and format, the int32
+    product and the fused thresholds on every engine."""
+    rng = np.random.default_rng([20240613, seed])
+    (w, wf), (a, af) = draw_operand(rng), draw_operand(rng)
+    M, N = int(rng.integers(1, 1700)), int(rng.integers(5, 1700))
+    K = int(rng.choice([64, 127, 128, 129, 255, 256, 257, 1024, 2304])) if rng.random() < 0.5 else int(rng.integers(1, 3000))
+    obits = int(rng.integers(1, 5))
+    W, A = draw(rng, (M, K), w, wf), draw(rng, (K, N), a, af)
+    C = oracle.gemm(W, A)
+    thr = np.sort(rng.integers(int(C.min()) - 2, int(C.max()) + 3, size=(M, (1 << obits) - 1)), axis=1).astype(np.int32)
+    what = "seed %d W%d(%d)A%d(%d) %dx%dx%d o=%d" % (seed, w, wf, a, af, M, K, N, obits)
+    Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
+    Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
+    assert_equal(gemm_all_engines(Wp, FMT[wf], Ap, FMT[af], K), C, "bs_gemm " + what)
+    assert_equal(gemm_threshold_all_engines(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits), oracle.threshold_pack(C, thr, obits),
+                 "bs_gemm_threshold " + what)
