@@ -39,7 +39,8 @@ dense_gemm_kernel(const DenseParams p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int li = lane & 31, lg = lane >> 5;
-    const int tile_m = blockIdx.x / p.gx, tile_n = blockIdx.x % p.gx;
+    int tile_m, tile_n;
+    tile_of_workgroup(p, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     // ---- loader: thread moves chunk (row, c) of the stacked [W rows; A rows] tile ----
@@ -222,7 +223,8 @@ dense_gemm_lds_kernel(const DenseParams p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
     const int li = lane & 31, lg = lane >> 5;
-    const int tile_m = blockIdx.x / p.gx, tile_n = blockIdx.x % p.gx;
+    int tile_m, tile_n;
+    tile_of_workgroup(p, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     // ---- loader: instruction j of this wavefront covers stacked rows (wave * LPW + j) * 16 .. + 15 ----
@@ -410,6 +412,9 @@ bs_status launch_dense(DenseParams &p, bool fuse, hipStream_t st)
     p.gy = (p.M + BM - 1) / BM;
     const long long blocks = (long long)p.gx * p.gy;
     if (blocks >= (1LL << 31)) return BS_ERR_UNSUPPORTED;
+    // panels: a tile's rows x the depth in bytes; an XCD's 32 compute units hold one workgroup of eight wavefronts
+    // (or of four of 64 x 64) each, two of the others
+    plan_tile_order(p, (long long)BM * p.K, (long long)BN * p.K, (NT == 512 || (WTM == 4 && WTN == 4)) ? 32 : 64);
     // four wavefronts of 128 x 128 exist in the register-staged kernel only (the direct-to-LDS kernel runs that tile on eight)
     constexpr bool DIRECT = !(WTM == 4 && WTN == 4);
     if (p.K % 16 == 0) {  // whole 16-byte chunks: operands can go straight from memory to LDS

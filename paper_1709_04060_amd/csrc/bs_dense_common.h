@@ -3,7 +3,9 @@
 // parameter block of the epilogue, and the epilogue itself (int32 store, or successive thresholding of
 // Sec. 2.1.1 with the packed-plane output).
 #pragma once
+#include <algorithm>
 #include <type_traits>
+#include <vector>
 
 #include "bs_common.h"
 
@@ -54,7 +56,57 @@ struct DenseParams {
     uint32_t *Y;
     int Yd;
     int gx, gy;        // tiles along N and M
+    // tile order (plan_tile_order): 0 = workgroup i takes tile i of the row-major order; 1, 2 = the workgroups of an
+    // XCD (workgroup index mod 8) take a run of consecutive tiles, xcd_base (+ 1 for the first xcd_rem XCDs) of them,
+    // in row-major (1) or column-major (2) order of the tile grid
+    int order, xcd_base, xcd_rem;
 };
+
+// Tile of the calling workgroup under the order chosen on the host.
+__device__ __forceinline__ void tile_of_workgroup(const DenseParams &p, int &tile_m, int &tile_n)
+{
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int lin = p.order == 0 ? (int)blockIdx.x : xcd * p.xcd_base + (xcd < p.xcd_rem ? xcd : p.xcd_rem) + local;
+    if (p.order == 2) { tile_n = lin / p.gy; tile_m = lin - tile_n * p.gy; }
+    else { tile_m = lin / p.gx; tile_n = lin - tile_m * p.gx; }
+}
+
+// Which tiles the workgroups of one XCD take.  Workgroups are dealt round-robin to the 8 XCDs, each with its own 4 MiB
+// L2, so workgroup i of the plain order lands on XCD i mod 8: with a tile grid whose width is a multiple of 8 an XCD
+// then owns a few tile columns and walks down all tile rows (good: its activation panels stay in L2), but with an odd
+// width, or few tile rows or columns, every XCD touches nearly every panel of the larger operand (384 x 10816 in 64 x 64
+// tiles: 127 of the 169 column panels per XCD, where a run of consecutive tiles in column-major order needs 22).  The
+// three orders are compared by walking XCD 0's tiles in launch order, `resident` at a time (what the XCD's compute
+// units hold): every panel (a tile's rows of one operand over the whole depth) that was not touched by the previous
+// group costs its bytes; if a group's panels exceed the L2, nothing is kept.  Ties keep the plain order.
+// w_panel, a_panel: bytes of a tile's weight rows and of its activation rows.
+inline void plan_tile_order(DenseParams &p, long long w_panel, long long a_panel, int resident)
+{
+    const long long blocks = (long long)p.gx * p.gy;
+    p.order = 0; p.xcd_base = (int)(blocks / 8); p.xcd_rem = (int)(blocks % 8);
+    if (blocks < 16 || blocks > 8192) return;  // small grids have nothing to order; the walk below stays a few microseconds of host time
+    const int gx = p.gx, gy = p.gy, n0 = (int)((blocks + 7) / 8);
+    long long best = -1;
+    std::vector<int> seen_row(gy), seen_col(gx);
+    for (int order = 0; order < 3; ++order) {
+        std::fill(seen_row.begin(), seen_row.end(), -2);
+        std::fill(seen_col.begin(), seen_col.end(), -2);
+        long long cost = 0;
+        for (int g0 = 0, g = 0; g0 < n0; g0 += resident, ++g) {
+            const int g1 = std::min(n0, g0 + resident);
+            long long fresh = 0, all = 0;
+            for (int local = g0; local < g1; ++local) {
+                const long long lin = order == 0 ? 8LL * local : local;
+                if (lin >= blocks) break;
+                const int tm = order == 2 ? (int)(lin % gy) : (int)(lin / gx), tn = order == 2 ? (int)(lin / gy) : (int)(lin % gx);
+                if (seen_row[tm] != g) { all += w_panel; if (seen_row[tm] != g - 1) fresh += w_panel; seen_row[tm] = g; }
+                if (seen_col[tn] != g) { all += a_panel; if (seen_col[tn] != g - 1) fresh += a_panel; seen_col[tn] = g; }
+            }
+            cost += all <= (3LL << 20) ? fresh : all;
+        }
+        if (best < 0 || cost < best) { best = cost; p.order = order; }
+    }
+}
 
 // zero the bytes of a 16-byte chunk that lie at or beyond depth index K
 __device__ __forceinline__ uint4 mask_tail(uint4 v, int k, int K)

@@ -36,8 +36,6 @@
 // Plane words are requested a period ahead, 16 bytes per row and plane: every lane of such a request touches
 // another cache line, and those look-ups bound the loader (with all lanes on one row the W4A4 8192^3 product took
 // 555 instead of 1105 us), hence as few and as wide requests as the registers allow.
-#include <algorithm>
-#include <vector>
 #include "bs_dense_common.h"
 #include "bs_gemm_kernel.h"
 
@@ -67,10 +65,6 @@ struct PlanesParams {
     float acc_scale;
     // implicit lowering (CONV kernels): Ap points at packed HWC image planes; see PlanesGemm
     int cH, cW, cCd, cPix, cKW, cStride, cPad, cOW, cOHW, cB, cKused;
-    // tile order (plan_order): 0 = workgroup i takes tile i of the row-major order; 1, 2 = the workgroups of an XCD
-    // (workgroup index mod 8) take a run of consecutive tiles, xcd_base (+ 1 for the first xcd_rem XCDs) of them, in
-    // row-major (1) or column-major (2) order of the tile grid
-    int order, xcd_base, xcd_rem;
 };
 
 // (a & m) | (b & ~m): one v_bfi_b32
@@ -162,12 +156,7 @@ planes_mfma_kernel(const PlanesParams p)
     const int wm = wave / WGN, wn = wave % WGN;
     const int li = lane & 31, lg = lane >> 5;
     int tile_m, tile_n;
-    {
-        const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-        const int lin = p.order == 0 ? (int)blockIdx.x : xcd * p.xcd_base + (xcd < p.xcd_rem ? xcd : p.xcd_rem) + local;
-        if (p.order == 2) { tile_n = lin / p.d.gy; tile_m = lin - tile_n * p.d.gy; }
-        else { tile_m = lin / p.d.gx; tile_n = lin - tile_m * p.d.gx; }
-    }
+    tile_of_workgroup(p.d, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     // ---- this thread's row: operand, the plane each code-bit slot takes, masks ----
@@ -484,43 +473,6 @@ OperandCoding coding_of(int bits, bs_format fmt, bool fp4)
     return c;
 }
 
-// Which tiles the workgroups of one XCD take.  Workgroups are dealt round-robin to the 8 XCDs, each with its own 4 MiB
-// L2, so workgroup i of the plain order lands on XCD i mod 8: with a tile grid whose width is a multiple of 8 an XCD
-// then owns a few tile columns and walks down all tile rows (good: its activation panels stay in L2), but with an odd
-// width, or few tile rows or columns, every XCD touches nearly every panel of the larger operand (384 x 10816 in 64 x 64
-// tiles: 127 of the 169 column panels per XCD, where a run of consecutive tiles in column-major order needs 22).  The
-// three orders are compared by walking XCD 0's tiles in launch order, `resident` at a time (what the XCD's compute
-// units hold): every panel (a tile's rows of all planes of one operand) that was not touched by the previous group
-// costs its planes; if a group's panels exceed the L2, nothing is kept.  Ties keep the plain order.
-void plan_order(PlanesParams &p, int tile, int resident)
-{
-    const long long blocks = (long long)p.d.gx * p.d.gy;
-    p.order = 0; p.xcd_base = (int)(blocks / 8); p.xcd_rem = (int)(blocks % 8);
-    if (blocks < 16 || blocks > 8192) return;  // small grids have nothing to order; the walk below stays a few microseconds of host time
-    const int gx = p.d.gx, gy = p.d.gy, n0 = (int)((blocks + 7) / 8);
-    const long long panel = (long long)tile * p.Kd * 4;   // bytes of a panel's plane
-    long long best = -1;
-    std::vector<int> seen_row(gy), seen_col(gx);
-    for (int order = 0; order < 3; ++order) {
-        std::fill(seen_row.begin(), seen_row.end(), -2);
-        std::fill(seen_col.begin(), seen_col.end(), -2);
-        long long cost = 0;
-        for (int g0 = 0, g = 0; g0 < n0; g0 += resident, ++g) {
-            const int g1 = std::min(n0, g0 + resident);
-            long long fresh = 0, all = 0;
-            for (int local = g0; local < g1; ++local) {
-                const long long lin = order == 0 ? 8LL * local : local;
-                if (lin >= blocks) break;
-                const int tm = order == 2 ? (int)(lin % gy) : (int)(lin / gx), tn = order == 2 ? (int)(lin / gy) : (int)(lin % gx);
-                if (seen_row[tm] != g) { all += p.cw.bits; if (seen_row[tm] != g - 1) fresh += p.cw.bits; seen_row[tm] = g; }
-                if (seen_col[tn] != g) { all += p.ca.bits; if (seen_col[tn] != g - 1) fresh += p.ca.bits; seen_col[tn] = g; }
-            }
-            cost += all * panel <= (3LL << 20) ? fresh : all;
-        }
-        if (best < 0 || cost < best) { best = cost; p.order = order; }
-    }
-}
-
 template <bool FP4, int WTM, int WTN, int WGM, int WGN>
 bs_status launch_tile(PlanesParams &p, bool fuse, bool conv, hipStream_t st)
 {
@@ -529,7 +481,8 @@ bs_status launch_tile(PlanesParams &p, bool fuse, bool conv, hipStream_t st)
     p.d.gy = (p.d.M + BM - 1) / BM;
     const long long blocks = (long long)p.d.gx * p.d.gy;
     if (blocks >= (1LL << 31)) return BS_ERR_UNSUPPORTED;
-    plan_order(p, BM, (int)(NT == 512 ? 32 : NT == 256 ? 64 : 128));
+    // panels: a tile's rows x the packed depth x the operand's planes; an XCD holds 32, 64 or 128 workgroups of the three tiles
+    plan_tile_order(p.d, (long long)BM * p.Kd * 4 * p.cw.bits, (long long)BN * p.Kd * 4 * p.ca.bits, (int)(NT == 512 ? 32 : NT == 256 ? 64 : 128));
     if (conv) {  // implicit lowering exists with the thresholding epilogue only
         if (!fuse) return BS_ERR_UNSUPPORTED;
         if (p.cCd % 4 == 0 && p.cPix % 4 == 0) planes_mfma_kernel<FP4, WTM, WTN, WGM, WGN, true, true, true><<<dim3((unsigned)blocks), NT, 0, st>>>(p);

@@ -294,7 +294,15 @@ def test_long_thin_outputs_on_every_engine(M, K, N, w, wf, a, af, obits):
     Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
     assert_equal(gemm_all_engines(Wp, FMT[wf], Ap, FMT[af], K), C, "long thin gemm %dx%dx%d" % (M, K, N))
     got = gemm_threshold_all_engines(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits)
-    assert_equal(got, oracle.threshold_pack(C, thr, obits), "long thin fused gemm+threshold %dx%dx%d" % (M, K, N))
+    want = oracle.threshold_pack(C, thr, obits)
+    assert_equal(got, want, "long thin fused gemm+threshold %dx%dx%d" % (M, K, N))
+    # the kernels on unpacked operands order their tiles the same way
+    W8, A8 = bs.bs_unpack_planes(Wp, FMT[wf], K), bs.bs_unpack_planes(Ap, FMT[af], K)
+    assert_equal(bs.bs_gemm_i8(W8, A8, K).cpu().numpy(), C, "long thin bs_gemm_i8 %dx%dx%d" % (M, K, N))
+    assert_equal(planes_to_numpy(bs.bs_gemm_i8_threshold(W8, A8, K, dev(thr), obits)), want, "long thin bs_gemm_i8_threshold")
+    if w <= 2 and a <= 2:
+        W4, A4 = bs.bs_unpack_planes_fp4(Wp, FMT[wf], K), bs.bs_unpack_planes_fp4(Ap, FMT[af], K)
+        assert_equal(planes_to_numpy(bs.bs_gemm_fp4_threshold(W4, A4, K, dev(thr), obits)), want, "long thin bs_gemm_fp4_threshold")
 
 
 # ------------------------------------------------------------------ S2 lowering
