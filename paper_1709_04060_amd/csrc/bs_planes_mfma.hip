@@ -392,53 +392,97 @@ planes_mfma_kernel(const PlanesParams p)
     // next two stages and has received the last fragments of this period (read in quarter 2), so quarter 3 may read the
     // next period's first fragments and request the plane words of the period after next into R, which the two
     // expansions have just released.  TAIL: one of the stages to expand may be the last one or lie past the depth.
-    auto period = [&](auto pp_c, auto tail_c, int P) {
+    auto request = [&](auto pp_c, int P) {       // plane words of period P + 2 (STASH: of two periods, every other period)
         constexpr int PP = decltype(pp_c)::value;
-        constexpr int B0 = 2 * PP, B1 = 2 * PP + 1, N0 = 2 * (PP ^ 1), N1 = 2 * (PP ^ 1) + 1;
-        load_frags(1, B0, 1);
-        mfmas(0);
-        interleave(kNoValu);
-        __builtin_amdgcn_sched_barrier(0);
-        expand_stage(tail_c, N0, 2 * P + 2, 0);
-        load_frags(0, B1, 0);
-        mfmas(1);
-        interleave(kExpandValu);
-        __builtin_amdgcn_sched_barrier(0);
-        expand_stage(tail_c, N1, 2 * P + 3, 1);
-        load_frags(1, B1, 1);
-        mfmas(0);
-        interleave(kExpandValu);
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
         if constexpr (!STASH) fetch(P + 2);
         else if constexpr (PP == 0) fetch_pair(P + 2);
         else unstash();
-        load_frags(0, N0, 0);
-        mfmas(1);
-        interleave(kNoValu);
-        __builtin_amdgcn_sched_barrier(0);
+    };
+    // LATE = false: the schedule described above.  LATE = true (the second four of eight wavefronts, which share
+    // their SIMDs with the first four): the same period with the vector work moved by half a period.  The second
+    // stage of the next period is expanded in quarter 0, the words of the period after next are requested in quarter
+    // 1, and its first stage is expanded in quarter 3, behind the barrier, into this period's first buffer (nobody
+    // reads that one after quarter 0).  The two wavefronts of a SIMD then alternate between a quarter of matrix
+    // instructions only and a quarter with the expansion between them, instead of both expanding at the same time:
+    // a SIMD does not issue vector and matrix instructions of one wavefront together, but it does overlap one
+    // wavefront's matrix instruction with the other's vector instructions.
+    auto period = [&](auto pp_c, auto tail_c, auto late_c, int P) __attribute__((always_inline)) {
+        constexpr int PP = decltype(pp_c)::value;
+        constexpr bool LATE = decltype(late_c)::value;
+        constexpr int B0 = 2 * PP, B1 = 2 * PP + 1, N0 = 2 * (PP ^ 1), N1 = 2 * (PP ^ 1) + 1;
+        if constexpr (!LATE) {
+            load_frags(1, B0, 1);
+            mfmas(0);
+            interleave(kNoValu);
+            __builtin_amdgcn_sched_barrier(0);
+            expand_stage(tail_c, N0, 2 * P + 2, 0);
+            load_frags(0, B1, 0);
+            mfmas(1);
+            interleave(kExpandValu);
+            __builtin_amdgcn_sched_barrier(0);
+            expand_stage(tail_c, N1, 2 * P + 3, 1);
+            load_frags(1, B1, 1);
+            mfmas(0);
+            interleave(kExpandValu);
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            request(pp_c, P);
+            load_frags(0, N0, 0);
+            mfmas(1);
+            interleave(kNoValu);
+            __builtin_amdgcn_sched_barrier(0);
+        } else {
+            expand_stage(tail_c, N1, 2 * P + 3, 1);
+            load_frags(1, B0, 1);
+            mfmas(0);
+            interleave(kExpandValu);
+            __builtin_amdgcn_sched_barrier(0);
+            request(pp_c, P);
+            load_frags(0, B1, 0);
+            mfmas(1);
+            interleave(kNoValu);
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(1, B1, 1);
+            mfmas(0);
+            interleave(kNoValu);
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            expand_stage(tail_c, B0, 2 * P + 4, 0);
+            load_frags(0, N0, 0);
+            mfmas(1);
+            interleave(kExpandValu);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
 
-    // prologue: the first period expanded, the second requested
-    fetch(0);
-    expand_stage(std::true_type{}, 0, 0, 0);
-    expand_stage(std::true_type{}, 1, 1, 1);
-    fetch(1);
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    load_frags(0, 0, 0);
-    int P = 0;
-    for (; 2 * P + 7 <= p.nst; P += 2) {          // the stages expanded here (up to 2 P + 5) lie wholly inside the depth
-        period(I0{}, std::false_type{}, P);
-        period(I1{}, std::false_type{}, P + 1);
-    }
-    for (; P + 1 < p.nper; P += 2) {
-        period(I0{}, std::true_type{}, P);
-        period(I1{}, std::true_type{}, P + 1);
-    }
-    if (P < p.nper) period(I0{}, std::true_type{}, P);
+    auto run = [&](auto late_c) __attribute__((always_inline)) {
+        constexpr bool LATE = decltype(late_c)::value;
+        // prologue: the first period expanded, the second requested (LATE: and its first stage expanded)
+        fetch(0);
+        expand_stage(std::true_type{}, 0, 0, 0);
+        expand_stage(std::true_type{}, 1, 1, 1);
+        fetch(1);
+        if constexpr (LATE) expand_stage(std::true_type{}, 2, 2, 0);
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        load_frags(0, 0, 0);
+        int P = 0;
+        for (; 2 * P + 8 <= p.nst; P += 2) {      // the stages expanded here (up to 2 P + 6) lie wholly inside the depth
+            period(I0{}, std::false_type{}, late_c, P);
+            period(I1{}, std::false_type{}, late_c, P + 1);
+        }
+        for (; P + 1 < p.nper; P += 2) {
+            period(I0{}, std::true_type{}, late_c, P);
+            period(I1{}, std::true_type{}, late_c, P + 1);
+        }
+        if (P < p.nper) period(I0{}, std::true_type{}, late_c, P);
+    };
+    // every wavefront passes the same number of barriers on either path
+    if (NT == 512 && wave >= 4) run(std::true_type{});
+    else run(std::false_type{});
 
     // ---- per-row terms of the affine correction: slot q carries weight 2^(q - shift) of the unsigned code ----
     // They go where the stashed plane words were.  The last periods still request words past the depth (clamped
