@@ -64,12 +64,12 @@ double t_planes(double M, double N, double K, int wbits, int abits, bool fp4)
     const double alone = tile == 64 ? 0.25 : 0.5;  // up to here every workgroup has a compute unit to itself
     const double shared = fill > alone ? fill - alone : 0.0;
     // fixed; per period: 1, P, fill, P fill, shared; epilogue per abits M N / 1e6
-    static const double c[2][3][7] = {{{4.63, 0.632, 0.0351, 0.0000, 0.0202, 0.373, 0.318},    // int8, 64 x 64
-                                       {5.79, 0.783, 0.0602, 0.2501, 0.0080, 0.284, 0.296},    // int8, 128 x 128
-                                       {10.08, 1.260, 0.1380, 0.0000, 0.0678, 0.000, 0.183}},  // int8, 256 x 256
-                                      {{4.45, 0.511, 0.0389, 0.0000, 0.0461, 0.288, 0.204},    // fp4, 64 x 64
-                                       {5.24, 0.682, 0.0648, 0.1107, 0.0000, 0.387, 0.248},    // fp4, 128 x 128
-                                       {8.82, 1.034, 0.1443, 0.0806, 0.0428, 0.000, 0.119}}}; // fp4, 256 x 256
+    static const double c[2][3][7] = {{{4.76, 0.628, 0.0343, 0.0000, 0.0216, 0.387, 0.315},    // int8, 64 x 64
+                                       {5.82, 0.777, 0.0598, 0.2312, 0.0102, 0.287, 0.300},    // int8, 128 x 128
+                                       {11.45, 1.053, 0.1341, 0.0000, 0.0738, 0.000, 0.191}},  // int8, 256 x 256
+                                      {{4.47, 0.518, 0.0344, 0.0000, 0.0454, 0.289, 0.215},    // fp4, 64 x 64
+                                       {5.29, 0.678, 0.0630, 0.1388, 0.0000, 0.372, 0.250},    // fp4, 128 x 128
+                                       {9.36, 0.850, 0.1459, 0.0000, 0.0821, 0.000, 0.120}}}; // fp4, 256 x 256
     const double *q = c[fp4 ? 1 : 0][tile == 256 ? 2 : (tile == 128 ? 1 : 0)];
     const double per = q[1] + q[2] * P + fill * (q[3] + q[4] * P) + shared * q[5];
     return q[0] + nper * (double)rounds * per + q[6] * abits * M * N / 1e6;
