@@ -31,7 +31,8 @@
 // masked with "index < K".
 //
 // Pipeline.  A thread owns one row of the stacked [W rows; A rows] tile.  Four LDS stage buffers of 64-byte rows
-// (XOR-swizzled 16-byte chunks, the layout of the direct-to-LDS dense kernel): a period of two stages is multiplied
+// (16-byte chunks XOR-swizzled with (row / 2) % 4, which keeps both this kernel's row-wise writes and the fragment reads
+// apart in the banks; the direct-to-LDS dense kernel, which has no such writes, takes (row / 4) % 4): a period of two stages is multiplied
 // from two of them while the next period's stages are expanded into the other two, with one barrier per period.
 // Plane words are requested a period ahead, 16 bytes per row and plane: every lane of such a request touches
 // another cache line, and those look-ups bound the loader (with all lanes on one row the W4A4 8192^3 product took
