@@ -31,8 +31,8 @@
 // masked with "index < K".
 //
 // Pipeline.  A thread owns one row of the stacked [W rows; A rows] tile.  Four LDS stage buffers of 64-byte rows
-// (16-byte chunks XOR-swizzled with (row / 2) % 4, which keeps both this kernel's row-wise writes and the fragment reads
-// apart in the banks; the direct-to-LDS dense kernel, which has no such writes, takes (row / 4) % 4): a period of two stages is multiplied
+// (16-byte chunks XOR-swizzled with (row / 4) % 4, the layout of the direct-to-LDS dense kernel, which keeps the fragment
+// reads apart in the banks; the threads own the rows in an order that does the same for their row-wise writes): a period of two stages is multiplied
 // from two of them while the next period's stages are expanded into the other two, with one barrier per period.
 // Plane words are requested a period ahead, 16 bytes per row and plane: every lane of such a request touches
 // another cache line, and those look-ups bound the loader (with all lanes on one row the W4A4 8192^3 product took
@@ -162,9 +162,13 @@ planes_mfma_kernel(const PlanesParams p)
 
     // ---- this thread's row: operand, the plane each code-bit slot takes, masks ----
     const bool isW = tid < BM;
+    // Row of the stacked tile this thread owns: within 16 rows, thread bits b3 b2 b1 b0 -> row bits b2 b1 b3 b0, so that
+    // the eight lanes an LDS write serves at a time own rows r, r + 1, r + 4, r + 5, r + 8, ...: with the chunk swizzle
+    // (row / 4) % 4, which keeps the fragment reads free of bank conflicts, these land in eight different bank groups.
+    const int own = (tid & ~15) | ((tid & 6) << 1) | ((tid & 8) >> 2) | (tid & 1);
     const OperandCoding cd = isW ? p.cw : p.ca;
     const int rows = isW ? p.d.M : p.d.N;
-    int row = isW ? m0 + tid : n0 + (tid - BM);
+    int row = isW ? m0 + own : n0 + (own - BM);
     if (row >= rows) row = rows - 1;             // clamped: its products land in outputs that are never stored
     // CONV, A rows: the row is output pixel (b, oh, ow); pix_h, pix_w = top-left input pixel of its window
     int pix_h = 0, pix_w = 0;
@@ -203,8 +207,8 @@ planes_mfma_kernel(const PlanesParams p)
     int popc[NB];                                // popcounts of this row's slots over the depth (for the row-sum terms)
 #pragma unroll
     for (int q = 0; q < NB; ++q) popc[q] = 0;
-    unsigned char *const my_row = lds + tid * DK;
-    const int wsw = (tid >> 1) & 3;              // chunk swizzle of this row
+    unsigned char *const my_row = lds + own * DK;
+    const int wsw = (own >> 2) & 3;              // chunk swizzle of this row
 
     // Plane words of one period (two stages) of this row: one request per slot and period where 16 bytes hold both
     // stages (int8 kind), two where they hold one (fp4 kind).  Every lane of a request reads another row, i.e. another
@@ -355,8 +359,8 @@ planes_mfma_kernel(const PlanesParams p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
 
-    // fragment addresses: row r of the tile, logical chunk c at r * 64 + 16 * (c ^ ((r / 2) % 4))
-    const int fsw = (li >> 1) & 3;
+    // fragment addresses: row r of the tile, logical chunk c at r * 64 + 16 * (c ^ ((r / 4) % 4))
+    const int fsw = (li >> 2) & 3;
     const int rowW = (wm * 32 * WTM + li) * DK, rowA = (BM + wn * 32 * WTN + li) * DK;
     v4i fa[2][WTM], fb[2][WTN];
     auto load_frags = [&](int set, int buf, int sub) {
@@ -494,7 +498,7 @@ planes_mfma_kernel(const PlanesParams p)
         int rs = 0;
 #pragma unroll
         for (int q = 0; q < NB; ++q) rs = wrap_add(rs, (q - cd.shift >= 0) ? (popc[q] << (q - cd.shift)) : 0);
-        terms[tid] = isW ? wrap_add(wrap_mul(p.row_coef, rs), p.row_const) : wrap_mul(p.col_coef, rs);
+        terms[own] = isW ? wrap_add(wrap_mul(p.row_coef, rs), p.row_const) : wrap_mul(p.col_coef, rs);
     }
     __syncthreads();
     PlanesResult result{p.mul, p.acc_scale, terms, terms + BM};
