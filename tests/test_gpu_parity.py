@@ -278,6 +278,24 @@ def test_fused_int8_planes_676_small_tiles_odd_period_count():
         assert_equal(gemm_threshold_all_engines(Wp, FMT[TC], Ap, FMT[U], K, dev(thr), obits), want, "fused W3A3 1620x2831x1657")
 
 
+@pytest.mark.parametrize("K", [1, 64, 129, 257, 385, 513, 641])
+@pytest.mark.parametrize("w,wf,a,af,obits", [(2, TC, 2, U, 2), (4, TC, 4, U, 4), (1, BP, 1, BP, 1)])
+def test_large_tiles_short_depths(K, w, wf, a, af, obits):
+    """2500 x 5000 outputs take the matrix-core kernels' 256 x 256 tiles, whose two groups of wavefronts run the period
+    with different schedules (one expands a stage ahead of the other): one to five stages, whole and partial, so that
+    prologue, tail and the stages past the depth of either schedule are what is exercised."""
+    rng = np.random.default_rng(7000 + K + w)
+    M, N = 2500, 5000
+    W, A = draw(rng, (M, K), w, wf), draw(rng, (K, N), a, af)
+    C = oracle.gemm(W, A)
+    thr = make_thr(rng, C, obits)
+    Wp = bs.bs_pack_planes(dev(W), w, FMT[wf])
+    Ap = bs.bs_pack_planes(dev(A), a, FMT[af], depth_is_strided=True)
+    assert_equal(gemm_all_engines(Wp, FMT[wf], Ap, FMT[af], K), C, "gemm 2500x%dx5000" % K)
+    assert_equal(gemm_threshold_all_engines(Wp, FMT[wf], Ap, FMT[af], K, dev(thr), obits), oracle.threshold_pack(C, thr, obits),
+                 "fused gemm+threshold 2500x%dx5000" % K)
+
+
 # Long, thin outputs: the matrix-core kernels on packed planes map their workgroups to tiles in one of three orders
 # (plain; runs of consecutive tiles per XCD, by rows or by columns of the tile grid), chosen on the host from the grid
 # and the operands' planes.  These shapes reach the two run orders with every tile size, ragged edges, a tile count
