@@ -430,9 +430,16 @@ planes_mfma_kernel(const PlanesParams p)
             mfmas(0);
             interleave(kExpandValu);
             __builtin_amdgcn_sched_barrier(0);
+            // the smaller tiles request the next words before the barrier, as soon as the registers are free (4 to 5 %
+            // faster: the wait at the barrier is time the requests are on their way); the 256 x 256 tile behind it (3 to 5 %
+            // slower the other way round)
+            if constexpr (NT < 512) {
+                request(pp_c, P);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
-            request(pp_c, P);
+            if constexpr (NT == 512) request(pp_c, P);
             load_frags(0, N0, 0);
             mfmas(1);
             interleave(kNoValu);
