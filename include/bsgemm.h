@@ -355,12 +355,12 @@ bs_status bs_streamline_thresholds(const double *t, int T, const double *a, cons
  *               f = the part of the chip's tile slots that is filled (256, 512, 1024 slots for the three tiles), h = 1/2
  *               (1/4 for the 64 x 64 tile): beyond it workgroups share a compute unit; c5 applies to max(0, f - h):
  *                                    F      c1     c2      c3      c4      c5     E
- *                 int8,  64 x 64     4.76   0.628  0.0343       0  0.0216  0.387  0.315
- *                 int8, 128 x 128    5.82   0.777  0.0598  0.2312  0.0102  0.287  0.300
- *                 int8, 256 x 256   11.45   1.053  0.1341       0  0.0738      0  0.191
- *                 fp4,   64 x 64     4.47   0.518  0.0344       0  0.0454  0.289  0.215
- *                 fp4,  128 x 128    5.29   0.678  0.0630  0.1388       0  0.372  0.250
- *                 fp4,  256 x 256    9.36   0.850  0.1459       0  0.0821      0  0.120
+ *                 int8,  64 x 64     4.64   0.613  0.0324       0  0.0248  0.335  0.316
+ *                 int8, 128 x 128    5.69   0.753  0.0581  0.0339  0.0303  0.285  0.305
+ *                 int8, 256 x 256   11.42   1.054  0.1341       0  0.0738      0  0.191
+ *                 fp4,   64 x 64     4.48   0.499  0.0328       0  0.0404  0.320  0.207
+ *                 fp4,  128 x 128    5.38   0.602  0.0500  0.0448  0.0321  0.516  0.247
+ *                 fp4,  256 x 256    9.29   0.854  0.1456       0  0.0862      0  0.120
  * N <= 4 is always bit-serial (weights are read once, wbits/8 byte per weight, and nothing is expanded).
  * Invalid arguments (bits outside 1..4, bipolar with bits != 1, non-positive sizes) return BS_ENGINE_BITSERIAL.
  */

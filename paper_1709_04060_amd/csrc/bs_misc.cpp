@@ -64,12 +64,12 @@ double t_planes(double M, double N, double K, int wbits, int abits, bool fp4)
     const double alone = tile == 64 ? 0.25 : 0.5;  // up to here every workgroup has a compute unit to itself
     const double shared = fill > alone ? fill - alone : 0.0;
     // fixed; per period: 1, P, fill, P fill, shared; epilogue per abits M N / 1e6
-    static const double c[2][3][7] = {{{4.76, 0.628, 0.0343, 0.0000, 0.0216, 0.387, 0.315},    // int8, 64 x 64
-                                       {5.82, 0.777, 0.0598, 0.2312, 0.0102, 0.287, 0.300},    // int8, 128 x 128
-                                       {11.45, 1.053, 0.1341, 0.0000, 0.0738, 0.000, 0.191}},  // int8, 256 x 256
-                                      {{4.47, 0.518, 0.0344, 0.0000, 0.0454, 0.289, 0.215},    // fp4, 64 x 64
-                                       {5.29, 0.678, 0.0630, 0.1388, 0.0000, 0.372, 0.250},    // fp4, 128 x 128
-                                       {9.36, 0.850, 0.1459, 0.0000, 0.0821, 0.000, 0.120}}}; // fp4, 256 x 256
+    static const double c[2][3][7] = {{{4.64, 0.613, 0.0324, 0.0000, 0.0248, 0.335, 0.316},    // int8, 64 x 64
+                                       {5.69, 0.753, 0.0581, 0.0339, 0.0303, 0.285, 0.305},    // int8, 128 x 128
+                                       {11.42, 1.054, 0.1341, 0.0000, 0.0738, 0.000, 0.191}},  // int8, 256 x 256
+                                      {{4.48, 0.499, 0.0328, 0.0000, 0.0404, 0.320, 0.207},    // fp4, 64 x 64
+                                       {5.38, 0.602, 0.0500, 0.0448, 0.0321, 0.516, 0.247},    // fp4, 128 x 128
+                                       {9.29, 0.854, 0.1456, 0.0000, 0.0862, 0.000, 0.120}}}; // fp4, 256 x 256
     const double *q = c[fp4 ? 1 : 0][tile == 256 ? 2 : (tile == 128 ? 1 : 0)];
     const double per = q[1] + q[2] * P + fill * (q[3] + q[4] * P) + shared * q[5];
     return q[0] + nper * (double)rounds * per + q[6] * abits * M * N / 1e6;
@@ -77,16 +77,16 @@ double t_planes(double M, double N, double K, int wbits, int abits, bool fp4)
 
 }  // namespace
 
-// Tile of the matrix-core kernel on packed planes for an M x N output.  Up to 256 tiles of 128 x 128: 64 x 64 tiles on
+// Tile of the matrix-core kernel on packed planes for an M x N output.  Up to 192 tiles of 128 x 128: 64 x 64 tiles on
 // two wavefronts, four times as many workgroups (the chip holds 1024 of them at a time, four per compute unit), each
-// expanding half the rows: up to 17 % faster than 128 x 128 tiles up to that size, within 3 % of them where it is not;
-// from 320 tiles of 128 x 128 on it is 20 to 50 % slower.  Beyond: 256 x 256 (one workgroup per compute unit) or
-// 128 x 128 (two); a round of 128 x 128 tiles over the chip (512 of them) takes 0.67 of a round of 256 x 256 tiles (256
-// of them) and covers half as much output.
+// expanding half the rows: 5 to 15 % faster than 128 x 128 tiles there; at 256 tiles of 128 x 128 the two tie for the
+// int8 kind and the larger tile is 10 to 16 % ahead for the fp4 kind on deep products; from 320 on the small tile is 20
+// to 50 % slower.  Beyond: 256 x 256 (one workgroup per compute unit) or 128 x 128 (two); a round of 128 x 128 tiles
+// over the chip (512 of them) takes 0.67 of a round of 256 x 256 tiles (256 of them) and covers half as much output.
 extern "C" int bs_planes_tile(int64_t M, int64_t N, long long *rounds, long long *tiles)
 {
     const long long t256 = ((M + 255) / 256) * ((N + 255) / 256), t128 = ((M + 127) / 128) * ((N + 127) / 128);
-    if (t128 <= 256) {
+    if (t128 <= 192) {
         const long long t64 = ((M + 63) / 64) * ((N + 63) / 64);
         if (rounds) *rounds = (t64 + 1023) / 1024;
         if (tiles) *tiles = t64;

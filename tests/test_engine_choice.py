@@ -48,7 +48,7 @@ def test_fixture_covers_the_fitted_range():
 
 def test_choice_is_close_to_the_fastest_engine_on_the_recorded_shapes():
     regret = np.array([chosen_time(*r) / min(r[5].values()) - 1.0 for r in load()])
-    # as fitted: 0.07 % on average, 14 % at worst (one shape); the bounds leave room for a refit, not for a wrong boundary
+    # as fitted: 0.4 % on average, 15 % at worst; the bounds leave room for a refit, not for a wrong boundary
     assert regret.mean() < 0.01, regret.mean()
     assert regret.max() < 0.20, regret.max()
     assert (regret > 0.10).sum() <= 8, (regret > 0.10).sum()
@@ -77,8 +77,8 @@ def test_tile_rule_picks_the_faster_tile():
     assert (loss > 0.10).mean() < 0.02, (loss > 0.10).mean()
 
 
-@pytest.mark.parametrize("M,N,want", [(4096, 4096, 256), (256, 256, 64), (1024, 1024, 64), (1024, 2048, 64), (2048, 2048, 64),
-                                      (384, 10816, 64), (2048, 2176, 128), (2048, 4096, 128), (3072, 3072, 256), (8192, 8192, 256)])
+@pytest.mark.parametrize("M,N,want", [(4096, 4096, 256), (256, 256, 64), (1024, 1024, 64), (1024, 2048, 64), (1536, 2048, 64),
+                                      (2048, 2048, 128), (384, 10816, 128), (2048, 2176, 128), (2048, 4096, 128), (3072, 3072, 256), (8192, 8192, 256)])
 def test_tile_rule_examples(M, N, want):
     tile, rounds, tiles = bs.bs_planes_tile(M, N)
     assert tile == want
